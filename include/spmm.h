@@ -1,0 +1,155 @@
+/*
+ * spmm.h -- C ABI of the MI355X (gfx950) sparse-times-dense library.
+ *
+ * Computes C = A x B in fp32 where A (M x K) is an unstructured-sparse weight
+ * matrix handed over once in CSR, B (K x N) is a dense row-major activation
+ * matrix and C (M x N) is dense row-major (paper: Section 1, second paragraph
+ * and Section 2, first paragraph, for the operands; Section 3.1, Listing 1,
+ * for the sum that defines every element of C).
+ *
+ * The three-phase shape of the interface is the paper's inspector / executor
+ * split (Section 3.1, Listing 2; Section 3.4 "Data transformer"): the weight
+ * matrix is analysed and re-stored once, the product is then executed many
+ * times against changing activations.
+ *
+ * No HIP or C++ type appears here.  Pointers are tagged HOST or DEVICE.
+ * No call aborts or throws; every failure is a status code.
+ */
+#ifndef SPMM_CDNA4_H
+#define SPMM_CDNA4_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct spmm_plan spmm_plan_t; /* opaque */
+
+typedef enum {
+    SPMM_OK = 0,
+    SPMM_ERR_INVALID_ARG = 1, /* null pointer, negative or oversized dimension, N < 1,
+                                 misaligned device pointer, host-only plan executed */
+    SPMM_ERR_INVALID_CSR = 2, /* row_ptr[0] != 0, decreasing row_ptr, column outside [0, K) */
+    SPMM_ERR_ALLOC = 3,       /* host or device allocation failed */
+    SPMM_ERR_HIP = 4,         /* any other HIP runtime failure (sticky error cleared) */
+    SPMM_ERR_UNSUPPORTED = 5  /* size outside the index range of the kernels */
+} spmm_status_t;
+
+/* Schedule constants and sizes of a plan (all read-only facts). */
+typedef struct {
+    int64_t M, K, nnz;
+    int32_t ufi;           /* rows per panel: height of the register tile (the paper's UFi) */
+    int32_t ufk;           /* enumerated columns in flight per wave (the paper's UFk) */
+    int32_t group_nnz;     /* nonzero budget of one row group (one wave's work item) */
+    int32_t group_panels;  /* most panels a row group may hold */
+    int64_t n_groups;      /* row groups = work items, in launch order */
+    int64_t n_split;       /* row groups that are pieces of a panel too heavy for one group */
+    int64_t n_enum;        /* enumerated columns: B rows a column tile must fetch per execute */
+    int64_t n_chunks;      /* chunks: runs of at most ufk enumerated columns of one pattern */
+    int64_t vals_words;    /* 32-bit words of the schedule-ordered value array (with padding) */
+    int64_t device_bytes;  /* device memory the plan holds (0 for a host-only plan) */
+} spmm_plan_info_t;
+
+/* Optional inspector settings; zero in a field means "let the inspector choose". */
+typedef struct {
+    int32_t group_nnz;     /* override the nonzero budget per row group (>= 32) */
+    int32_t group_panels;  /* override the panel cap per row group (>= 1) */
+    int32_t host_only;     /* nonzero: build the plan in host memory only (no device needed;
+                              such a plan can be described and exported but not executed) */
+    int32_t reserved;
+} spmm_options_t;
+
+/*
+ * Inspector (paper Section 3.2 "Enumeration", Section 3.3 "Data
+ * transformation", Section 3.4 "Data transformer"; here from CSR in O(nnz log)
+ * rather than from dense A).  Validates the CSR, orders the columns of every
+ * row, enumerates nnz-balanced row groups, merges the columns of each panel of
+ * `ufi` rows into enumerated columns tagged with their nonzero pattern,
+ * re-stores the values in schedule order and uploads the result.
+ *
+ *   plan     HOST  out; set to NULL on failure
+ *   M, K     rows / columns of A; 0 is legal
+ *   row_ptr  HOST  int32[M+1], row_ptr[0] == 0, non-decreasing; nnz = row_ptr[M]
+ *   col_idx  HOST  int32[nnz], each in [0, K); any order inside a row; duplicates
+ *                  are legal and are summed
+ *   vals     HOST  float[nnz]; finite values (explicit zeros are ordinary terms)
+ *
+ * The three arrays are only read during the call; the caller may free them when
+ * it returns.  The plan owns its device memory on the device that is current at
+ * the time of the call.
+ */
+spmm_status_t spmm_plan_create(spmm_plan_t **plan, int64_t M, int64_t K,
+                               const int32_t *row_ptr, const int32_t *col_idx,
+                               const float *vals);
+
+/* Same, with explicit settings (opts may be NULL). */
+spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
+                                  const int32_t *row_ptr, const int32_t *col_idx,
+                                  const float *vals, const spmm_options_t *opts);
+
+/*
+ * Executor (paper Section 3.3 "Sparse Coarsen", Listings 5-7): C <- A x B.
+ *
+ *   B       DEVICE  const float[K*N], row-major, leading dimension N, finite values
+ *   N       columns of B and C, >= 1 (32, 64 and 128 have tuned kernels; every
+ *           other N runs through masked column tiles)
+ *   C       DEVICE  float[M*N], row-major, leading dimension N; every element is
+ *           overwritten (rows of A without nonzeros become +0.0); must not alias B
+ *   stream  hipStream_t passed as void* (NULL = the default stream)
+ *
+ * Asynchronous: kernels are enqueued on `stream` and the call returns.  It
+ * allocates nothing and does not synchronise.  Row groups that are pieces of a
+ * split panel meet in scratch memory owned by the plan, so at most one execute
+ * per plan may be in flight at a time (successive calls on one stream are
+ * fine); a plan without split groups (info.n_split == 0) has no such limit.
+ * B and C must be 4-byte aligned; 8-byte alignment with even N enables the
+ * two-columns-per-lane kernels.
+ */
+spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N,
+                           float *C, void *stream);
+
+/* Frees the plan and its device memory.  NULL is a no-op returning SPMM_OK. */
+spmm_status_t spmm_plan_destroy(spmm_plan_t *plan);
+
+/* Read-only introspection: schedule constants and sizes. */
+spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out);
+
+/*
+ * Row groups in launch order, five int32 each:
+ *   row_begin, row_end   rows of A (and of C) the group covers
+ *   nnz_begin, nnz_end   its range in the schedule-ordered value sequence; for a
+ *                        group of whole panels this equals the CSR range
+ *                        row_ptr[row_begin] .. row_ptr[row_end]
+ *   flags                bit 0: the group is one piece of a split panel
+ *   out  HOST int32[5 * cap];  cap must be >= info.n_groups.
+ */
+spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_t cap);
+
+/*
+ * Raw copies of the plan's schedule-ordered arrays (host mirror), for format
+ * round-trip tests and byte accounting.  Layouts are those the kernels read:
+ *   SPMM_ARRAY_HDR    one word per chunk: bits 0-3 pattern (panel rows present in
+ *                     every column of the chunk), bits 4-7 number of real columns,
+ *                     bit 8 last chunk of its panel
+ *   SPMM_ARRAY_COLS   ufk words per chunk: column index per slot (unused slots
+ *                     repeat a real column)
+ *   SPMM_ARRAY_VALS   per chunk, one block of ufk float bit patterns per set pattern
+ *                     row in ascending row order (zeros in unused slots)
+ *   SPMM_ARRAY_ITEMS  16 words per row group in launch order: first row, rows, first
+ *                     chunk, chunks, first value word, flags, then for pieces of
+ *                     split panels: arrival counter, pieces, first scratch slot, piece
+ *   out   HOST, cap_words 32-bit words of room; *n_words (may be NULL) receives the
+ *         array's length.  out == NULL only queries the length.  A too small
+ *         cap_words copies nothing and returns SPMM_ERR_INVALID_ARG.
+ */
+enum { SPMM_ARRAY_HDR = 0, SPMM_ARRAY_COLS = 1, SPMM_ARRAY_VALS = 2, SPMM_ARRAY_ITEMS = 3 };
+spmm_status_t spmm_plan_get_array(const spmm_plan_t *plan, int32_t which,
+                                  uint32_t *out, int64_t cap_words, int64_t *n_words);
+
+const char *spmm_status_string(spmm_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPMM_CDNA4_H */

@@ -1,0 +1,248 @@
+// C ABI of the library (include/spmm.h): plan life cycle, upload, execute-time
+// dispatch of the gfx950 kernels.
+#include "../../include/spmm.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "spmm_format.h"
+#include "spmm_kernels.h"
+#include "spmm_plan.h"
+
+using namespace spmm_fmt;
+
+struct spmm_plan {
+    HostPlan host;
+    bool on_device = false;
+    int device = -1;
+    uint32_t *d_hdr = nullptr, *d_cols = nullptr, *d_vals = nullptr, *d_items = nullptr;
+    float *d_scratch = nullptr;
+    uint32_t *d_tickets = nullptr;
+    int64_t device_bytes = 0;
+    bool force_wide = false;  // test hook: exercise the 64-bit addressing kernels on small inputs
+};
+
+namespace {
+
+int env_int(const char *name)
+{
+    const char *s = std::getenv(name);
+    if (!s || !*s) return 0;
+    return std::atoi(s);
+}
+
+spmm_status_t hip_fail()
+{
+    (void)hipGetLastError();  // clear the sticky error
+    return SPMM_ERR_HIP;
+}
+
+template <typename T>
+spmm_status_t upload(T **dst, const void *src, size_t bytes, int64_t &total)
+{
+    *dst = nullptr;
+    if (bytes == 0) return SPMM_OK;
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return e == hipErrorOutOfMemory ? SPMM_ERR_ALLOC : SPMM_ERR_HIP;
+    }
+    *dst = static_cast<T *>(p);
+    total += (int64_t)bytes;
+    if (src) {
+        if (hipMemcpy(p, src, bytes, hipMemcpyHostToDevice) != hipSuccess) return hip_fail();
+    } else {
+        if (hipMemset(p, 0, bytes) != hipSuccess) return hip_fail();
+    }
+    return SPMM_OK;
+}
+
+void release_device(spmm_plan *p)
+{
+    if (p->d_hdr) (void)hipFree(p->d_hdr);
+    if (p->d_cols) (void)hipFree(p->d_cols);
+    if (p->d_vals) (void)hipFree(p->d_vals);
+    if (p->d_items) (void)hipFree(p->d_items);
+    if (p->d_scratch) (void)hipFree(p->d_scratch);
+    if (p->d_tickets) (void)hipFree(p->d_tickets);
+    p->d_hdr = p->d_cols = p->d_vals = p->d_items = nullptr;
+    p->d_scratch = nullptr;
+    p->d_tickets = nullptr;
+    (void)hipGetLastError();
+}
+
+}  // namespace
+
+extern "C" {
+
+spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, const int32_t *row_ptr,
+                                  const int32_t *col_idx, const float *vals, const spmm_options_t *opts)
+{
+    if (!plan) return SPMM_ERR_INVALID_ARG;
+    *plan = nullptr;
+    InspectorOptions io;
+    io.group_nnz = env_int("SPMM_GROUP_NNZ");
+    io.group_panels = env_int("SPMM_GROUP_PANELS");
+    bool host_only = false;
+    if (opts) {
+        if (opts->group_nnz < 0 || opts->group_panels < 0) return SPMM_ERR_INVALID_ARG;
+        if (opts->group_nnz > 0) io.group_nnz = opts->group_nnz;
+        if (opts->group_panels > 0) io.group_panels = opts->group_panels;
+        host_only = opts->host_only != 0;
+    }
+    spmm_plan *p = new (std::nothrow) spmm_plan();
+    if (!p) return SPMM_ERR_ALLOC;
+    const int rc = spmm_inspect(M, K, row_ptr, col_idx, vals, io, p->host);
+    if (rc != 0) {
+        delete p;
+        return (spmm_status_t)rc;
+    }
+    p->force_wide = env_int("SPMM_FORCE_WIDE") != 0;
+    if (!host_only) {
+        if (hipGetDevice(&p->device) != hipSuccess) {
+            delete p;
+            return hip_fail();
+        }
+        const HostPlan &h = p->host;
+        spmm_status_t st = SPMM_OK;
+        if (st == SPMM_OK) st = upload(&p->d_hdr, h.hdr.data(), h.hdr.size() * 4, p->device_bytes);
+        if (st == SPMM_OK) st = upload(&p->d_cols, h.cols.data(), h.cols.size() * 4, p->device_bytes);
+        if (st == SPMM_OK) st = upload(&p->d_vals, h.vals.data(), h.vals.size() * 4, p->device_bytes);
+        if (st == SPMM_OK) st = upload(&p->d_items, h.items.data(), h.items.size() * 4, p->device_bytes);
+        if (st == SPMM_OK)
+            st = upload(&p->d_scratch, nullptr, (size_t)h.n_slots * SLOT_FLOATS * sizeof(float), p->device_bytes);
+        if (st == SPMM_OK) st = upload(&p->d_tickets, nullptr, (size_t)h.n_tickets * 4, p->device_bytes);
+        if (st != SPMM_OK) {
+            release_device(p);
+            delete p;
+            return st;
+        }
+        p->on_device = true;
+    }
+    *plan = p;
+    return SPMM_OK;
+}
+
+spmm_status_t spmm_plan_create(spmm_plan_t **plan, int64_t M, int64_t K, const int32_t *row_ptr,
+                               const int32_t *col_idx, const float *vals)
+{
+    return spmm_plan_create_ex(plan, M, K, row_ptr, col_idx, vals, nullptr);
+}
+
+spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, float *C, void *stream)
+{
+    if (!plan || N < 1) return SPMM_ERR_INVALID_ARG;
+    if (!plan->on_device) return SPMM_ERR_INVALID_ARG;
+    const HostPlan &h = plan->host;
+    if (h.M == 0) return SPMM_OK;
+    if (!C) return SPMM_ERR_INVALID_ARG;
+    if (h.K > 0 && !B) return SPMM_ERR_INVALID_ARG;
+    if (((uintptr_t)B & 3u) || ((uintptr_t)C & 3u)) return SPMM_ERR_INVALID_ARG;
+
+    const uint64_t b_total = (uint64_t)h.K * (uint64_t)N * 4u;
+    const bool wide = plan->force_wide || b_total > 0xFFFFFFFFull;
+    // Two columns per lane need 8-byte aligned rows; up to 64 columns fit one per lane.
+    const bool pairs = N > 64 && (N % 2 == 0) && !((uintptr_t)B & 7u) && !((uintptr_t)C & 7u);
+    const int vw = pairs ? 2 : 1;
+    const int32_t tile = 64 * vw;
+    const int64_t n_items = (int64_t)(h.items.size() / ITEM_WORDS);
+
+    spmm_launch_args a;
+    a.hdr = plan->d_hdr;
+    a.cols = plan->d_cols;
+    a.vals = plan->d_vals;
+    a.items = plan->d_items;
+    a.n_items = (int32_t)n_items;
+    a.ldn = N;
+    a.scratch = plan->d_scratch;
+    a.tickets = plan->d_tickets;
+    // Column tiles run one after another on the stream, so the scratch slots and
+    // arrival counters of split panels are free again when the next tile starts.
+    for (int32_t j0 = 0; j0 < N; j0 += tile) {
+        a.B = B ? B + j0 : nullptr;
+        a.C = C + j0;
+        a.width = (N - j0 < tile) ? N - j0 : tile;
+        a.b_bytes = wide ? 0u : (uint32_t)(b_total - (uint64_t)j0 * 4u);
+        const int e = spmm_launch_chunks(a, vw, wide, stream);
+        if (e != 0) return SPMM_ERR_HIP;
+    }
+    return SPMM_OK;
+}
+
+spmm_status_t spmm_plan_destroy(spmm_plan_t *plan)
+{
+    if (!plan) return SPMM_OK;
+    if (plan->on_device) release_device(plan);
+    delete plan;
+    return SPMM_OK;
+}
+
+spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
+{
+    if (!plan || !out) return SPMM_ERR_INVALID_ARG;
+    const HostPlan &h = plan->host;
+    std::memset(out, 0, sizeof(*out));
+    out->M = h.M;
+    out->K = h.K;
+    out->nnz = h.nnz;
+    out->ufi = UFI;
+    out->ufk = UFK;
+    out->group_nnz = h.group_nnz;
+    out->group_panels = h.group_panels;
+    out->n_groups = (int64_t)(h.groups.size() / 5);
+    out->n_split = h.n_split;
+    out->n_enum = h.n_enum;
+    out->n_chunks = h.n_chunks;
+    out->vals_words = (int64_t)h.vals.size();
+    out->device_bytes = plan->device_bytes;
+    return SPMM_OK;
+}
+
+spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_t cap)
+{
+    if (!plan || !out) return SPMM_ERR_INVALID_ARG;
+    const HostPlan &h = plan->host;
+    const int64_t n = (int64_t)(h.groups.size() / 5);
+    if (cap < n) return SPMM_ERR_INVALID_ARG;
+    if (n) std::memcpy(out, h.groups.data(), (size_t)n * 5 * sizeof(int32_t));
+    return SPMM_OK;
+}
+
+spmm_status_t spmm_plan_get_array(const spmm_plan_t *plan, int32_t which, uint32_t *out, int64_t cap_words,
+                                  int64_t *n_words)
+{
+    if (!plan) return SPMM_ERR_INVALID_ARG;
+    const HostPlan &h = plan->host;
+    const std::vector<uint32_t> *v = nullptr;
+    switch (which) {
+    case SPMM_ARRAY_HDR: v = &h.hdr; break;
+    case SPMM_ARRAY_COLS: v = &h.cols; break;
+    case SPMM_ARRAY_VALS: v = &h.vals; break;
+    case SPMM_ARRAY_ITEMS: v = &h.items; break;
+    default: return SPMM_ERR_INVALID_ARG;
+    }
+    if (n_words) *n_words = (int64_t)v->size();
+    if (!out) return SPMM_OK;
+    if (cap_words < (int64_t)v->size()) return SPMM_ERR_INVALID_ARG;
+    if (!v->empty()) std::memcpy(out, v->data(), v->size() * 4);
+    return SPMM_OK;
+}
+
+const char *spmm_status_string(spmm_status_t status)
+{
+    switch (status) {
+    case SPMM_OK: return "ok";
+    case SPMM_ERR_INVALID_ARG: return "invalid argument";
+    case SPMM_ERR_INVALID_CSR: return "invalid CSR structure";
+    case SPMM_ERR_ALLOC: return "allocation failed";
+    case SPMM_ERR_HIP: return "HIP runtime error";
+    case SPMM_ERR_UNSUPPORTED: return "size not supported";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

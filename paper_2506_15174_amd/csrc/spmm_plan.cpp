@@ -1,0 +1,373 @@
+// Host inspector: CSR -> nnz-balanced row groups -> per-panel enumeration of
+// nonzero patterns -> chunked, schedule-ordered arrays (spmm_format.h).
+//
+// Paper correspondence: Section 3.2 "Enumeration" (panels of UFI rows, one
+// enumerated block per nonzero pattern, columns of equal pattern listed
+// together), Section 3.3.3 "Data transformation" and Section 3.4 "Data
+// transformer" (values re-stored in the order the schedule consumes them, one
+// column index per enumerated column).  The paper scans dense A in O(M K); this
+// builds the same structure from CSR in O(nnz) plus a per-row sort only for rows
+// whose columns arrive unsorted.
+#include "spmm_plan.h"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "spmm_format.h"
+
+using namespace spmm_fmt;
+
+namespace {
+
+enum { ST_OK = 0, ST_INVALID_ARG = 1, ST_INVALID_CSR = 2, ST_ALLOC = 3, ST_UNSUPPORTED = 5 };
+
+struct Group {
+    int32_t row_begin, row_end, nnz_begin, nnz_end, flags;
+    int32_t seg, nseg;      // piece index / pieces of the panel (split groups only)
+    int64_t ticket, slot0;  // split groups only
+    // filled while emitting
+    int64_t chunk0 = 0, n_chunks = 0, vals0 = 0, n_vals = 0;
+};
+
+// One enumerated column of a panel: a column index with the set of panel rows
+// that hold a value there.
+struct Entry {
+    int32_t col;
+    uint32_t pattern;
+    float v[UFI];  // indexed by row inside the panel
+};
+
+// Nonzero budget of a row group: aim at about 8192 groups (256 compute units x
+// 32 resident waves), in steps of 32, never below 128 nor above 1024 nonzeros.
+int32_t choose_group_nnz(int64_t nnz)
+{
+    int64_t g = (nnz + 8191) / 8192;
+    g = (g + 31) / 32 * 32;
+    if (g < 128) g = 128;
+    if (g > 1024) g = 1024;
+    return (int32_t)g;
+}
+
+struct Emitter {
+    std::vector<uint32_t> hdr, cols, vals;  // creation order
+    int64_t n_enum = 0;
+
+    // Emits one chunk of `count` entries (all of pattern `pattern`).
+    void chunk(const Entry *e, int count, uint32_t pattern, bool end_panel)
+    {
+        uint32_t h = pattern | ((uint32_t)count << HDR_COUNT_SHIFT);
+        if (end_panel) h |= HDR_END_PANEL;
+        hdr.push_back(h);
+        for (int u = 0; u < UFK; ++u) {
+            int32_t c = 0;
+            if (count > 0) c = e[u < count ? u : count - 1].col;
+            cols.push_back((uint32_t)c);
+        }
+        for (int r = 0; r < UFI; ++r) {
+            if (!(pattern & (1u << r))) continue;
+            for (int u = 0; u < UFK; ++u) {
+                uint32_t bits = 0;
+                if (u < count) std::memcpy(&bits, &e[u].v[r], 4);
+                vals.push_back(bits);
+            }
+        }
+        n_enum += count;
+    }
+
+    // Emits the chunks of one panel (or one piece of a panel) whose entries are
+    // ordered so that equal patterns are adjacent.
+    void panel(const std::vector<Entry> &ents)
+    {
+        if (ents.empty()) {
+            chunk(nullptr, 0, 0, true);
+            return;
+        }
+        size_t i = 0;
+        const size_t n = ents.size();
+        while (i < n) {
+            size_t j = i + 1;
+            while (j < n && j - i < (size_t)UFK && ents[j].pattern == ents[i].pattern) ++j;
+            chunk(&ents[i], (int)(j - i), ents[i].pattern, j == n);
+            i = j;
+        }
+    }
+};
+
+}  // namespace
+
+int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *col_idx,
+                 const float *vals, const InspectorOptions &opts, HostPlan &out)
+{
+    if (M < 0 || K < 0 || M > INT32_MAX || K > INT32_MAX) return ST_INVALID_ARG;
+    if (!row_ptr) return ST_INVALID_ARG;
+    if (row_ptr[0] != 0) return ST_INVALID_CSR;
+    for (int64_t i = 0; i < M; ++i)
+        if (row_ptr[i + 1] < row_ptr[i]) return ST_INVALID_CSR;
+    const int64_t nnz = row_ptr[M];
+    if (nnz > 0 && (!col_idx || !vals)) return ST_INVALID_ARG;
+    for (int64_t p = 0; p < nnz; ++p)
+        if (col_idx[p] < 0 || (int64_t)col_idx[p] >= K) return ST_INVALID_CSR;
+
+    try {
+        out = HostPlan();
+        out.M = M;
+        out.K = K;
+        out.nnz = nnz;
+        out.group_nnz = opts.group_nnz > 0 ? std::max(32, opts.group_nnz) : choose_group_nnz(nnz);
+        out.group_panels = opts.group_panels > 0 ? opts.group_panels : 16;
+        const int64_t G = out.group_nnz;
+        const int64_t GP = out.group_panels;
+
+        // ---- 1. row groups, from row_ptr alone -------------------------------
+        // Panels (UFI consecutive rows) are taken in order.  A panel heavier than
+        // the budget is cut into ceil(nnz / G) pieces of G nonzeros of its
+        // schedule order (the last piece takes the rest).  Lighter panels are
+        // packed greedily: a group closes when the next panel would exceed the
+        // budget or the panel cap.
+        std::vector<Group> groups;
+        const int64_t P = (M + UFI - 1) / UFI;
+        int64_t n_tickets = 0, n_slots = 0;
+        {
+            bool open = false;
+            Group cur{};
+            int64_t cur_panels = 0;
+            auto flush = [&]() {
+                if (open) groups.push_back(cur);
+                open = false;
+            };
+            for (int64_t p = 0; p < P; ++p) {
+                const int64_t r0 = p * UFI, r1 = std::min<int64_t>(M, r0 + UFI);
+                const int64_t a = row_ptr[r0], b = row_ptr[r1];
+                const int64_t pn = b - a;
+                if (pn > G) {
+                    flush();
+                    const int64_t nseg = (pn + G - 1) / G;
+                    for (int64_t s = 0; s < nseg; ++s) {
+                        Group g{};
+                        g.row_begin = (int32_t)r0;
+                        g.row_end = (int32_t)r1;
+                        g.nnz_begin = (int32_t)(a + s * G);
+                        g.nnz_end = (int32_t)std::min<int64_t>(b, a + (s + 1) * G);
+                        g.flags = FLAG_SPLIT;
+                        g.seg = (int32_t)s;
+                        g.nseg = (int32_t)nseg;
+                        g.ticket = n_tickets;
+                        g.slot0 = n_slots;
+                        groups.push_back(g);
+                    }
+                    n_tickets += 1;
+                    n_slots += nseg;
+                    continue;
+                }
+                if (open && ((int64_t)cur.nnz_end - cur.nnz_begin + pn > G || cur_panels == GP)) flush();
+                if (!open) {
+                    cur = Group{};
+                    cur.row_begin = (int32_t)r0;
+                    cur.nnz_begin = (int32_t)a;
+                    cur.flags = 0;
+                    cur_panels = 0;
+                    open = true;
+                }
+                cur.row_end = (int32_t)r1;
+                cur.nnz_end = (int32_t)b;
+                cur_panels += 1;
+            }
+            flush();
+        }
+        const int64_t n_groups = (int64_t)groups.size();
+
+        // ---- 2. enumeration and emission, panel by panel ----------------------
+        Emitter em;
+        em.hdr.reserve((size_t)(nnz / 4 + P + 16));
+        em.cols.reserve((size_t)(nnz / 4 + P + 16) * UFK);
+        em.vals.reserve((size_t)(nnz + nnz / 2 + 64));
+
+        std::vector<int32_t> order;                  // canonical order of one row
+        std::vector<int32_t> ccol[UFI];              // canonical columns per panel row
+        std::vector<float> cval[UFI];
+        std::vector<Entry> merged, by_pattern, piece;
+        struct Flat { int32_t entry; int32_t row; };
+        std::vector<Flat> flat;
+
+        int64_t gi = 0;
+        while (gi < n_groups) {
+            Group &g0 = groups[gi];
+            const bool split = (g0.flags & FLAG_SPLIT) != 0;
+            const int64_t g_last = split ? gi + g0.nseg - 1 : gi;  // pieces of a panel are adjacent
+            if (!split) {
+                g0.chunk0 = (int64_t)em.hdr.size();
+                g0.vals0 = (int64_t)em.vals.size();
+            }
+            const int64_t first_panel = g0.row_begin / UFI;
+            const int64_t last_panel = (g0.row_end + UFI - 1) / UFI;  // exclusive
+            for (int64_t p = first_panel; p < last_panel; ++p) {
+                const int64_t r0 = p * UFI, r1 = std::min<int64_t>(M, r0 + UFI);
+                const int rows = (int)(r1 - r0);
+                // canonical rows: stable order by column (duplicates keep stored order)
+                for (int r = 0; r < rows; ++r) {
+                    const int64_t a = row_ptr[r0 + r], b = row_ptr[r0 + r + 1];
+                    const int64_t len = b - a;
+                    ccol[r].resize((size_t)len);
+                    cval[r].resize((size_t)len);
+                    bool sorted = true;
+                    for (int64_t q = a + 1; q < b; ++q)
+                        if (col_idx[q] < col_idx[q - 1]) { sorted = false; break; }
+                    if (sorted) {
+                        std::copy(col_idx + a, col_idx + b, ccol[r].begin());
+                        std::copy(vals + a, vals + b, cval[r].begin());
+                    } else {
+                        order.resize((size_t)len);
+                        std::iota(order.begin(), order.end(), 0);
+                        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+                            return col_idx[a + x] < col_idx[a + y];
+                        });
+                        for (int64_t q = 0; q < len; ++q) {
+                            ccol[r][(size_t)q] = col_idx[a + order[(size_t)q]];
+                            cval[r][(size_t)q] = vals[a + order[(size_t)q]];
+                        }
+                    }
+                }
+                // merge the rows' column lists.  The t-th occurrence of a column in
+                // a row meets the t-th occurrences in the other rows, so a column
+                // stored twice in one row yields two enumerated columns.
+                merged.clear();
+                size_t head[UFI] = {0, 0, 0, 0};
+                uint32_t layer[UFI] = {0, 0, 0, 0};
+                for (;;) {
+                    int32_t best_col = INT32_MAX;
+                    uint32_t best_layer = UINT32_MAX;
+                    bool any = false;
+                    for (int r = 0; r < rows; ++r) {
+                        if (head[r] >= ccol[r].size()) continue;
+                        const int32_t c = ccol[r][head[r]];
+                        if (!any || c < best_col || (c == best_col && layer[r] < best_layer)) {
+                            best_col = c;
+                            best_layer = layer[r];
+                            any = true;
+                        }
+                    }
+                    if (!any) break;
+                    Entry e{};
+                    e.col = best_col;
+                    e.pattern = 0;
+                    for (int r = 0; r < rows; ++r) {
+                        if (head[r] >= ccol[r].size()) continue;
+                        if (ccol[r][head[r]] == best_col && layer[r] == best_layer) {
+                            e.pattern |= 1u << r;
+                            e.v[r] = cval[r][head[r]];
+                            const size_t nx = head[r] + 1;
+                            layer[r] = (nx < ccol[r].size() && ccol[r][nx] == best_col) ? layer[r] + 1 : 0;
+                            head[r] = nx;
+                        }
+                    }
+                    merged.push_back(e);
+                }
+                // list columns of equal pattern together (stable: ascending column inside a pattern)
+                by_pattern.resize(merged.size());
+                {
+                    size_t count[N_PATTERNS + 2] = {0};
+                    for (const Entry &e : merged) count[e.pattern + 1]++;
+                    for (int q = 1; q <= N_PATTERNS + 1; ++q) count[q] += count[q - 1];
+                    for (const Entry &e : merged) by_pattern[count[e.pattern]++] = e;
+                }
+                if (!split) {
+                    em.panel(by_pattern);
+                    continue;
+                }
+                // split panel: cut the schedule order (pattern by pattern, column by
+                // column, row by row) at multiples of the budget; an enumerated
+                // column that straddles a cut is divided between the two pieces.
+                flat.clear();
+                for (size_t e = 0; e < by_pattern.size(); ++e)
+                    for (int r = 0; r < UFI; ++r)
+                        if (by_pattern[e].pattern & (1u << r)) flat.push_back(Flat{(int32_t)e, r});
+                const int64_t base = g0.nnz_begin;
+                for (int64_t s = gi; s <= g_last; ++s) {
+                    Group &gs = groups[s];
+                    gs.chunk0 = (int64_t)em.hdr.size();
+                    gs.vals0 = (int64_t)em.vals.size();
+                    piece.clear();
+                    for (int64_t q = gs.nnz_begin - base; q < gs.nnz_end - base; ++q) {
+                        const Flat &f = flat[(size_t)q];
+                        if (piece.empty() || q == gs.nnz_begin - base || flat[(size_t)q - 1].entry != f.entry) {
+                            Entry e{};
+                            e.col = by_pattern[(size_t)f.entry].col;
+                            e.pattern = 0;
+                            piece.push_back(e);
+                        }
+                        piece.back().pattern |= 1u << f.row;
+                        piece.back().v[f.row] = by_pattern[(size_t)f.entry].v[f.row];
+                    }
+                    em.panel(piece);
+                    gs.n_chunks = (int64_t)em.hdr.size() - gs.chunk0;
+                    gs.n_vals = (int64_t)em.vals.size() - gs.vals0;
+                }
+            }
+            if (!split) {
+                g0.n_chunks = (int64_t)em.hdr.size() - g0.chunk0;
+                g0.n_vals = (int64_t)em.vals.size() - g0.vals0;
+            }
+            gi = g_last + 1;
+        }
+
+        // ---- 3. launch order: heaviest groups first (stable) -------------------
+        std::vector<int64_t> perm((size_t)n_groups);
+        std::iota(perm.begin(), perm.end(), 0);
+        std::stable_sort(perm.begin(), perm.end(), [&](int64_t x, int64_t y) {
+            return (groups[(size_t)x].nnz_end - groups[(size_t)x].nnz_begin) >
+                   (groups[(size_t)y].nnz_end - groups[(size_t)y].nnz_begin);
+        });
+
+        const int64_t total_chunks = (int64_t)em.hdr.size();
+        const int64_t total_vals = (int64_t)em.vals.size();
+        if (total_chunks + CHUNK_TAIL_PAD >= ((int64_t)1 << 31) - 8 || total_vals + VALS_TAIL_PAD >= ((int64_t)1 << 32) ||
+            n_groups >= ((int64_t)1 << 31) - WAVES_PER_WG)
+            return ST_UNSUPPORTED;
+
+        out.hdr.resize((size_t)(total_chunks + CHUNK_TAIL_PAD), 0u);
+        out.cols.resize((size_t)(total_chunks + CHUNK_TAIL_PAD) * UFK, 0u);
+        out.vals.resize((size_t)(total_vals + VALS_TAIL_PAD), 0u);
+        out.groups.resize((size_t)n_groups * 5);
+        out.items.assign((size_t)n_groups * ITEM_WORDS, 0u);
+        int64_t c_at = 0, v_at = 0;
+        for (int64_t i = 0; i < n_groups; ++i) {
+            const Group &g = groups[(size_t)perm[(size_t)i]];
+            std::copy(em.hdr.begin() + g.chunk0, em.hdr.begin() + g.chunk0 + g.n_chunks, out.hdr.begin() + c_at);
+            std::copy(em.cols.begin() + g.chunk0 * UFK, em.cols.begin() + (g.chunk0 + g.n_chunks) * UFK,
+                      out.cols.begin() + c_at * UFK);
+            std::copy(em.vals.begin() + g.vals0, em.vals.begin() + g.vals0 + g.n_vals, out.vals.begin() + v_at);
+            int32_t *gg = &out.groups[(size_t)i * 5];
+            gg[0] = g.row_begin;
+            gg[1] = g.row_end;
+            gg[2] = g.nnz_begin;
+            gg[3] = g.nnz_end;
+            gg[4] = g.flags;
+            uint32_t *it = &out.items[(size_t)i * ITEM_WORDS];
+            it[IT_ROW0] = (uint32_t)g.row_begin;
+            it[IT_NROWS] = (uint32_t)(g.row_end - g.row_begin);
+            it[IT_CHUNK0] = (uint32_t)c_at;
+            it[IT_NCHUNKS] = (uint32_t)g.n_chunks;
+            it[IT_VALS0] = (uint32_t)v_at;
+            it[IT_FLAGS] = (uint32_t)g.flags;
+            if (g.flags & FLAG_SPLIT) {
+                it[IT_TICKET] = (uint32_t)g.ticket;
+                it[IT_NSEG] = (uint32_t)g.nseg;
+                it[IT_SLOT0] = (uint32_t)g.slot0;
+                it[IT_SEG] = (uint32_t)g.seg;
+                out.n_split += 1;
+            }
+            c_at += g.n_chunks;
+            v_at += g.n_vals;
+        }
+        out.n_chunks = total_chunks;
+        out.n_enum = em.n_enum;
+        out.n_tickets = n_tickets;
+        out.n_slots = n_slots;
+    } catch (const std::bad_alloc &) {
+        out = HostPlan();
+        return ST_ALLOC;
+    }
+    return ST_OK;
+}

@@ -1,0 +1,37 @@
+// Host inspector (internal): builds the schedule-ordered arrays of
+// spmm_format.h from CSR.  No HIP here; spmm_api.cpp uploads the result.
+#ifndef SPMM_PLAN_H
+#define SPMM_PLAN_H
+
+#include <stdint.h>
+#include <vector>
+
+struct HostPlan {
+    int64_t M = 0, K = 0, nnz = 0;
+    int32_t group_nnz = 0;     // nonzero budget per row group
+    int32_t group_panels = 0;  // panel cap per row group
+
+    // Row groups in launch order, five int32 each (see include/spmm.h).
+    std::vector<int32_t> groups;
+    // Kernel descriptors, ITEM_WORDS per group, launch order.
+    std::vector<uint32_t> items;
+    // Chunk arrays (already padded for the kernels' look-ahead).
+    std::vector<uint32_t> hdr, cols, vals;
+    int64_t n_chunks = 0;      // real chunks (without the padding)
+    int64_t n_enum = 0;        // enumerated columns (real column slots)
+    int64_t n_split = 0;       // groups that are pieces of split panels
+    int64_t n_tickets = 0;     // split panels
+    int64_t n_slots = 0;       // scratch slots (= n_split)
+};
+
+struct InspectorOptions {
+    int32_t group_nnz = 0;     // 0 = choose
+    int32_t group_panels = 0;  // 0 = choose
+};
+
+// Status codes follow spmm_status_t (0 ok, 1 invalid argument, 2 invalid CSR,
+// 3 allocation failure, 5 unsupported size).
+int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *col_idx,
+                 const float *vals, const InspectorOptions &opts, HostPlan &out);
+
+#endif

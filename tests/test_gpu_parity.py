@@ -1,0 +1,225 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the
+C ABI (GPU machine only: run with -m gpu).
+
+Bar (written out here): |C_gpu - C_ref| <= 1e-5 * S per element, where C_ref is
+the oracle's double-precision value and S = sum |A_ik| |B_kj| over the same
+terms; elements with S == 0 must be exactly zero.  With small-integer data every
+summation order is exact in fp32, so those cases must match the oracle bit for
+bit.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import paper_2506_15174_amd as spmm
+from workloads import generators as gen
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def torch_gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    spmm.load()
+    return torch
+
+
+def gpu_product(torch, csr, B, guard_rows=0, stream=None, **plan_kw):
+    """plan_create + execute through the C ABI; returns C as numpy (and the plan)."""
+    plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, **plan_kw)
+    dB = torch.from_numpy(np.ascontiguousarray(B)).cuda()
+    N = B.shape[1]
+    if guard_rows:
+        full = torch.full((csr.M + 2 * guard_rows, N), float("nan"), dtype=torch.float32, device="cuda")
+        dC = full[guard_rows:guard_rows + csr.M]
+        plan.execute(dB, dC, stream=stream)
+        torch.cuda.synchronize()
+        host = full.cpu().numpy()
+        assert np.isnan(host[:guard_rows]).all() and np.isnan(host[guard_rows + csr.M:]).all(), \
+            "rows outside C were written"
+        return host[guard_rows:guard_rows + csr.M].copy(), plan
+    dC = torch.full((csr.M, N), float("nan"), dtype=torch.float32, device="cuda")
+    plan.execute(dB, dC, stream=stream)
+    torch.cuda.synchronize()
+    return dC.cpu().numpy(), plan
+
+
+def check(oracle, csr, B, C):
+    C_ref, S = oracle.spmm(csr.row_ptr, csr.col_idx, csr.vals, B)
+    err, bad_zero = oracle.parity_error(C, C_ref, S)
+    assert bad_zero == 0, "%d elements without terms are not exactly zero" % bad_zero
+    assert err <= TOL, "max relative error %.3e" % err
+    return err
+
+
+def heavy_tail(M, K, seed):
+    rng = np.random.default_rng(seed)
+    W = np.where(rng.random((M, K)) < 0.05, rng.standard_normal((M, K)), 0.0).astype(np.float32)
+    W[3] = rng.standard_normal(K)
+    W[M // 2] = rng.standard_normal(K)
+    W[[0, 5, 6, 7, 8, M - 1]] = 0
+    return gen.csr_from_dense(W)
+
+
+def test_tiny_config(torch_gpu, oracle):
+    csr = gen.tiny()
+    B = gen.activations_for(csr, 32)
+    C, _ = gpu_product(torch_gpu, csr, B, guard_rows=8)
+    check(oracle, csr, B, C)
+
+
+@pytest.mark.parametrize("N", [32, 64, 128])
+def test_conv_config(torch_gpu, oracle, N):
+    csr = gen.conv_layer()
+    B = gen.activations_for(csr, N)
+    C, plan = gpu_product(torch_gpu, csr, B, guard_rows=4)
+    check(oracle, csr, B, C)
+    assert plan.describe()["n_split"] > 0  # 410 nonzeros per row: every panel is split
+
+
+@pytest.mark.parametrize("shape_index,sparsity_index,N", [
+    (0, 0, 128), (0, 1, 64), (0, 2, 32), (0, 3, 128), (1, 0, 32), (1, 1, 128), (1, 2, 64), (1, 3, 32)])
+def test_ffn_config(torch_gpu, oracle, shape_index, sparsity_index, N):
+    csr = gen.ffn(shape_index, sparsity_index)
+    B = gen.activations_for(csr, N)
+    C, _ = gpu_product(torch_gpu, csr, B)
+    check(oracle, csr, B, C)
+
+
+@pytest.mark.parametrize("N", [1, 2, 31, 33, 63, 65, 96, 127, 130, 200, 256, 257])
+def test_any_column_count_with_ragged_rows_and_split_panels(torch_gpu, oracle, N):
+    csr = heavy_tail(39, 1500, 40 + N)   # M % 4 != 0, dense rows, empty rows
+    B = gen.dense_activations(csr.K, N, 50 + N)
+    C, plan = gpu_product(torch_gpu, csr, B, guard_rows=3, group_nnz=96)
+    assert plan.describe()["n_split"] > 0
+    check(oracle, csr, B, C)
+
+
+@pytest.mark.parametrize("group_nnz", [32, 64, 1000, 100000])
+def test_group_budget_does_not_change_the_result_class(torch_gpu, oracle, group_nnz):
+    csr = gen.lognormal_rows(300, 700, 0.8, 61)
+    B = gen.dense_activations(csr.K, 128, 62)
+    C, _ = gpu_product(torch_gpu, csr, B, group_nnz=group_nnz)
+    check(oracle, csr, B, C)
+
+
+@pytest.mark.parametrize("N", [32, 64, 128, 100])
+def test_small_integer_data_is_bit_exact(torch_gpu, oracle, N):
+    rng = np.random.default_rng(70 + N)
+    M, K = 203, 900
+    W = np.where(rng.random((M, K)) < 0.2, rng.integers(-8, 9, (M, K)), 0).astype(np.float32)
+    W[17] = rng.integers(1, 9, K)          # a dense row: split panel, partial sums meet in scratch
+    csr = gen.csr_from_dense(W)
+    B = rng.integers(-16, 17, (K, N)).astype(np.float32)
+    C, plan = gpu_product(torch_gpu, csr, B, group_nnz=128)
+    assert plan.describe()["n_split"] > 0
+    C_ref, _ = oracle.spmm(csr.row_ptr, csr.col_idx, csr.vals, B)
+    assert np.abs(C_ref).max() < 2 ** 24
+    assert np.array_equal(C.astype(np.float64), C_ref)
+
+
+def test_identity_and_empty_matrices(torch_gpu, oracle):
+    n = 130
+    eye = gen.csr_from_dense(np.eye(n, dtype=np.float32))
+    B = gen.dense_activations(n, 64, 80)
+    C, _ = gpu_product(torch_gpu, eye, B)
+    assert np.array_equal(C, B)
+    empty = gen.csr_from_dense(np.zeros((11, n), dtype=np.float32))
+    C0, _ = gpu_product(torch_gpu, empty, B)
+    assert C0.shape == (11, 64) and not C0.any() and not np.signbit(C0).any()
+    # no rows at all: nothing to launch, nothing written
+    none = spmm.plan_create(0, n, np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
+    dB = torch_gpu.from_numpy(B).cuda()
+    out = none.execute(dB)
+    assert tuple(out.shape) == (0, 64)
+
+
+def test_column_order_inside_rows_does_not_matter(torch_gpu):
+    rng = np.random.default_rng(81)
+    csr = gen.uniform_positions(64, 300, 0.7, 82)
+    col, val = csr.col_idx.copy(), csr.vals.copy()
+    for i in range(csr.M):
+        lo, hi = csr.row_ptr[i], csr.row_ptr[i + 1]
+        perm = rng.permutation(hi - lo)
+        col[lo:hi], val[lo:hi] = col[lo:hi][perm], val[lo:hi][perm]
+    B = gen.dense_activations(csr.K, 128, 83)
+    C0, _ = gpu_product(torch_gpu, csr, B)
+    C1, _ = gpu_product(torch_gpu, gen.Csr(csr.M, csr.K, csr.row_ptr, col, val), B)
+    assert np.array_equal(C0, C1)
+
+
+def test_repeated_and_other_stream_executes_are_bit_identical(torch_gpu, oracle):
+    csr = heavy_tail(64, 2000, 90)
+    B = gen.dense_activations(csr.K, 128, 91)
+    plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, group_nnz=64)
+    assert plan.describe()["n_split"] > 0
+    dB = torch_gpu.from_numpy(B).cuda()
+    first = plan.execute(dB).cpu().numpy()
+    check(oracle, csr, B, first)
+    for _ in range(5):
+        again = plan.execute(dB)
+        torch_gpu.cuda.synchronize()
+        assert np.array_equal(first, again.cpu().numpy())
+    side = torch_gpu.cuda.Stream()
+    side.wait_stream(torch_gpu.cuda.current_stream())
+    with torch_gpu.cuda.stream(side):
+        other = plan.execute(dB)
+    side.synchronize()
+    assert np.array_equal(first, other.cpu().numpy())
+
+
+def test_wide_addressing_kernels(torch_gpu, oracle):
+    os.environ["SPMM_FORCE_WIDE"] = "1"
+    try:
+        csr = heavy_tail(50, 800, 95)
+        for N in (32, 128, 77):
+            B = gen.dense_activations(csr.K, N, 96 + N)
+            C, _ = gpu_product(torch_gpu, csr, B, guard_rows=2, group_nnz=128)
+            check(oracle, csr, B, C)
+    finally:
+        del os.environ["SPMM_FORCE_WIDE"]
+
+
+def test_execute_rejects_bad_arguments(torch_gpu):
+    csr = gen.tiny()
+    plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals)
+    dB = torch_gpu.zeros((csr.K, 32), dtype=torch_gpu.float32, device="cuda")
+    dC = torch_gpu.zeros((csr.M, 32), dtype=torch_gpu.float32, device="cuda")
+    lib = spmm.load()
+    assert lib.spmm_execute(plan.handle, dB.data_ptr(), 0, dC.data_ptr(), None) == spmm.SPMM_ERR_INVALID_ARG
+    assert lib.spmm_execute(plan.handle, None, 32, dC.data_ptr(), None) == spmm.SPMM_ERR_INVALID_ARG
+    assert lib.spmm_execute(plan.handle, dB.data_ptr(), 32, None, None) == spmm.SPMM_ERR_INVALID_ARG
+    assert lib.spmm_execute(plan.handle, dB.data_ptr() + 2, 32, dC.data_ptr(), None) == spmm.SPMM_ERR_INVALID_ARG
+    assert plan.describe()["device_bytes"] > 0
+
+
+def test_stress_config_sampled_rows_at_full_size(torch_gpu, oracle):
+    """Full 16384 x 16384 Zipf matrix at N = 128 in the launch configuration the
+    benchmark times; the oracle checks a sample of rows one by one (all rows of
+    256 sampled panels plus every dense and every empty row among them)."""
+    csr = gen.stress()
+    B = gen.activations_for(csr, 128)
+    C, plan = gpu_product(torch_gpu, csr, B)
+    assert np.isfinite(C).all()
+    rng = np.random.default_rng(123)
+    lens = np.diff(csr.row_ptr)
+    sample = set()
+    for p in rng.choice(csr.M // 4, size=256, replace=False):
+        sample.update(range(4 * p, 4 * p + 4))
+    sample.update(np.flatnonzero(lens == lens.max())[:16].tolist())
+    sample.update(np.flatnonzero(lens == 0)[:64].tolist())
+    rows = np.array(sorted(sample))
+    counts = lens[rows]
+    sub_ptr = np.zeros(len(rows) + 1, dtype=np.int32)
+    np.cumsum(counts, out=sub_ptr[1:])
+    idx = np.concatenate([np.arange(csr.row_ptr[r], csr.row_ptr[r + 1]) for r in rows])
+    sub = gen.Csr(len(rows), csr.K, sub_ptr, csr.col_idx[idx], csr.vals[idx])
+    C_ref, S = oracle.spmm(sub.row_ptr, sub.col_idx, sub.vals, B)
+    err, bad_zero = oracle.parity_error(C[rows], C_ref, S)
+    assert bad_zero == 0 and err <= TOL, "max relative error %.3e" % err
+    # every empty row of the full matrix is exactly zero
+    assert not C[lens == 0].any()

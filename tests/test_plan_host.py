@@ -1,0 +1,280 @@
+"""Host logic of the library, checked without a GPU (host-only plans).
+
+Covers: the exported C ABI, the row-group enumeration against an independent
+re-derivation from row_ptr (bit-exact), the format round trip back to the
+canonical CSR (bit-exact), the closed forms the paper gives for pattern
+enumeration, the meaning of the chunk arrays (evaluated by a test-side
+interpreter against the oracle) and the error codes of the boundary.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2506_15174_amd as spmm
+from workloads import generators as gen
+
+from plan_reference import (UFI, UFK, canonical_csr, decode_plan, derive_groups,
+                            interpret_plan)
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def host_plan(csr, **kw):
+    return spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, host_only=True, **kw)
+
+
+def arrays(plan):
+    return (plan.get_array(spmm.ARRAY_ITEMS), plan.get_array(spmm.ARRAY_HDR),
+            plan.get_array(spmm.ARRAY_COLS), plan.get_array(spmm.ARRAY_VALS))
+
+
+def heavy_tail_matrix(M, K, seed, heavy_rows=(3, 10), empty_rows=(0, 5, 6, 7, 8)):
+    """Random sparse matrix with a few dense rows and a few empty ones."""
+    rng = np.random.default_rng(seed)
+    W = np.where(rng.random((M, K)) < 0.08, rng.standard_normal((M, K)), 0.0).astype(np.float32)
+    for r in heavy_rows:
+        if r < M:
+            W[r] = rng.standard_normal(K).astype(np.float32)
+    for r in empty_rows:
+        if r < M:
+            W[r] = 0
+    return gen.csr_from_dense(W)
+
+
+CASES = {
+    "tiny": lambda: gen.tiny(),
+    "uniform_half": lambda: gen.uniform_positions(64, 96, 0.5, 3),
+    "ragged_rows": lambda: gen.uniform_positions(37, 50, 0.8, 4),       # M % 4 != 0
+    "heavy_tail": lambda: heavy_tail_matrix(30, 700, 5),                # split panels + empty rows
+    "all_empty": lambda: gen.csr_from_dense(np.zeros((9, 12), np.float32)),
+    "single_row": lambda: gen.uniform_positions(1, 300, 0.3, 6),
+    "lognormal": lambda: gen.lognormal_rows(128, 256, 0.9, 7),
+}
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "spmm.h")).read()
+    declared = set(re.findall(r"\b(spmm_[a-z_]+)\s*\(", header))
+    assert declared == set(spmm.EXPORTS)
+    lib = ctypes.CDLL(spmm.LIB_PATH)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert spmm.status_string(0) == "ok"
+    assert "CSR" in spmm.status_string(spmm.SPMM_ERR_INVALID_CSR)
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+@pytest.mark.parametrize("group_nnz", [0, 32, 200])
+def test_row_groups_match_python_rederivation(name, group_nnz):
+    csr = CASES[name]()
+    plan = host_plan(csr, group_nnz=group_nnz)
+    info = plan.describe()
+    assert (info["M"], info["K"], info["nnz"]) == (csr.M, csr.K, int(csr.row_ptr[-1]))
+    assert (info["ufi"], info["ufk"]) == (UFI, UFK)
+    if group_nnz:
+        assert info["group_nnz"] == group_nnz
+    got = plan.get_groups()
+    want = derive_groups(csr.row_ptr, csr.M, info["group_nnz"], info["group_panels"])
+    assert got.shape == want.shape and np.array_equal(got, want)
+    assert info["n_groups"] == len(want) and info["n_split"] == int((want[:, 4] & 1).sum())
+    # invariants: whole rows and the whole nonzero range are covered exactly once
+    by_row = got[np.lexsort((got[:, 2], got[:, 0]))]
+    nnz_cover = 0
+    next_row = 0
+    for rb, re_, nb, ne, fl in by_row:
+        assert ne - nb <= info["group_nnz"] and ne >= nb
+        if fl & 1:
+            assert re_ - rb <= UFI and rb % UFI == 0 and ne > nb
+            assert rb in (next_row, next_row - (re_ - rb))  # pieces share their panel's rows
+        else:
+            assert rb == next_row and rb % UFI == 0
+            assert (nb, ne) == (csr.row_ptr[rb], csr.row_ptr[re_])
+        assert nb == nnz_cover
+        nnz_cover = ne
+        next_row = re_
+    assert next_row == csr.M and nnz_cover == csr.row_ptr[-1]
+    sizes = got[:, 3] - got[:, 2]
+    assert np.all(np.diff(sizes) <= 0), "launch order is heaviest first"
+
+
+def test_default_group_budget_rule():
+    for nnz, want in ((0, 128), (6554, 128), (1258291, 160), (13330308, 1024), (8192 * 512, 512)):
+        row_ptr = np.array([0], dtype=np.int32)
+        # the rule depends on nnz only: one row of that many entries is enough
+        if nnz:
+            K = nnz
+            csr = gen.Csr(1, K, np.array([0, nnz], np.int32), np.arange(nnz, dtype=np.int32),
+                          np.ones(nnz, np.float32))
+            info = host_plan(csr).describe()
+        else:
+            info = spmm.plan_create(0, 5, row_ptr, np.zeros(0, np.int32), np.zeros(0, np.float32),
+                                    host_only=True).describe()
+        assert info["group_nnz"] == want and info["group_panels"] == 16
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+@pytest.mark.parametrize("group_nnz", [0, 32, 200])
+def test_format_round_trip_is_bit_exact(name, group_nnz):
+    csr = CASES[name]()
+    plan = host_plan(csr, group_nnz=group_nnz)
+    items, hdr, cols, vals = arrays(plan)
+    rows, cc, bits = decode_plan(items, hdr, cols, vals)
+    assert len(rows) == csr.row_ptr[-1] == plan.describe()["nnz"]
+    order = np.lexsort((cc, rows))
+    want_rows, want_cols, want_bits = canonical_csr(csr.row_ptr, csr.col_idx, csr.vals)
+    assert np.array_equal(rows[order], want_rows)
+    assert np.array_equal(cc[order], want_cols)
+    assert np.array_equal(bits[order], want_bits)
+    info = plan.describe()
+    counts = (hdr[:info["n_chunks"]] >> 4) & 15
+    assert int(counts.sum()) == info["n_enum"]
+    assert len(hdr) >= info["n_chunks"] + 2 and not hdr[info["n_chunks"]:].any()
+    assert len(cols) == len(hdr) * UFK and len(vals) == info["vals_words"]
+
+
+def test_unsorted_and_duplicate_columns_are_canonicalised():
+    row_ptr = np.array([0, 5, 5, 8, 9], dtype=np.int32)
+    col_idx = np.array([7, 2, 7, 0, 2, 2, 7, 1, 7], dtype=np.int32)
+    vals = np.array([1, 2, 3, 4, 5, 6, 7, 8, 9], dtype=np.float32)
+    csr = gen.Csr(4, 8, row_ptr, col_idx, vals)
+    plan = host_plan(csr)
+    items, hdr, cols, v = arrays(plan)
+    rows, cc, bits = decode_plan(items, hdr, cols, v)
+    got = sorted(zip(rows.tolist(), cc.tolist(), bits.view(np.float32).tolist()))
+    want = sorted(zip([0, 0, 0, 0, 0, 2, 2, 2, 3], col_idx.tolist(), vals.tolist()))
+    assert got == want
+    # column 7 is stored twice in row 0: its second occurrence cannot share an
+    # enumerated column with the first, so 7 appears in two different column slots
+    n = plan.describe()["n_chunks"]
+    slots = [int(cols[c * UFK + u]) for c in range(n) for u in range((int(hdr[c]) >> 4) & 15)]
+    assert slots.count(7) == 2 and slots.count(2) == 2
+    # within a row, duplicates keep their stored order (3 after 1 for column 7 of row 0)
+    B = np.eye(8, dtype=np.float32)
+    C = interpret_plan(items, hdr, cols, v, B, 4)
+    assert C[0, 7] == 4.0 and C[0, 2] == 7.0 and C[2, 2] == 6.0 and C[3, 7] == 9.0
+    assert not C[1].any()
+
+
+def test_every_pattern_of_a_four_row_panel_is_enumerated():
+    # Paper Section 2: a tile of 4 rows has 15 possible nonzero patterns.
+    W = np.zeros((4, 15), dtype=np.float32)
+    for p in range(1, 16):
+        for r in range(4):
+            if (p >> r) & 1:
+                W[r, p - 1] = 10 * p + r
+    plan = host_plan(gen.csr_from_dense(W))
+    items, hdr, cols, vals = arrays(plan)
+    n = plan.describe()["n_chunks"]
+    seen = {int(h) & 15: int(cols[c * UFK]) for c, h in enumerate(hdr[:n])}
+    assert sorted(seen) == list(range(1, 16)) and len(seen) == 2 ** UFI - 1
+    assert all(col == p - 1 for p, col in seen.items())
+    # three rows give 2^3 - 1 = 7 patterns (caption of the paper's Figure 4)
+    plan3 = host_plan(gen.csr_from_dense(W[:3]))
+    _, hdr3, _, _ = arrays(plan3)
+    pats3 = {int(h) & 15 for h in hdr3[:plan3.describe()["n_chunks"]]}
+    assert pats3 == set(range(1, 8))
+
+
+def test_pattern_histogram_of_uniform_sparsity_matches_closed_form():
+    # With independent positions of density d a panel column shows pattern p with
+    # probability d^r (1-d)^(4-r), r = popcount(p) (the paper's "nearly uniform
+    # frequency" at d = 1/2, Section 3.2.2); the reuse factor nnz / n_enum is
+    # 4 d / (1 - (1-d)^4).
+    for d, seed in ((0.5, 21), (0.2, 22), (0.1, 23)):
+        M, K = 256, 2048
+        rng = np.random.default_rng(seed)
+        W = np.where(rng.random((M, K)) < d, 1.0, 0.0).astype(np.float32)
+        csr = gen.csr_from_dense(W)
+        plan = host_plan(csr, group_nnz=1 << 20, group_panels=1 << 20)
+        info = plan.describe()
+        items, hdr, cols, vals = arrays(plan)
+        n = info["n_chunks"]
+        pat = hdr[:n] & 15
+        cnt = (hdr[:n] >> 4) & 15
+        hist = np.bincount(pat, weights=cnt, minlength=16)
+        total_columns = (M // UFI) * K
+        for p in range(1, 16):
+            r = bin(p).count("1")
+            prob = d ** r * (1 - d) ** (UFI - r)
+            sigma = np.sqrt(total_columns * prob * (1 - prob))
+            assert abs(hist[p] - total_columns * prob) < 6 * sigma + 1
+        reuse = info["nnz"] / info["n_enum"]
+        assert abs(reuse - UFI * d / (1 - (1 - d) ** UFI)) < 0.02
+
+
+@pytest.mark.parametrize("name", ["tiny", "ragged_rows", "heavy_tail", "all_empty", "single_row"])
+@pytest.mark.parametrize("group_nnz", [0, 32])
+def test_chunk_arrays_evaluate_to_the_product(oracle, name, group_nnz):
+    csr = CASES[name]()
+    B = gen.dense_activations(csr.K, 5, 99)
+    plan = host_plan(csr, group_nnz=group_nnz)
+    C = interpret_plan(*arrays(plan), B, csr.M)
+    C_ref, S = oracle.spmm(csr.row_ptr, csr.col_idx, csr.vals, B)
+    err, bad_zero = oracle.parity_error(C, C_ref, S)
+    assert err <= 1e-5 and bad_zero == 0
+
+
+def test_plan_bytes_against_csr_bytes_trend():
+    # Paper Section 4.4: the transformed format is smaller than CSR at moderate
+    # sparsity (one index per merged column instead of one per nonzero) and larger
+    # at extreme sparsity (metadata).  Here: 4 bytes per value slot, 4 per column
+    # slot, 4 per chunk header.
+    def ratio(sparsity):
+        csr = gen.uniform_positions(512, 512, sparsity, 31)
+        info = host_plan(csr).describe()
+        plan_bytes = 4 * (info["vals_words"] + info["n_chunks"] * (UFK + 1))
+        csr_bytes = 8 * info["nnz"] + 4 * (csr.M + 1)
+        return plan_bytes / csr_bytes
+    assert ratio(0.5) < ratio(0.9) < ratio(0.99)
+    assert ratio(0.5) < 1.0 < ratio(0.99)
+
+
+def test_error_codes_of_the_boundary():
+    ok_rp = np.array([0, 1, 2], dtype=np.int32)
+    ci = np.array([0, 1], dtype=np.int32)
+    v = np.ones(2, dtype=np.float32)
+
+    def status(*args, **kw):
+        try:
+            spmm.plan_create(*args, host_only=True, **kw)
+        except spmm.SpmmError as e:
+            return e.status
+        return 0
+
+    assert status(2, 2, ok_rp, ci, v) == 0
+    assert status(-1, 2, ok_rp, ci, v) == spmm.SPMM_ERR_INVALID_ARG
+    assert status(2, -1, ok_rp, ci, v) == spmm.SPMM_ERR_INVALID_ARG
+    assert status(2, 2 ** 31, ok_rp, ci, v) == spmm.SPMM_ERR_INVALID_ARG
+    assert status(2, 2, np.array([1, 1, 2], np.int32), ci, v) == spmm.SPMM_ERR_INVALID_CSR
+    assert status(2, 2, np.array([0, 2, 1], np.int32), ci, v) == spmm.SPMM_ERR_INVALID_CSR
+    assert status(2, 2, ok_rp, np.array([0, 2], np.int32), v) == spmm.SPMM_ERR_INVALID_CSR
+    assert status(2, 2, ok_rp, np.array([0, -1], np.int32), v) == spmm.SPMM_ERR_INVALID_CSR
+    assert status(2, 2, ok_rp, ci, v, group_nnz=-5) == spmm.SPMM_ERR_INVALID_ARG
+    lib = spmm.load()
+    h = ctypes.c_void_p(123)
+    assert lib.spmm_plan_create(ctypes.byref(h), 2, 2, None, None, None) == spmm.SPMM_ERR_INVALID_ARG
+    assert h.value is None
+    assert lib.spmm_plan_create(None, 2, 2, ok_rp.ctypes.data, ci.ctypes.data, v.ctypes.data) \
+        == spmm.SPMM_ERR_INVALID_ARG
+    assert lib.spmm_plan_destroy(None) == spmm.SPMM_OK
+    assert lib.spmm_plan_describe(None, None) == spmm.SPMM_ERR_INVALID_ARG
+    assert lib.spmm_execute(None, None, 32, None, None) == spmm.SPMM_ERR_INVALID_ARG
+    # a host-only plan refuses to execute (there is no CPU path)
+    plan = spmm.plan_create(2, 2, ok_rp, ci, v, host_only=True)
+    assert lib.spmm_execute(plan.handle, None, 32, None, None) == spmm.SPMM_ERR_INVALID_ARG
+    small = np.zeros(1, dtype=np.uint32)
+    assert lib.spmm_plan_get_array(plan.handle, spmm.ARRAY_COLS, small.ctypes.data, 1, None) \
+        == spmm.SPMM_ERR_INVALID_ARG
+    assert lib.spmm_plan_get_array(plan.handle, 9, None, 0, None) == spmm.SPMM_ERR_INVALID_ARG
+    out = np.zeros(5, dtype=np.int32)
+    assert lib.spmm_plan_get_groups(plan.handle, out.ctypes.data, 0) == spmm.SPMM_ERR_INVALID_ARG
+
+
+def test_plan_is_deterministic():
+    csr = CASES["heavy_tail"]()
+    a = arrays(host_plan(csr, group_nnz=64))
+    b = arrays(host_plan(csr, group_nnz=64))
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
