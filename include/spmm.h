@@ -43,7 +43,8 @@ typedef struct {
     int32_t ufk;           /* enumerated columns in flight per wave (the paper's UFk) */
     int32_t group_nnz;     /* nonzero budget of one row group (one wave's work item) */
     int32_t group_panels;  /* most panels a row group may hold */
-    int64_t n_groups;      /* row groups = work items, in launch order */
+    int64_t n_groups;      /* row groups = wave-level work items, in launch order */
+    int64_t n_blocks;      /* workgroups of one launch (16 wave slots each) */
     int64_t n_split;       /* row groups that are pieces of a panel too heavy for one group */
     int64_t n_enum;        /* enumerated columns: B rows a column tile must fetch per execute */
     int64_t n_chunks;      /* chunks: runs of at most ufk enumerated columns of one pattern */
@@ -99,12 +100,11 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
  *   stream  hipStream_t passed as void* (NULL = the default stream)
  *
  * Asynchronous: kernels are enqueued on `stream` and the call returns.  It
- * allocates nothing and does not synchronise.  Row groups that are pieces of a
- * split panel meet in scratch memory owned by the plan, so at most one execute
- * per plan may be in flight at a time (successive calls on one stream are
- * fine); a plan without split groups (info.n_split == 0) has no such limit.
- * B and C must be 4-byte aligned; 8-byte alignment with even N enables the
- * two-columns-per-lane kernels.
+ * allocates nothing and does not synchronise.  The plan is read-only during
+ * execution (pieces of a split panel meet in on-chip memory, not in the plan),
+ * so any number of executes of one plan may be in flight on any streams.
+ * Results are bit-identical from run to run.  B and C must be 4-byte aligned;
+ * 8-byte alignment with even N enables the two-columns-per-lane kernels.
  */
 spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N,
                            float *C, void *stream);
@@ -122,6 +122,8 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
  *                        group of whole panels this equals the CSR range
  *                        row_ptr[row_begin] .. row_ptr[row_end]
  *   flags                bit 0: the group is one piece of a split panel
+ * Order: pieces of split panels first (heaviest panel first, pieces in order),
+ * then groups of whole panels (heaviest first); ties keep row order.
  *   out  HOST int32[5 * cap];  cap must be >= info.n_groups.
  */
 spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_t cap);
@@ -136,9 +138,11 @@ spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_
  *                     repeat a real column)
  *   SPMM_ARRAY_VALS   per chunk, one block of ufk float bit patterns per set pattern
  *                     row in ascending row order (zeros in unused slots)
- *   SPMM_ARRAY_ITEMS  16 words per row group in launch order: first row, rows, first
- *                     chunk, chunks, first value word, flags, then for pieces of
- *                     split panels: arrival counter, pieces, first scratch slot, piece
+ *   SPMM_ARRAY_ITEMS  16 words per wave slot, 16 slots per workgroup, launch order:
+ *                     first row, rows, first chunk, chunks, first value word, flags
+ *                     (1 piece of a split panel, 2 idle slot, 4 workgroup with split
+ *                     panels), then the slot's share of the split-panel sums: pieces
+ *                     to add, first piece's slot, tile row, row of C
  *   out   HOST, cap_words 32-bit words of room; *n_words (may be NULL) receives the
  *         array's length.  out == NULL only queries the length.  A too small
  *         cap_words copies nothing and returns SPMM_ERR_INVALID_ARG.

@@ -30,7 +30,8 @@ class PlanInfo(ctypes.Structure):
     _fields_ = [("M", ctypes.c_int64), ("K", ctypes.c_int64), ("nnz", ctypes.c_int64),
                 ("ufi", ctypes.c_int32), ("ufk", ctypes.c_int32),
                 ("group_nnz", ctypes.c_int32), ("group_panels", ctypes.c_int32),
-                ("n_groups", ctypes.c_int64), ("n_split", ctypes.c_int64),
+                ("n_groups", ctypes.c_int64), ("n_blocks", ctypes.c_int64),
+                ("n_split", ctypes.c_int64),
                 ("n_enum", ctypes.c_int64), ("n_chunks", ctypes.c_int64),
                 ("vals_words", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
 

@@ -19,8 +19,6 @@ struct spmm_plan {
     bool on_device = false;
     int device = -1;
     uint32_t *d_hdr = nullptr, *d_cols = nullptr, *d_vals = nullptr, *d_items = nullptr;
-    float *d_scratch = nullptr;
-    uint32_t *d_tickets = nullptr;
     int64_t device_bytes = 0;
     bool force_wide = false;  // test hook: exercise the 64-bit addressing kernels on small inputs
 };
@@ -67,11 +65,7 @@ void release_device(spmm_plan *p)
     if (p->d_cols) (void)hipFree(p->d_cols);
     if (p->d_vals) (void)hipFree(p->d_vals);
     if (p->d_items) (void)hipFree(p->d_items);
-    if (p->d_scratch) (void)hipFree(p->d_scratch);
-    if (p->d_tickets) (void)hipFree(p->d_tickets);
     p->d_hdr = p->d_cols = p->d_vals = p->d_items = nullptr;
-    p->d_scratch = nullptr;
-    p->d_tickets = nullptr;
     (void)hipGetLastError();
 }
 
@@ -113,9 +107,6 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
         if (st == SPMM_OK) st = upload(&p->d_cols, h.cols.data(), h.cols.size() * 4, p->device_bytes);
         if (st == SPMM_OK) st = upload(&p->d_vals, h.vals.data(), h.vals.size() * 4, p->device_bytes);
         if (st == SPMM_OK) st = upload(&p->d_items, h.items.data(), h.items.size() * 4, p->device_bytes);
-        if (st == SPMM_OK)
-            st = upload(&p->d_scratch, nullptr, (size_t)h.n_slots * SLOT_FLOATS * sizeof(float), p->device_bytes);
-        if (st == SPMM_OK) st = upload(&p->d_tickets, nullptr, (size_t)h.n_tickets * 4, p->device_bytes);
         if (st != SPMM_OK) {
             release_device(p);
             delete p;
@@ -144,24 +135,18 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
     if (((uintptr_t)B & 3u) || ((uintptr_t)C & 3u)) return SPMM_ERR_INVALID_ARG;
 
     const uint64_t b_total = (uint64_t)h.K * (uint64_t)N * 4u;
-    const bool wide = plan->force_wide || b_total > 0xFFFFFFFFull;
+    const bool wide = b_total > 0xFFFFFFFFull || (plan->force_wide && b_total > 0);
     // Two columns per lane need 8-byte aligned rows; up to 64 columns fit one per lane.
     const bool pairs = N > 64 && (N % 2 == 0) && !((uintptr_t)B & 7u) && !((uintptr_t)C & 7u);
     const int vw = pairs ? 2 : 1;
     const int32_t tile = 64 * vw;
-    const int64_t n_items = (int64_t)(h.items.size() / ITEM_WORDS);
-
     spmm_launch_args a;
     a.hdr = plan->d_hdr;
     a.cols = plan->d_cols;
     a.vals = plan->d_vals;
     a.items = plan->d_items;
-    a.n_items = (int32_t)n_items;
+    a.n_blocks = (int32_t)h.n_blocks;
     a.ldn = N;
-    a.scratch = plan->d_scratch;
-    a.tickets = plan->d_tickets;
-    // Column tiles run one after another on the stream, so the scratch slots and
-    // arrival counters of split panels are free again when the next tile starts.
     for (int32_t j0 = 0; j0 < N; j0 += tile) {
         a.B = B ? B + j0 : nullptr;
         a.C = C + j0;
@@ -194,6 +179,7 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
     out->group_nnz = h.group_nnz;
     out->group_panels = h.group_panels;
     out->n_groups = (int64_t)(h.groups.size() / 5);
+    out->n_blocks = h.n_blocks;
     out->n_split = h.n_split;
     out->n_enum = h.n_enum;
     out->n_chunks = h.n_chunks;

@@ -46,34 +46,37 @@ constexpr uint32_t HDR_COUNT_MASK = 0xFu;
 constexpr uint32_t HDR_END_PANEL = 1u << 8;
 
 // Chunks (all zero) appended after the last real chunk so that the kernels'
-// look-ahead of two chunks never leaves the arrays.
-constexpr int CHUNK_TAIL_PAD = 4;
+// look-ahead of four chunks never leaves the arrays.
+constexpr int CHUNK_TAIL_PAD = 8;
 // Zero words appended to vals so that the four per-row block loads of a chunk
 // stay inside the array whatever its pattern.
 constexpr int VALS_TAIL_PAD = UFI * UFK;
 
-// Work-item descriptor, one per row group, launch order.
+// Waves per workgroup.  One wave executes one row group; a workgroup ("block")
+// holds up to WAVES_PER_WG of them.  A panel too heavy for one wave is cut into
+// at most WAVES_PER_WG pieces that sit in one block and meet in LDS.
+constexpr int WAVES_PER_WG = 16;
+// Most split panels one block may hold: WAVES_PER_WG / UFI, so that every
+// (panel, row) sum after the barrier has a wave of its own.
+constexpr int SPLIT_PANELS_PER_WG = WAVES_PER_WG / UFI;
+
+// Wave-slot descriptor: WAVES_PER_WG per block, launch order.
 constexpr int ITEM_WORDS = 16;
 enum ItemField {
-    IT_ROW0 = 0,    // first row
-    IT_NROWS = 1,   // rows covered (whole panels; the last may be short)
-    IT_CHUNK0 = 2,  // first chunk
-    IT_NCHUNKS = 3, // chunks of the group (>= 1)
-    IT_VALS0 = 4,   // first word of the group's values
-    IT_FLAGS = 5,   // bit 0: piece of a split panel
-    IT_TICKET = 6,  // split: index of the panel's arrival counter
-    IT_NSEG = 7,    // split: pieces the panel was cut into
-    IT_SLOT0 = 8,   // split: scratch slot of the panel's first piece
-    IT_SEG = 9      // split: index of this piece
+    IT_ROW0 = 0,      // first row
+    IT_NROWS = 1,     // rows covered (whole panels; the last may be short)
+    IT_CHUNK0 = 2,    // first chunk
+    IT_NCHUNKS = 3,   // chunks of the group (0 for an idle slot)
+    IT_VALS0 = 4,     // first word of the group's values
+    IT_FLAGS = 5,     // FLAG_* bits
+    IT_RED_NSEG = 6,  // after the barrier: pieces to add (0 = this wave adds nothing)
+    IT_RED_SLOT0 = 7, // ... wave slot of the first piece
+    IT_RED_R = 8,     // ... row of the tile to add
+    IT_RED_ROW = 9    // ... row of C to write
 };
-constexpr int FLAG_SPLIT = 1;
-
-// Scratch slot of one piece: UFI rows x SLOT_COLS floats.
-constexpr int SLOT_COLS = 128;
-constexpr int SLOT_FLOATS = UFI * SLOT_COLS;
-
-// Waves (= work items) per workgroup.
-constexpr int WAVES_PER_WG = 4;
+constexpr int FLAG_SPLIT = 1;  // the group is one piece of a split panel: its tile goes to LDS
+constexpr int FLAG_IDLE = 2;   // no group in this wave slot
+constexpr int FLAG_SYNC = 4;   // the block holds split panels: every wave meets at one barrier
 
 }  // namespace spmm_fmt
 #endif

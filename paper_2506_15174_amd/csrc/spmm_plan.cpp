@@ -25,8 +25,7 @@ enum { ST_OK = 0, ST_INVALID_ARG = 1, ST_INVALID_CSR = 2, ST_ALLOC = 3, ST_UNSUP
 
 struct Group {
     int32_t row_begin, row_end, nnz_begin, nnz_end, flags;
-    int32_t seg, nseg;      // piece index / pieces of the panel (split groups only)
-    int64_t ticket, slot0;  // split groups only
+    int32_t seg, nseg;  // piece index / pieces of the panel (split groups only)
     // filled while emitting
     int64_t chunk0 = 0, n_chunks = 0, vals0 = 0, n_vals = 0;
 };
@@ -122,13 +121,12 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
 
         // ---- 1. row groups, from row_ptr alone -------------------------------
         // Panels (UFI consecutive rows) are taken in order.  A panel heavier than
-        // the budget is cut into ceil(nnz / G) pieces of G nonzeros of its
-        // schedule order (the last piece takes the rest).  Lighter panels are
-        // packed greedily: a group closes when the next panel would exceed the
-        // budget or the panel cap.
+        // the budget G is cut into nseg = min(16, ceil(nnz / G)) pieces of
+        // ceil(nnz / nseg) nonzeros of its schedule order (the last piece takes
+        // the rest).  Lighter panels are packed greedily: a group closes when the
+        // next panel would exceed the budget or the panel cap.
         std::vector<Group> groups;
         const int64_t P = (M + UFI - 1) / UFI;
-        int64_t n_tickets = 0, n_slots = 0;
         {
             bool open = false;
             Group cur{};
@@ -143,22 +141,20 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                 const int64_t pn = b - a;
                 if (pn > G) {
                     flush();
-                    const int64_t nseg = (pn + G - 1) / G;
+                    const int64_t want = std::min<int64_t>(WAVES_PER_WG, (pn + G - 1) / G);
+                    const int64_t size = (pn + want - 1) / want;
+                    const int64_t nseg = (pn + size - 1) / size;
                     for (int64_t s = 0; s < nseg; ++s) {
                         Group g{};
                         g.row_begin = (int32_t)r0;
                         g.row_end = (int32_t)r1;
-                        g.nnz_begin = (int32_t)(a + s * G);
-                        g.nnz_end = (int32_t)std::min<int64_t>(b, a + (s + 1) * G);
+                        g.nnz_begin = (int32_t)(a + s * size);
+                        g.nnz_end = (int32_t)std::min<int64_t>(b, a + (s + 1) * size);
                         g.flags = FLAG_SPLIT;
                         g.seg = (int32_t)s;
                         g.nseg = (int32_t)nseg;
-                        g.ticket = n_tickets;
-                        g.slot0 = n_slots;
                         groups.push_back(g);
                     }
-                    n_tickets += 1;
-                    n_slots += nseg;
                     continue;
                 }
                 if (open && ((int64_t)cur.nnz_end - cur.nnz_begin + pn > G || cur_panels == GP)) flush();
@@ -312,59 +308,114 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
             gi = g_last + 1;
         }
 
-        // ---- 3. launch order: heaviest groups first (stable) -------------------
-        std::vector<int64_t> perm((size_t)n_groups);
-        std::iota(perm.begin(), perm.end(), 0);
-        std::stable_sort(perm.begin(), perm.end(), [&](int64_t x, int64_t y) {
+        // ---- 3. launch order and blocks ---------------------------------------
+        // Split panels first, heaviest panel first (stable), each with its pieces
+        // in order; then the groups of whole panels, heaviest first (stable).
+        // Blocks of WAVES_PER_WG wave slots are filled in that order.  The pieces
+        // of a panel never straddle a block and a block holds at most
+        // SPLIT_PANELS_PER_WG split panels; slots left over stay idle.
+        std::vector<int64_t> split_heads, whole;
+        for (int64_t i = 0; i < n_groups; ++i) {
+            const Group &g = groups[(size_t)i];
+            if (!(g.flags & FLAG_SPLIT)) whole.push_back(i);
+            else if (g.seg == 0) split_heads.push_back(i);
+        }
+        auto panel_nnz = [&](int64_t head) {
+            const Group &g0 = groups[(size_t)head];
+            return (int64_t)groups[(size_t)(head + g0.nseg - 1)].nnz_end - g0.nnz_begin;
+        };
+        std::stable_sort(split_heads.begin(), split_heads.end(),
+                         [&](int64_t x, int64_t y) { return panel_nnz(x) > panel_nnz(y); });
+        std::stable_sort(whole.begin(), whole.end(), [&](int64_t x, int64_t y) {
             return (groups[(size_t)x].nnz_end - groups[(size_t)x].nnz_begin) >
                    (groups[(size_t)y].nnz_end - groups[(size_t)y].nnz_begin);
         });
 
         const int64_t total_chunks = (int64_t)em.hdr.size();
         const int64_t total_vals = (int64_t)em.vals.size();
-        if (total_chunks + CHUNK_TAIL_PAD >= ((int64_t)1 << 31) - 8 || total_vals + VALS_TAIL_PAD >= ((int64_t)1 << 32) ||
-            n_groups >= ((int64_t)1 << 31) - WAVES_PER_WG)
+        if (total_chunks + CHUNK_TAIL_PAD >= ((int64_t)1 << 31) - 8 ||
+            total_vals + VALS_TAIL_PAD >= ((int64_t)1 << 32) || n_groups >= ((int64_t)1 << 31) - WAVES_PER_WG)
             return ST_UNSUPPORTED;
 
         out.hdr.resize((size_t)(total_chunks + CHUNK_TAIL_PAD), 0u);
         out.cols.resize((size_t)(total_chunks + CHUNK_TAIL_PAD) * UFK, 0u);
         out.vals.resize((size_t)(total_vals + VALS_TAIL_PAD), 0u);
-        out.groups.resize((size_t)n_groups * 5);
-        out.items.assign((size_t)n_groups * ITEM_WORDS, 0u);
+        out.groups.reserve((size_t)n_groups * 5);
         int64_t c_at = 0, v_at = 0;
-        for (int64_t i = 0; i < n_groups; ++i) {
-            const Group &g = groups[(size_t)perm[(size_t)i]];
+
+        // appends one group to the launch-ordered arrays and returns its descriptor
+        auto place = [&](const Group &g, uint32_t *it) {
             std::copy(em.hdr.begin() + g.chunk0, em.hdr.begin() + g.chunk0 + g.n_chunks, out.hdr.begin() + c_at);
             std::copy(em.cols.begin() + g.chunk0 * UFK, em.cols.begin() + (g.chunk0 + g.n_chunks) * UFK,
                       out.cols.begin() + c_at * UFK);
             std::copy(em.vals.begin() + g.vals0, em.vals.begin() + g.vals0 + g.n_vals, out.vals.begin() + v_at);
-            int32_t *gg = &out.groups[(size_t)i * 5];
-            gg[0] = g.row_begin;
-            gg[1] = g.row_end;
-            gg[2] = g.nnz_begin;
-            gg[3] = g.nnz_end;
-            gg[4] = g.flags;
-            uint32_t *it = &out.items[(size_t)i * ITEM_WORDS];
+            out.groups.push_back(g.row_begin);
+            out.groups.push_back(g.row_end);
+            out.groups.push_back(g.nnz_begin);
+            out.groups.push_back(g.nnz_end);
+            out.groups.push_back(g.flags);
             it[IT_ROW0] = (uint32_t)g.row_begin;
             it[IT_NROWS] = (uint32_t)(g.row_end - g.row_begin);
             it[IT_CHUNK0] = (uint32_t)c_at;
             it[IT_NCHUNKS] = (uint32_t)g.n_chunks;
             it[IT_VALS0] = (uint32_t)v_at;
             it[IT_FLAGS] = (uint32_t)g.flags;
-            if (g.flags & FLAG_SPLIT) {
-                it[IT_TICKET] = (uint32_t)g.ticket;
-                it[IT_NSEG] = (uint32_t)g.nseg;
-                it[IT_SLOT0] = (uint32_t)g.slot0;
-                it[IT_SEG] = (uint32_t)g.seg;
-                out.n_split += 1;
-            }
             c_at += g.n_chunks;
             v_at += g.n_vals;
+        };
+        auto new_block = [&](uint32_t flags) {
+            const size_t at = out.items.size();
+            out.items.resize(at + (size_t)WAVES_PER_WG * ITEM_WORDS, 0u);
+            for (int w = 0; w < WAVES_PER_WG; ++w) out.items[at + (size_t)w * ITEM_WORDS + IT_FLAGS] = FLAG_IDLE | flags;
+            out.n_blocks += 1;
+            return at;
+        };
+
+        // blocks of split panels
+        {
+            size_t at = 0;
+            int used = WAVES_PER_WG, panels = SPLIT_PANELS_PER_WG;  // forces a new block
+            for (int64_t head : split_heads) {
+                const int nseg = groups[(size_t)head].nseg;
+                if (used + nseg > WAVES_PER_WG || panels == SPLIT_PANELS_PER_WG) {
+                    at = new_block(FLAG_SYNC);
+                    used = 0;
+                    panels = 0;
+                }
+                for (int sidx = 0; sidx < nseg; ++sidx) {
+                    uint32_t *it = &out.items[at + (size_t)(used + sidx) * ITEM_WORDS];
+                    place(groups[(size_t)(head + sidx)], it);
+                    it[IT_FLAGS] |= FLAG_SYNC;
+                    out.n_split += 1;
+                }
+                // after the barrier wave UFI * panels + r adds row r of this panel
+                const Group &g0 = groups[(size_t)head];
+                for (int r = 0; r < g0.row_end - g0.row_begin; ++r) {
+                    uint32_t *it = &out.items[at + (size_t)(UFI * panels + r) * ITEM_WORDS];
+                    it[IT_RED_NSEG] = (uint32_t)nseg;
+                    it[IT_RED_SLOT0] = (uint32_t)used;
+                    it[IT_RED_R] = (uint32_t)r;
+                    it[IT_RED_ROW] = (uint32_t)(g0.row_begin + r);
+                }
+                used += nseg;
+                panels += 1;
+            }
+        }
+        // blocks of whole-panel groups
+        {
+            size_t at = 0;
+            int used = WAVES_PER_WG;
+            for (int64_t gi2 : whole) {
+                if (used == WAVES_PER_WG) {
+                    at = new_block(0);
+                    used = 0;
+                }
+                place(groups[(size_t)gi2], &out.items[at + (size_t)used * ITEM_WORDS]);
+                used += 1;
+            }
         }
         out.n_chunks = total_chunks;
         out.n_enum = em.n_enum;
-        out.n_tickets = n_tickets;
-        out.n_slots = n_slots;
     } catch (const std::bad_alloc &) {
         out = HostPlan();
         return ST_ALLOC;

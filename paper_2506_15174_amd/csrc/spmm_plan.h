@@ -13,15 +13,14 @@ struct HostPlan {
 
     // Row groups in launch order, five int32 each (see include/spmm.h).
     std::vector<int32_t> groups;
-    // Kernel descriptors, ITEM_WORDS per group, launch order.
+    // Wave-slot descriptors, ITEM_WORDS per slot, WAVES_PER_WG slots per block.
     std::vector<uint32_t> items;
+    int64_t n_blocks = 0;      // workgroups of one launch
     // Chunk arrays (already padded for the kernels' look-ahead).
     std::vector<uint32_t> hdr, cols, vals;
     int64_t n_chunks = 0;      // real chunks (without the padding)
     int64_t n_enum = 0;        // enumerated columns (real column slots)
     int64_t n_split = 0;       // groups that are pieces of split panels
-    int64_t n_tickets = 0;     // split panels
-    int64_t n_slots = 0;       // scratch slots (= n_split)
 };
 
 struct InspectorOptions {

@@ -12,10 +12,14 @@ UFK = 8
 ITEM_WORDS = 16
 
 
+WAVES_PER_WG = 16
+FLAG_SPLIT, FLAG_IDLE, FLAG_SYNC = 1, 2, 4
+
+
 def derive_groups(row_ptr, M, group_nnz, group_panels):
     """Row groups in launch order as an (n, 5) int32 array, from row_ptr only."""
     rp = [int(x) for x in row_ptr]
-    groups = []
+    whole, split = [], []          # split: list of panels, each a list of pieces
     cur = None
     cur_panels = 0
     P = (M + UFI - 1) // UFI
@@ -25,14 +29,15 @@ def derive_groups(row_ptr, M, group_nnz, group_panels):
         pn = b - a
         if pn > group_nnz:
             if cur is not None:
-                groups.append(cur)
+                whole.append(cur)
                 cur = None
-            nseg = -(-pn // group_nnz)
-            for s in range(nseg):
-                groups.append([r0, r1, a + s * group_nnz, min(b, a + (s + 1) * group_nnz), 1])
+            want = min(WAVES_PER_WG, -(-pn // group_nnz))
+            size = -(-pn // want)
+            nseg = -(-pn // size)
+            split.append([[r0, r1, a + s * size, min(b, a + (s + 1) * size), 1] for s in range(nseg)])
             continue
         if cur is not None and (cur[3] - cur[2] + pn > group_nnz or cur_panels == group_panels):
-            groups.append(cur)
+            whole.append(cur)
             cur = None
         if cur is None:
             cur = [r0, r1, a, b, 0]
@@ -40,10 +45,13 @@ def derive_groups(row_ptr, M, group_nnz, group_panels):
         cur[1], cur[3] = r1, b
         cur_panels += 1
     if cur is not None:
-        groups.append(cur)
-    # heaviest first, ties in creation order
-    order = sorted(range(len(groups)), key=lambda i: (-(groups[i][3] - groups[i][2]), i))
-    return np.array([groups[i] for i in order], dtype=np.int32).reshape(-1, 5)
+        whole.append(cur)
+    # split panels first, heaviest panel first; then whole-panel groups, heaviest
+    # first; ties keep row order
+    split.sort(key=lambda pieces: -(pieces[-1][3] - pieces[0][2]))
+    whole.sort(key=lambda g: -(g[3] - g[2]))
+    out = [piece for pieces in split for piece in pieces] + whole
+    return np.array(out, dtype=np.int32).reshape(-1, 5)
 
 
 def canonical_csr(row_ptr, col_idx, vals):
@@ -53,15 +61,55 @@ def canonical_csr(row_ptr, col_idx, vals):
     return rows[order], np.asarray(col_idx)[order], np.asarray(vals, dtype=np.float32).view(np.uint32)[order]
 
 
+def check_blocks(items):
+    """Structural invariants of the wave-slot table."""
+    items = items.reshape(-1, WAVES_PER_WG, ITEM_WORDS)
+    for blk in items:
+        flags = blk[:, 5]
+        sync = (flags & FLAG_SYNC) != 0
+        assert sync.all() or not sync.any(), "the barrier flag is a property of the block"
+        idle = (flags & FLAG_IDLE) != 0
+        assert np.all(blk[idle, 3] == 0) and np.all(blk[~idle, 3] >= 1)
+        is_split = (flags & FLAG_SPLIT) != 0
+        if not sync.any():
+            assert not is_split.any() and not blk[:, 6].any()
+            continue
+        assert not (is_split & idle).any()
+        assert np.all(is_split | idle), "blocks with split panels hold nothing else"
+        # every split panel of the block has one adding wave per row, covering
+        # exactly the slots of its pieces
+        slots = np.flatnonzero(is_split)
+        covered = np.zeros(WAVES_PER_WG, dtype=int)
+        rows_written = set()
+        for w in range(WAVES_PER_WG):
+            nseg, slot0, r, crow = (int(x) for x in blk[w, 6:10])
+            if nseg == 0:
+                continue
+            pieces = blk[slot0:slot0 + nseg]
+            assert np.all((pieces[:, 5] & FLAG_SPLIT) != 0)
+            assert len(set(pieces[:, 0])) == 1 and len(set(pieces[:, 1])) == 1
+            assert crow == int(pieces[0, 0]) + r and r < int(pieces[0, 1])
+            assert crow not in rows_written
+            rows_written.add(crow)
+            if r == 0:
+                covered[slot0:slot0 + nseg] += 1
+        assert np.all(covered[slots] == 1) and covered.sum() == len(slots)
+        for w in slots:
+            for r in range(int(blk[w, 1])):
+                assert int(blk[w, 0]) + r in rows_written
+
+
 def decode_plan(items, hdr, cols, vals):
-    """Chunk arrays -> list of (row, col, value bits, group index, position) in the
-    order the kernel consumes them.  Also checks the structural invariants of the
-    format and raises AssertionError on any violation."""
+    """Chunk arrays -> (row, col, value bits) arrays in the order the kernel
+    consumes them.  Also checks the structural invariants of the format and
+    raises AssertionError on any violation."""
+    check_blocks(items)
     items = items.reshape(-1, ITEM_WORDS)
     out_rows, out_cols, out_bits = [], [], []
-    for gi, it in enumerate(items):
+    for it in items:
         row0, nrows, chunk0, nchunks, vals0, flags = (int(x) for x in it[:6])
-        assert nchunks >= 1
+        if flags & FLAG_IDLE:
+            continue
         v = vals0
         row = row0
         rows_left = nrows
@@ -91,55 +139,56 @@ def decode_plan(items, hdr, cols, vals):
             if end:
                 row += rows_here
                 rows_left -= rows_here
-        assert rows_left == 0 or (flags & 1), "whole-panel groups end with their last panel"
-        if flags & 1:
-            assert nrows <= UFI and rows_left == 0
+        assert rows_left == 0
+        if flags & FLAG_SPLIT:
+            assert nrows <= UFI
     return (np.array(out_rows, dtype=np.int64), np.array(out_cols, dtype=np.int64),
             np.array(out_bits, dtype=np.uint32))
 
 
 def interpret_plan(items, hdr, cols, vals, B, M):
-    """Evaluates C from the chunk arrays in float32, chunk by chunk, FMA by FMA in
-    the kernel's order (row blocks in ascending row, slots in ascending order;
-    pieces of a split panel summed in piece order)."""
-    items = items.reshape(-1, ITEM_WORDS)
+    """Evaluates C from the chunk arrays in float32, block by block, chunk by
+    chunk, FMA by FMA in the kernel's order (row blocks in ascending row, slots in
+    ascending order; pieces of a split panel added in slot order by the wave slot
+    the table names)."""
+    blocks = items.reshape(-1, WAVES_PER_WG, ITEM_WORDS)
     N = B.shape[1]
     C = np.full((M, N), np.nan, dtype=np.float32)
-    partial = {}
     fvals = vals.view(np.float32)
     B64 = B.astype(np.float64)
-    for it in items:
-        row0, nrows, chunk0, nchunks, vals0, flags, ticket, nseg, slot0, seg = (int(x) for x in it[:10])
-        acc = np.zeros((UFI, N), dtype=np.float32)
-        v = vals0
-        row, rows_left = row0, nrows
-        for c in range(chunk0, chunk0 + nchunks):
-            h = int(hdr[c])
-            pattern, end = h & 15, (h >> 8) & 1
-            cc = cols[c * UFK:(c + 1) * UFK]
-            for r in range(UFI):
-                if not (pattern >> r) & 1:
-                    continue
-                for u in range(UFK):
-                    a = np.float64(fvals[v + u])
-                    # fused multiply-add in float32: exact product and sum in double, one rounding
-                    acc[r] = (a * B64[cc[u]] + acc[r].astype(np.float64)).astype(np.float32)
-                v += UFK
-            if end:
-                rows_here = min(UFI, rows_left)
-                if flags & 1:
-                    partial.setdefault(ticket, {})[seg] = (acc.copy(), row, rows_here, nseg)
-                else:
-                    C[row:row + rows_here] = acc[:rows_here]
-                row += rows_here
-                rows_left -= rows_here
-                acc[:] = 0
-    for ticket, pieces in partial.items():
-        nseg = next(iter(pieces.values()))[3]
-        assert sorted(pieces) == list(range(nseg))
-        total = np.zeros((UFI, N), dtype=np.float32)
-        for s in range(nseg):
-            total = total + pieces[s][0]
-        _, row, rows_here, _ = pieces[0]
-        C[row:row + rows_here] = total[:rows_here]
+    for blk in blocks:
+        tiles = np.zeros((WAVES_PER_WG, UFI, N), dtype=np.float32)
+        for w, it in enumerate(blk):
+            row0, nrows, chunk0, nchunks, vals0, flags = (int(x) for x in it[:6])
+            acc = np.zeros((UFI, N), dtype=np.float32)
+            v = vals0
+            row, rows_left = row0, nrows
+            for c in range(chunk0, chunk0 + nchunks):
+                h = int(hdr[c])
+                pattern, end = h & 15, (h >> 8) & 1
+                cc = cols[c * UFK:(c + 1) * UFK]
+                for r in range(UFI):
+                    if not (pattern >> r) & 1:
+                        continue
+                    for u in range(UFK):
+                        a = np.float64(fvals[v + u])
+                        # fused multiply-add: exact product and sum in double, one rounding
+                        acc[r] = (a * B64[cc[u]] + acc[r].astype(np.float64)).astype(np.float32)
+                    v += UFK
+                if end:
+                    rows_here = min(UFI, rows_left)
+                    if flags & FLAG_SPLIT:
+                        tiles[w] = acc
+                    else:
+                        C[row:row + rows_here] = acc[:rows_here]
+                    row += rows_here
+                    rows_left -= rows_here
+                    acc[:] = 0
+        for it in blk:
+            nseg, slot0, r, crow = (int(x) for x in it[6:10])
+            if int(it[5]) & FLAG_SYNC and nseg:
+                total = np.zeros(N, dtype=np.float32)
+                for p in range(nseg):
+                    total = total + tiles[slot0 + p, r]
+                C[crow] = total
     return C

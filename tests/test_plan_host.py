@@ -80,24 +80,31 @@ def test_row_groups_match_python_rederivation(name, group_nnz):
     want = derive_groups(csr.row_ptr, csr.M, info["group_nnz"], info["group_panels"])
     assert got.shape == want.shape and np.array_equal(got, want)
     assert info["n_groups"] == len(want) and info["n_split"] == int((want[:, 4] & 1).sum())
+    assert info["n_blocks"] * 16 * 16 == len(plan.get_array(spmm.ARRAY_ITEMS))
     # invariants: whole rows and the whole nonzero range are covered exactly once
     by_row = got[np.lexsort((got[:, 2], got[:, 0]))]
     nnz_cover = 0
     next_row = 0
     for rb, re_, nb, ne, fl in by_row:
-        assert ne - nb <= info["group_nnz"] and ne >= nb
+        assert ne >= nb
         if fl & 1:
             assert re_ - rb <= UFI and rb % UFI == 0 and ne > nb
             assert rb in (next_row, next_row - (re_ - rb))  # pieces share their panel's rows
+            pn = int(csr.row_ptr[re_] - csr.row_ptr[rb])
+            assert pn > info["group_nnz"]
+            assert ne - nb <= max(info["group_nnz"], -(-pn // 16))
         else:
             assert rb == next_row and rb % UFI == 0
             assert (nb, ne) == (csr.row_ptr[rb], csr.row_ptr[re_])
+            assert ne - nb <= info["group_nnz"]
         assert nb == nnz_cover
         nnz_cover = ne
         next_row = re_
     assert next_row == csr.M and nnz_cover == csr.row_ptr[-1]
-    sizes = got[:, 3] - got[:, 2]
-    assert np.all(np.diff(sizes) <= 0), "launch order is heaviest first"
+    whole = got[(got[:, 4] & 1) == 0]
+    assert np.all(np.diff(whole[:, 3] - whole[:, 2]) <= 0), "whole-panel groups: heaviest first"
+    n_split = int((got[:, 4] & 1).sum())
+    assert np.all((got[:n_split, 4] & 1) == 1), "pieces of split panels come first"
 
 
 def test_default_group_budget_rule():
