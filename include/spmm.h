@@ -48,7 +48,7 @@ typedef struct {
     int64_t n_split;       /* row groups that are pieces of a panel too heavy for one group */
     int64_t n_enum;        /* enumerated columns: B rows a column tile must fetch per execute */
     int64_t n_chunks;      /* chunks: runs of at most ufk enumerated columns of one pattern */
-    int64_t vals_words;    /* 32-bit words of the schedule-ordered value array (with padding) */
+    int64_t stream_words;  /* 32-bit words of the chunk records (column indices and values, with padding) */
     int64_t device_bytes;  /* device memory the plan holds (0 for a host-only plan) */
 } spmm_plan_info_t;
 
@@ -131,23 +131,26 @@ spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_
 /*
  * Raw copies of the plan's schedule-ordered arrays (host mirror), for format
  * round-trip tests and byte accounting.  Layouts are those the kernels read:
- *   SPMM_ARRAY_HDR    one word per chunk: bits 0-3 pattern (panel rows present in
- *                     every column of the chunk), bits 4-7 number of real columns,
- *                     bit 8 last chunk of its panel
- *   SPMM_ARRAY_COLS   ufk words per chunk: column index per slot (unused slots
- *                     repeat a real column)
- *   SPMM_ARRAY_VALS   per chunk, one block of ufk float bit patterns per set pattern
- *                     row in ascending row order (zeros in unused slots)
- *   SPMM_ARRAY_ITEMS  16 words per wave slot, 16 slots per workgroup, launch order:
- *                     first row, rows, first chunk, chunks, first value word, flags
- *                     (1 piece of a split panel, 2 idle slot, 4 workgroup with split
- *                     panels), then the slot's share of the split-panel sums: pieces
- *                     to add, first piece's slot, tile row, row of C
+ *   SPMM_ARRAY_HDR     one word per chunk: bits 0-3 pattern (panel rows present in
+ *                      every column of the chunk), bits 4-7 number of real columns,
+ *                      bit 8 last chunk of its panel
+ *   SPMM_ARRAY_STREAM  one record per chunk, back to back: ufk column indices (unused
+ *                      slots repeat a real column), then one block of ufk float bit
+ *                      patterns per set pattern row in ascending row order (zeros in
+ *                      unused slots)
+ *   SPMM_ARRAY_WINS    one word per LDS staging window of a group: bits 0-15 chunks,
+ *                      bits 16-31 record words (at most 1024)
+ *   SPMM_ARRAY_ITEMS   16 words per wave slot, 16 slots per workgroup, launch order:
+ *                      first row, rows, first chunk, chunks, first record word, flags
+ *                      (1 piece of a split panel, 2 idle slot, 4 workgroup with split
+ *                      panels), the slot's share of the split-panel sums (pieces to
+ *                      add, first piece's slot, tile row, row of C), first window,
+ *                      windows
  *   out   HOST, cap_words 32-bit words of room; *n_words (may be NULL) receives the
  *         array's length.  out == NULL only queries the length.  A too small
  *         cap_words copies nothing and returns SPMM_ERR_INVALID_ARG.
  */
-enum { SPMM_ARRAY_HDR = 0, SPMM_ARRAY_COLS = 1, SPMM_ARRAY_VALS = 2, SPMM_ARRAY_ITEMS = 3 };
+enum { SPMM_ARRAY_HDR = 0, SPMM_ARRAY_STREAM = 1, SPMM_ARRAY_WINS = 2, SPMM_ARRAY_ITEMS = 3 };
 spmm_status_t spmm_plan_get_array(const spmm_plan_t *plan, int32_t which,
                                   uint32_t *out, int64_t cap_words, int64_t *n_words);
 

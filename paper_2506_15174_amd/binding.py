@@ -19,7 +19,7 @@ SPMM_ERR_ALLOC = 3
 SPMM_ERR_HIP = 4
 SPMM_ERR_UNSUPPORTED = 5
 
-ARRAY_HDR, ARRAY_COLS, ARRAY_VALS, ARRAY_ITEMS = 0, 1, 2, 3
+ARRAY_HDR, ARRAY_STREAM, ARRAY_WINS, ARRAY_ITEMS = 0, 1, 2, 3
 
 EXPORTS = ("spmm_plan_create", "spmm_plan_create_ex", "spmm_execute",
            "spmm_plan_destroy", "spmm_plan_describe", "spmm_plan_get_groups",
@@ -33,7 +33,7 @@ class PlanInfo(ctypes.Structure):
                 ("n_groups", ctypes.c_int64), ("n_blocks", ctypes.c_int64),
                 ("n_split", ctypes.c_int64),
                 ("n_enum", ctypes.c_int64), ("n_chunks", ctypes.c_int64),
-                ("vals_words", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
+                ("stream_words", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
 
     def as_dict(self):
         return {name: int(getattr(self, name)) for name, _ in self._fields_}

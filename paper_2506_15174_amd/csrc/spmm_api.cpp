@@ -18,7 +18,7 @@ struct spmm_plan {
     HostPlan host;
     bool on_device = false;
     int device = -1;
-    uint32_t *d_hdr = nullptr, *d_cols = nullptr, *d_vals = nullptr, *d_items = nullptr;
+    uint32_t *d_hdr = nullptr, *d_stream = nullptr, *d_wins = nullptr, *d_items = nullptr;
     int64_t device_bytes = 0;
     bool force_wide = false;  // test hook: exercise the 64-bit addressing kernels on small inputs
 };
@@ -62,10 +62,10 @@ spmm_status_t upload(T **dst, const void *src, size_t bytes, int64_t &total)
 void release_device(spmm_plan *p)
 {
     if (p->d_hdr) (void)hipFree(p->d_hdr);
-    if (p->d_cols) (void)hipFree(p->d_cols);
-    if (p->d_vals) (void)hipFree(p->d_vals);
+    if (p->d_stream) (void)hipFree(p->d_stream);
+    if (p->d_wins) (void)hipFree(p->d_wins);
     if (p->d_items) (void)hipFree(p->d_items);
-    p->d_hdr = p->d_cols = p->d_vals = p->d_items = nullptr;
+    p->d_hdr = p->d_stream = p->d_wins = p->d_items = nullptr;
     (void)hipGetLastError();
 }
 
@@ -104,8 +104,8 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
         const HostPlan &h = p->host;
         spmm_status_t st = SPMM_OK;
         if (st == SPMM_OK) st = upload(&p->d_hdr, h.hdr.data(), h.hdr.size() * 4, p->device_bytes);
-        if (st == SPMM_OK) st = upload(&p->d_cols, h.cols.data(), h.cols.size() * 4, p->device_bytes);
-        if (st == SPMM_OK) st = upload(&p->d_vals, h.vals.data(), h.vals.size() * 4, p->device_bytes);
+        if (st == SPMM_OK) st = upload(&p->d_stream, h.stream.data(), h.stream.size() * 4, p->device_bytes);
+        if (st == SPMM_OK) st = upload(&p->d_wins, h.wins.data(), h.wins.size() * 4, p->device_bytes);
         if (st == SPMM_OK) st = upload(&p->d_items, h.items.data(), h.items.size() * 4, p->device_bytes);
         if (st != SPMM_OK) {
             release_device(p);
@@ -135,25 +135,38 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
     if (((uintptr_t)B & 3u) || ((uintptr_t)C & 3u)) return SPMM_ERR_INVALID_ARG;
 
     const uint64_t b_total = (uint64_t)h.K * (uint64_t)N * 4u;
-    const bool wide = b_total > 0xFFFFFFFFull || (plan->force_wide && b_total > 0);
-    // Two columns per lane need 8-byte aligned rows; up to 64 columns fit one per lane.
-    const bool pairs = N > 64 && (N % 2 == 0) && !((uintptr_t)B & 7u) && !((uintptr_t)C & 7u);
-    const int vw = pairs ? 2 : 1;
-    const int32_t tile = 64 * vw;
+    // Narrow addressing: 32-bit byte offsets into B formed by a 24 x 24-bit multiply.
+    const bool narrow_ok = b_total <= 0xFFFFFFFFull && h.K < (1 << 24) && (uint64_t)N * 4u < (1u << 24);
+    const bool wide = !narrow_ok || (plan->force_wide && b_total > 0);
+    // Four columns per lane need 16-byte aligned rows.
+    const bool quads = (N % 4 == 0) && !((uintptr_t)B & 15u) && !((uintptr_t)C & 15u);
     spmm_launch_args a;
     a.hdr = plan->d_hdr;
-    a.cols = plan->d_cols;
-    a.vals = plan->d_vals;
+    a.stream = plan->d_stream;
+    a.wins = plan->d_wins;
     a.items = plan->d_items;
     a.n_blocks = (int32_t)h.n_blocks;
     a.ldn = N;
-    for (int32_t j0 = 0; j0 < N; j0 += tile) {
+    // Column tiles run one after another on the stream.
+    int32_t j0 = 0;
+    while (j0 < N) {
+        const int32_t left = N - j0;
+        int slices;
+        int32_t tile;
+        if (quads) {
+            slices = left > 64 ? 2 : left > 32 ? 4 : 8;
+            tile = 256 / slices;
+        } else {
+            slices = 1;
+            tile = 64;
+        }
         a.B = B ? B + j0 : nullptr;
         a.C = C + j0;
-        a.width = (N - j0 < tile) ? N - j0 : tile;
+        a.width = left < tile ? left : tile;
         a.b_bytes = wide ? 0u : (uint32_t)(b_total - (uint64_t)j0 * 4u);
-        const int e = spmm_launch_chunks(a, vw, wide, stream);
+        const int e = spmm_launch_chunks(a, slices, wide, stream);
         if (e != 0) return SPMM_ERR_HIP;
+        j0 += a.width;
     }
     return SPMM_OK;
 }
@@ -183,7 +196,7 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
     out->n_split = h.n_split;
     out->n_enum = h.n_enum;
     out->n_chunks = h.n_chunks;
-    out->vals_words = (int64_t)h.vals.size();
+    out->stream_words = (int64_t)h.stream.size();
     out->device_bytes = plan->device_bytes;
     return SPMM_OK;
 }
@@ -206,8 +219,8 @@ spmm_status_t spmm_plan_get_array(const spmm_plan_t *plan, int32_t which, uint32
     const std::vector<uint32_t> *v = nullptr;
     switch (which) {
     case SPMM_ARRAY_HDR: v = &h.hdr; break;
-    case SPMM_ARRAY_COLS: v = &h.cols; break;
-    case SPMM_ARRAY_VALS: v = &h.vals; break;
+    case SPMM_ARRAY_STREAM: v = &h.stream; break;
+    case SPMM_ARRAY_WINS: v = &h.wins; break;
     case SPMM_ARRAY_ITEMS: v = &h.items; break;
     default: return SPMM_ERR_INVALID_ARG;
     }

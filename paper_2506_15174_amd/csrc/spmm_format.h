@@ -26,31 +26,38 @@ constexpr int N_PATTERNS = (1 << UFI) - 1;  // 15 nonzero patterns (paper Sectio
 // Enumerated columns per chunk (the paper's UFk).
 constexpr int UFK = 8;
 
-// Three parallel arrays describe the chunks, in launch order of their groups:
+// The chunks of a row group are described by two arrays, in launch order of
+// their groups:
 //
-//   hdr[c]            one word:  bits 0..3  pattern (rows of the panel that own a value
-//                                           in every column of the chunk), 0 only for
-//                                           the single chunk of a panel without nonzeros
-//                                bits 4..7  count of real columns, 0..UFK
-//                                bit  8     last chunk of its panel (store the tile)
-//   cols[c*UFK + u]   column index of slot u; slots >= count repeat a valid column
-//                     of the chunk (or 0) and carry zero values
-//   vals              for chunk c, popcount(pattern) blocks of UFK floats, one block
-//                     per set row in ascending row order, block[u] = value of that
-//                     row in column slot u (zero in unused slots); chunks follow each
-//                     other without gaps, so a chunk's block offset is the running
-//                     sum of UFK * popcount(pattern)
+//   hdr[c]     one word:  bits 0..3  pattern (rows of the panel that own a value in
+//                                    every column of the chunk), 0 only for the
+//                                    single chunk of a panel without nonzeros
+//                         bits 4..7  count of real columns, 0..UFK
+//                         bit  8     last chunk of its panel (write the tile)
+//   stream     one record per chunk, records back to back:
+//                UFK column indices (slots >= count repeat a valid column of the
+//                chunk, or 0, and carry zero values), then for every set row of
+//                the pattern in ascending row order UFK value words (float bits,
+//                value of that row in column slot u; zero in unused slots).
+//              A record therefore has UFK * (1 + popcount(pattern)) words and a
+//              chunk's record offset is the running sum of those sizes.
+//
+// A group's records are staged through LDS in *windows* of at most WIN_WORDS
+// words; a record never straddles two windows.
+//   wins[i]    one word per window: bits 0..15 chunks, bits 16..31 words
 constexpr uint32_t HDR_PATTERN_MASK = 0xFu;
 constexpr int HDR_COUNT_SHIFT = 4;
 constexpr uint32_t HDR_COUNT_MASK = 0xFu;
 constexpr uint32_t HDR_END_PANEL = 1u << 8;
 
-// Chunks (all zero) appended after the last real chunk so that the kernels'
-// look-ahead of four chunks never leaves the arrays.
-constexpr int CHUNK_TAIL_PAD = 8;
-// Zero words appended to vals so that the four per-row block loads of a chunk
-// stay inside the array whatever its pattern.
-constexpr int VALS_TAIL_PAD = UFI * UFK;
+// Words of LDS one wave owns (its window; later its partial tile).
+constexpr int WIN_WORDS = 1024;
+
+// Headers (all zero) appended after the last real chunk so that the kernels'
+// look-ahead never leaves the array.
+constexpr int CHUNK_TAIL_PAD = 16;
+// Zero words appended to the stream.
+constexpr int STREAM_TAIL_PAD = 16;
 
 // Waves per workgroup.  One wave executes one row group; a workgroup ("block")
 // holds up to WAVES_PER_WG of them.  A panel too heavy for one wave is cut into
@@ -67,12 +74,14 @@ enum ItemField {
     IT_NROWS = 1,     // rows covered (whole panels; the last may be short)
     IT_CHUNK0 = 2,    // first chunk
     IT_NCHUNKS = 3,   // chunks of the group (0 for an idle slot)
-    IT_VALS0 = 4,     // first word of the group's values
+    IT_STREAM0 = 4,   // first word of the group's records
     IT_FLAGS = 5,     // FLAG_* bits
     IT_RED_NSEG = 6,  // after the barrier: pieces to add (0 = this wave adds nothing)
     IT_RED_SLOT0 = 7, // ... wave slot of the first piece
     IT_RED_R = 8,     // ... row of the tile to add
-    IT_RED_ROW = 9    // ... row of C to write
+    IT_RED_ROW = 9,   // ... row of C to write
+    IT_WIN0 = 10,     // first window of the group
+    IT_NWINS = 11     // windows of the group (0 for an idle slot)
 };
 constexpr int FLAG_SPLIT = 1;  // the group is one piece of a split panel: its tile goes to LDS
 constexpr int FLAG_IDLE = 2;   // no group in this wave slot

@@ -7,19 +7,21 @@
 
 struct spmm_launch_args {
     const uint32_t *hdr;    // DEVICE chunk headers
-    const uint32_t *cols;   // DEVICE chunk column slots
-    const uint32_t *vals;   // DEVICE chunk value blocks (float bits)
+    const uint32_t *stream; // DEVICE chunk records (column indices and value bits)
+    const uint32_t *wins;   // DEVICE staging windows
     const uint32_t *items;  // DEVICE wave-slot descriptors, 16 per block
     int32_t n_blocks;       // workgroups to launch
     const float *B;         // DEVICE first column of the column tile
     uint32_t b_bytes;       // bytes of B reachable from that pointer (narrow addressing only)
     float *C;               // DEVICE first column of the column tile
     int32_t ldn;            // leading dimension of B and C (= N)
-    int32_t width;          // columns in this tile (<= 64 * vw)
+    int32_t width;          // columns in this tile
 };
 
-// Enqueues one column tile.  vw = columns per lane (1 or 2); wide = byte offsets
-// into B exceed 32 bits.  Returns the hipError_t of the launch as int.
-int spmm_launch_chunks(const spmm_launch_args &a, int vw, bool wide, void *stream);
+// Enqueues one column tile.  slices = 2 / 4 / 8: four columns per lane, tile of up
+// to 128 / 64 / 32 columns (width a multiple of 4, B and C 16-byte aligned);
+// slices = 1: one column per lane, tile of up to 64 columns, any alignment.
+// wide = 64-bit addressing of B.  Returns the hipError_t of the launch as int.
+int spmm_launch_chunks(const spmm_launch_args &a, int slices, bool wide, void *stream);
 
 #endif

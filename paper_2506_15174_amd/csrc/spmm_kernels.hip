@@ -1,29 +1,35 @@
 // gfx950 executor: C <- A x B over the chunked, schedule-ordered arrays built by
 // the inspector (paper Section 3.3 "Sparse Coarsen", Listings 5-7, re-derived
-// for wave64).
+// for wave64 and for the memory paths of a CDNA4 compute unit).
 //
-// Mapping (one wave = one row group, up to 16 waves per workgroup):
-//   * lanes run along j, the columns of B and C (the paper's map(j, .),
-//     Listing 5): lane l owns columns VW*l .. VW*l+VW-1 of the current column
-//     tile, so one wave-wide load fetches a whole B row segment, coalesced;
-//   * the UFI x VW accumulators of a panel stay in VGPRs across all chunks of
-//     the panel (the paper's register tile, Listing 6) and are written once;
-//   * everything that describes A -- chunk headers, column indices, values -- is
-//     identical for all lanes, so it is fetched with scalar loads into SGPRs; the
-//     values feed v_fmac_f32 as scalar operands and the row offsets feed the
-//     buffer loads as scalar offsets.  No lane ever tests a sparsity condition
-//     (Section 3.2.2: enumerated blocks carry no conditionals): the pattern of a
-//     chunk selects, with wave-uniform branches, which of the UFI row blocks run;
-//   * a chunk is UFK enumerated columns of one pattern: UFK independent B loads,
-//     then popcount(pattern) x UFK x VW FMAs (the paper's unroll(k, UFk)).  The
-//     loop is software-pipelined three chunks deep: while chunk c is multiplied,
-//     the B rows of chunks c+1 and c+2 are in flight and the descriptors of
-//     chunks c+3 and c+4 are on their way;
-//   * pieces of a panel that was too heavy for one wave sit in the same
-//     workgroup: they park their partial tiles in LDS, meet at one barrier and
-//     one wave per tile row adds the pieces in piece order (the paper's
-//     write-after-write hazard, Section 3.3.2, solved without atomics and with a
-//     fixed summation order).
+// One wave executes one row group; up to 16 waves form a workgroup.
+//
+//   * Lanes run along j, the columns of B and C (the paper's map(j, .),
+//     Listing 5).  A vector load costs the compute unit's address path the same
+//     ~16 cycles whether a lane asks for 4, 8 or 16 bytes, so every lane asks for
+//     16 (four columns).  A column tile of 128 / 64 / 32 columns then needs only
+//     32 / 16 / 8 lanes, and the wave is cut into S = 2 / 4 / 8 *slices* that work
+//     on different enumerated columns of the same chunk (the paper's map(k, .)
+//     inside a warp, Section 3.3.1); their partial tiles are added across lanes
+//     when a panel ends (the warp-level reduction of Section 3.3.2).
+//   * The UFI x 4 accumulators of a panel stay in VGPRs across all chunks of the
+//     panel (the paper's register tile, Listing 6).
+//   * A chunk is UFK = 8 enumerated columns of one nonzero pattern.  Its column
+//     indices and values are staged through LDS, a window of the group's stream
+//     at a time, with coalesced 16-byte loads (the scalar data path tops out far
+//     below what the stream needs); a slice reads its own slots back with one
+//     broadcast LDS read per row of the pattern.  Only the one-word chunk headers
+//     travel through scalar loads: the pattern selects, with wave-uniform
+//     branches, which of the UFI row blocks run, so no lane ever tests a
+//     sparsity condition (Section 3.2.2: enumerated blocks carry no
+//     conditionals).
+//   * The chunk loop is software-pipelined D chunks deep (the paper's
+//     unroll(k, UFk) for loads in flight, Section 3.3.2): while chunk c is
+//     multiplied the B rows of chunks c+1 .. c+D-1 are in flight.
+//   * Pieces of a panel that was too heavy for one wave sit in one workgroup:
+//     they park their partial tiles in LDS, meet at one barrier and one wave per
+//     tile row adds the pieces in piece order (the write-after-write hazard of
+//     Section 3.3.2, solved without atomics and with a fixed summation order).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -38,206 +44,277 @@ namespace {
 // address space are issued as s_load_* when the address is uniform.
 typedef const uint32_t __attribute__((address_space(4))) cword_t;
 
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <int VW> struct Vec;
-template <> struct Vec<1> { typedef float type; };
-template <> struct Vec<2> { typedef float2 type; };
+template <> struct Vec<1> {
+    typedef float type;
+    static __device__ __forceinline__ type zero() { return 0.0f; }
+};
+template <> struct Vec<4> {
+    typedef float4 type;
+    static __device__ __forceinline__ type zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+};
 
 __device__ __forceinline__ void fma_acc(float &acc, float a, float b) { acc = __builtin_fmaf(a, b, acc); }
-__device__ __forceinline__ void fma_acc(float2 &acc, float a, float2 b)
+__device__ __forceinline__ void fma_acc(float4 &acc, float a, const float4 &b)
 {
     acc.x = __builtin_fmaf(a, b.x, acc.x);
     acc.y = __builtin_fmaf(a, b.y, acc.y);
+    acc.z = __builtin_fmaf(a, b.z, acc.z);
+    acc.w = __builtin_fmaf(a, b.w, acc.w);
 }
-__device__ __forceinline__ void zero(float &v) { v = 0.0f; }
-__device__ __forceinline__ void zero(float2 &v) { v.x = 0.0f; v.y = 0.0f; }
 __device__ __forceinline__ void add_to(float &a, float b) { a += b; }
-__device__ __forceinline__ void add_to(float2 &a, float2 b) { a.x += b.x; a.y += b.y; }
+__device__ __forceinline__ void add_to(float4 &a, const float4 &b)
+{
+    a.x += b.x;
+    a.y += b.y;
+    a.z += b.z;
+    a.w += b.w;
+}
+template <int MASK> __device__ __forceinline__ void add_across(float &a) { a += __shfl_xor(a, MASK); }
+template <int MASK> __device__ __forceinline__ void add_across(float4 &a)
+{
+    a.x += __shfl_xor(a.x, MASK);
+    a.y += __shfl_xor(a.y, MASK);
+    a.z += __shfl_xor(a.z, MASK);
+    a.w += __shfl_xor(a.w, MASK);
+}
 
 // Source of B rows.  Narrow: a raw buffer descriptor over the column tile's
-// bytes (hardware range check, scalar row offset, per-lane byte offset).  Wide:
-// plain 64-bit addressing for B larger than 4 GiB.
+// bytes (hardware range check, 32-bit per-lane byte offset).  Wide: plain 64-bit
+// addressing for B beyond the narrow limits.
 template <bool WIDE> struct BSource;
 
 template <> struct BSource<false> {
     __amdgpu_buffer_rsrc_t rsrc;
-    uint32_t lane_off;
-    __device__ __forceinline__ void init(const float *B, uint32_t lane_off_, uint32_t n_bytes)
+    __device__ __forceinline__ void init(const float *B, uint32_t n_bytes)
     {
         // word 3: 32-bit data format, raw (untyped, stride 0) addressing
         rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(B), 0, (int)n_bytes, 0x00020000);
-        lane_off = lane_off_;
     }
-    __device__ __forceinline__ float load(uint32_t col, uint32_t ld_bytes, float) const
+    // byte offset of a lane's segment: row pitch and column index both below 2^24
+    static __device__ __forceinline__ uint32_t offset(uint32_t col, uint32_t ld_bytes, uint32_t lane_off)
     {
-        return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, lane_off, col * ld_bytes, 0));
+        return __umul24(col, ld_bytes) + lane_off;
     }
-    __device__ __forceinline__ float2 load(uint32_t col, uint32_t ld_bytes, float2) const
+    typedef uint32_t off_t;
+    __device__ __forceinline__ float load(uint32_t off, float) const
     {
-        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, lane_off, col * ld_bytes, 0);
-        return make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
+        return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, 0));
+    }
+    __device__ __forceinline__ float4 load(uint32_t off, float4) const
+    {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
+        return make_float4(__uint_as_float(v[0]), __uint_as_float(v[1]), __uint_as_float(v[2]),
+                           __uint_as_float(v[3]));
     }
 };
 
 template <> struct BSource<true> {
     const char *base;
-    uint32_t lane_off;
-    __device__ __forceinline__ void init(const float *B, uint32_t lane_off_, uint32_t)
+    __device__ __forceinline__ void init(const float *B, uint32_t) { base = reinterpret_cast<const char *>(B); }
+    static __device__ __forceinline__ uint64_t offset(uint32_t col, uint32_t ld_bytes, uint32_t lane_off)
     {
-        base = reinterpret_cast<const char *>(B);
-        lane_off = lane_off_;
+        return (uint64_t)col * (uint64_t)ld_bytes + lane_off;
     }
-    __device__ __forceinline__ float load(uint32_t col, uint32_t ld_bytes, float) const
+    typedef uint64_t off_t;
+    __device__ __forceinline__ float load(uint64_t off, float) const
     {
-        return *reinterpret_cast<const float *>(base + (uint64_t)col * ld_bytes + lane_off);
+        return *reinterpret_cast<const float *>(base + off);
     }
-    __device__ __forceinline__ float2 load(uint32_t col, uint32_t ld_bytes, float2) const
+    __device__ __forceinline__ float4 load(uint64_t off, float4) const
     {
-        return *reinterpret_cast<const float2 *>(base + (uint64_t)col * ld_bytes + lane_off);
+        return *reinterpret_cast<const float4 *>(base + off);
     }
 };
 
-struct ChunkDesc {
-    uint32_t hdr;
-    uint32_t col[UFK];
-};
-
-__device__ __forceinline__ void fetch_desc(ChunkDesc &d, cword_t *hdrs, cword_t *cols, uint32_t c)
+// Q consecutive words of this wave's LDS window, starting at word `at`.
+template <int Q> __device__ __forceinline__ void lds_read(uint32_t (&out)[Q], const uint32_t *win, uint32_t at)
 {
-    d.hdr = hdrs[c];
-#pragma unroll
-    for (int u = 0; u < UFK; ++u) d.col[u] = cols[(size_t)c * UFK + u];
-}
-
-// Requests the UFK B rows of one chunk.  ld_bytes is the row pitch, or 0 for a
-// chunk past the group's end: then every slot reads row 0 (one cached line per
-// lane group), so the loop needs no conditional loads and its wait counts stay
-// exact.
-template <int VW, bool WIDE>
-__device__ __forceinline__ void issue_b(typename Vec<VW>::type (&b)[UFK], const ChunkDesc &d,
-                                        const BSource<WIDE> &src, uint32_t ld_bytes)
-{
-    typedef typename Vec<VW>::type vec_t;
-#pragma unroll
-    for (int u = 0; u < UFK; ++u) b[u] = src.load(d.col[u], ld_bytes, vec_t());
-}
-
-// The enumerated block of one chunk (paper Listing 7): for every row r of the
-// pattern, UFK FMAs per lane column with the row's values as scalar operands.
-// Returns the number of value words the chunk owns.
-template <int VW>
-__device__ __forceinline__ uint32_t
-fma_chunk(typename Vec<VW>::type (&acc)[UFI], const typename Vec<VW>::type (&b)[UFK], uint32_t hdr,
-          cword_t *vals)
-{
-    const uint32_t pattern = hdr & HDR_PATTERN_MASK;
-#pragma unroll
-    for (int r = 0; r < UFI; ++r) {
-        if (pattern & (1u << r)) {
-            // value block of row r: UFK words per set row below r
-            const uint32_t below = __builtin_popcount(pattern & ((1u << r) - 1u));
-            uint32_t w[UFK];
-#pragma unroll
-            for (int u = 0; u < UFK; ++u) w[u] = vals[below * UFK + u];
-#pragma unroll
-            for (int u = 0; u < UFK; ++u) fma_acc(acc[r], __uint_as_float(w[u]), b[u]);
-        }
+    if constexpr (Q == 8) {
+        const uint4 lo = *reinterpret_cast<const uint4 *>(win + at);
+        const uint4 hi = *reinterpret_cast<const uint4 *>(win + at + 4);
+        out[0] = lo.x; out[1] = lo.y; out[2] = lo.z; out[3] = lo.w;
+        out[4] = hi.x; out[5] = hi.y; out[6] = hi.z; out[7] = hi.w;
+    } else if constexpr (Q == 4) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(win + at);
+        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+    } else if constexpr (Q == 2) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(win + at);
+        out[0] = v.x; out[1] = v.y;
+    } else {
+        out[0] = win[at];
     }
-    return (uint32_t)__builtin_popcount(pattern) * UFK;
 }
 
-template <int VW>
-__device__ __forceinline__ void store_row(float *__restrict__ row, int lane, typename Vec<VW>::type v)
-{
-    *reinterpret_cast<typename Vec<VW>::type *>(row + lane * VW) = v;
-}
-
-// VW   columns per lane (1: tiles of up to 64 columns, 2: tiles of up to 128)
-// WIDE byte offsets into B need more than 32 bits
-template <int VW, bool WIDE>
+// S     slices per wave (1, 2, 4, 8); a slice has 64 / S lanes and UFK / S column slots per chunk
+// VW    columns per lane (4 with 16-byte loads; 1 for the generic path, S == 1 only)
+// D     chunks of B rows in flight per wave
+// WIDE  64-bit addressing of B
+template <int S, int VW, int D, bool WIDE>
 __global__ __launch_bounds__(64 * WAVES_PER_WG) void
-spmm_chunks_kernel(const uint32_t *__restrict__ hdr_g, const uint32_t *__restrict__ cols_g,
-                   const uint32_t *__restrict__ vals_g, const uint32_t *__restrict__ items_g,
+spmm_chunks_kernel(const uint32_t *__restrict__ hdr_g, const uint32_t *__restrict__ stream_g,
+                   const uint32_t *__restrict__ wins_g, const uint32_t *__restrict__ items_g,
                    const float *__restrict__ B, uint32_t b_bytes, float *__restrict__ C, int32_t ldn,
                    int32_t width)
 {
     typedef typename Vec<VW>::type vec_t;
-    // Partial tiles of split panels, one per wave slot.
-    __shared__ vec_t tiles[WAVES_PER_WG][UFI][64];
+    typedef typename BSource<WIDE>::off_t off_t;
+    constexpr int L = 64 / S;    // lanes per slice
+    constexpr int Q = UFK / S;   // column slots per slice and chunk
+    static_assert(UFK % S == 0 && VW * L * UFI * 4 <= WIN_WORDS * 4, "tile must fit the wave's window");
+
+    // Per wave: the staged window of its stream; later the partial tile of a split panel.
+    __shared__ __attribute__((aligned(16))) uint32_t lds[WAVES_PER_WG][WIN_WORDS];
 
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
+    const int slice = lane / L;
+    const int sl = lane % L;
     cword_t *it = (cword_t *)(items_g) + ((size_t)blockIdx.x * WAVES_PER_WG + wave) * ITEM_WORDS;
     const uint32_t flags = it[IT_FLAGS];
-    const uint32_t n_chunks = it[IT_NCHUNKS];
+    const uint32_t n_wins = it[IT_NWINS];
+    uint32_t *win = lds[wave];
 
     // Lanes beyond the tile width compute on the tile's first columns and store
     // nothing: no divergent control flow in the hot loop, no out-of-range access.
-    const bool active = lane * VW < width;
+    const bool active = sl * VW < width;
 
-    if (n_chunks != 0) {
+    if (n_wins != 0) {
         uint32_t row = it[IT_ROW0];
         uint32_t rows_left = it[IT_NROWS];
-        const uint32_t chunk0 = it[IT_CHUNK0];
-        cword_t *vals = (cword_t *)(vals_g) + it[IT_VALS0];
-        cword_t *hdrs = (cword_t *)(hdr_g) + chunk0;
-        cword_t *cols = (cword_t *)(cols_g) + (size_t)chunk0 * UFK;
+        cword_t *hdrs = (cword_t *)(hdr_g) + it[IT_CHUNK0];
+        cword_t *wins = (cword_t *)(wins_g) + it[IT_WIN0];
+        const uint32_t *stream = stream_g + (size_t)it[IT_STREAM0];
         const uint32_t ld_bytes = (uint32_t)ldn * 4u;
+        const uint32_t lane_off = active ? (uint32_t)(sl * VW * 4) : 0u;
+        const uint32_t slot0 = (uint32_t)(slice * Q);  // this slice's first column slot
         BSource<WIDE> src;
-        src.init(B, active ? (uint32_t)(lane * VW * 4) : 0u, b_bytes);
+        src.init(B, b_bytes);
 
         vec_t acc[UFI];
 #pragma unroll
-        for (int r = 0; r < UFI; ++r) zero(acc[r]);
+        for (int r = 0; r < UFI; ++r) acc[r] = Vec<VW>::zero();
 
-        // Three-deep rings, all indexed by (chunk number mod 3):
-        //   d[k % 3]  descriptor of chunk k, from its request until its B rows are requested
-        //   b[k % 3]  B rows of chunk k, from their request until the chunk is multiplied
-        //   h[k % 3]  header of chunk k, kept for the multiply step
-        ChunkDesc d[3];
-        vec_t b[3][UFK];
-        uint32_t h[3];
-        fetch_desc(d[0], hdrs, cols, 0);
-        fetch_desc(d[1], hdrs, cols, 1);
-        fetch_desc(d[2], hdrs, cols, 2);
-        issue_b<VW, WIDE>(b[0], d[0], src, ld_bytes);
-        h[0] = d[0].hdr;
-        fetch_desc(d[0], hdrs, cols, 3);
-        issue_b<VW, WIDE>(b[1], d[1], src, n_chunks > 1 ? ld_bytes : 0u);
-        h[1] = d[1].hdr;
+        for (uint32_t w = 0; w < n_wins; ++w) {
+            const uint32_t wd = wins[w];
+            const uint32_t wc = wd & 0xFFFFu;   // chunks in this window
+            const uint32_t ww = wd >> 16;       // words in this window
+            // ---- stage the window (the wave's LDS traffic is in order: no wait needed
+            //      between these writes and the reads below)
+            for (uint32_t i = (uint32_t)lane * 4u; i < ww; i += 256u)
+                *reinterpret_cast<uint4 *>(win + i) = *reinterpret_cast<const uint4 *>(stream + i);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        uint32_t c = 0;
-        bool more = true;
-        while (more) {
+            // ---- pipeline over the window's chunks.  Record of a chunk: 8 column
+            //      words, then 8 value words per row of its pattern.
+            vec_t b[D][Q];
+            off_t voff[Q];
+            uint32_t at_look = 0;   // record of the chunk whose columns are read next
+            uint32_t at_mul = 0;    // record of the chunk multiplied next
 #pragma unroll
-            for (int s = 0; s < 3; ++s) {
-                // step for chunk c (c % 3 == s)
-                issue_b<VW, WIDE>(b[(s + 2) % 3], d[(s + 2) % 3], src, c + 2 < n_chunks ? ld_bytes : 0u);
-                h[(s + 2) % 3] = d[(s + 2) % 3].hdr;
-                fetch_desc(d[(s + 1) % 3], hdrs, cols, c + 4);
-                vals += fma_chunk<VW>(acc, b[s], h[s], vals);
-                if (h[s] & HDR_END_PANEL) {
-                    const uint32_t rows_here = rows_left < (uint32_t)UFI ? rows_left : (uint32_t)UFI;
-                    if (flags & FLAG_SPLIT) {
+            for (int j = 0; j < D - 1; ++j) {
+                const uint32_t hj = hdrs[j];
+                uint32_t cv[Q];
+                lds_read<Q>(cv, win, at_look + slot0);
+                const uint32_t ld_eff = (uint32_t)j < wc ? ld_bytes : 0u;
 #pragma unroll
-                        for (int r = 0; r < UFI; ++r) tiles[wave][r][lane] = acc[r];
-                    } else if (active) {
-                        float *c_panel = C + (size_t)row * (size_t)ldn;
+                for (int q = 0; q < Q; ++q)
+                    b[j][q] = src.load(BSource<WIDE>::offset(cv[q], ld_eff, lane_off), vec_t());
+                at_look += (uint32_t)UFK * (1u + (uint32_t)__builtin_popcount(hj & HDR_PATTERN_MASK));
+            }
+            {
+                uint32_t cv[Q];
+                lds_read<Q>(cv, win, at_look + slot0);
+                const uint32_t ld_eff = (uint32_t)(D - 1) < wc ? ld_bytes : 0u;
 #pragma unroll
-                        for (int r = 0; r < UFI; ++r)
-                            if ((uint32_t)r < rows_here) store_row<VW>(c_panel + (size_t)r * ldn, lane, acc[r]);
+                for (int q = 0; q < Q; ++q) voff[q] = BSource<WIDE>::offset(cv[q], ld_eff, lane_off);
+                at_look += (uint32_t)UFK * (1u + (uint32_t)__builtin_popcount(hdrs[D - 1] & HDR_PATTERN_MASK));
+            }
+            uint32_t h_look = hdrs[D];  // header of the chunk whose columns are read in the next step
+            uint32_t h_mul = hdrs[0];   // header of the chunk multiplied in the next step
+
+            uint32_t c = 0;
+            bool more = true;
+            while (more) {
+#pragma unroll
+                for (int s = 0; s < D; ++s) {
+                    // step for chunk c (c % D == s): voff holds the offsets of chunk c+D-1
+#pragma unroll
+                    for (int q = 0; q < Q; ++q) b[(s + D - 1) % D][q] = src.load(voff[q], vec_t());
+                    // columns of chunk c+D for the next step; a chunk past the window's
+                    // end reads row 0 through a zero pitch (its columns are never used)
+                    uint32_t cv[Q];
+                    lds_read<Q>(cv, win, at_look + slot0);
+                    at_look += (uint32_t)UFK * (1u + (uint32_t)__builtin_popcount(h_look & HDR_PATTERN_MASK));
+                    const uint32_t ld_next = c + (uint32_t)D < wc ? ld_bytes : 0u;
+                    const uint32_t h_now = h_mul;
+                    h_look = hdrs[c + D + 1];
+                    h_mul = hdrs[c + 1];
+
+                    // the enumerated block of chunk c (paper Listing 7)
+                    const uint32_t pattern = h_now & HDR_PATTERN_MASK;
+                    uint32_t at_val = at_mul + (uint32_t)UFK + slot0;
+#pragma unroll
+                    for (int r = 0; r < UFI; ++r) {
+                        if (pattern & (1u << r)) {
+                            uint32_t a[Q];
+                            lds_read<Q>(a, win, at_val);
+#pragma unroll
+                            for (int q = 0; q < Q; ++q) fma_acc(acc[r], __uint_as_float(a[q]), b[s][q]);
+                            at_val += (uint32_t)UFK;
+                        }
                     }
-                    row += rows_here;
-                    rows_left -= rows_here;
+                    at_mul += (uint32_t)UFK * (1u + (uint32_t)__builtin_popcount(pattern));
+
 #pragma unroll
-                    for (int r = 0; r < UFI; ++r) zero(acc[r]);
-                }
-                if (++c >= n_chunks) {
-                    more = false;
-                    break;
+                    for (int q = 0; q < Q; ++q) voff[q] = BSource<WIDE>::offset(cv[q], ld_next, lane_off);
+
+                    if (h_now & HDR_END_PANEL) {
+                        // add the slices' partial tiles across lanes
+                        if constexpr (S >= 2) {
+#pragma unroll
+                            for (int r = 0; r < UFI; ++r) add_across<32>(acc[r]);
+                        }
+                        if constexpr (S >= 4) {
+#pragma unroll
+                            for (int r = 0; r < UFI; ++r) add_across<16>(acc[r]);
+                        }
+                        if constexpr (S >= 8) {
+#pragma unroll
+                            for (int r = 0; r < UFI; ++r) add_across<8>(acc[r]);
+                        }
+                        const uint32_t rows_here = rows_left < (uint32_t)UFI ? rows_left : (uint32_t)UFI;
+                        if (slice == 0) {
+                            if (flags & FLAG_SPLIT) {
+                                // the window is dead by now (a piece ends with its panel)
+#pragma unroll
+                                for (int r = 0; r < UFI; ++r)
+                                    *reinterpret_cast<vec_t *>(win + (r * L + sl) * VW) = acc[r];
+                            } else if (active) {
+                                float *c_panel = C + (size_t)row * (size_t)ldn + sl * VW;
+#pragma unroll
+                                for (int r = 0; r < UFI; ++r)
+                                    if ((uint32_t)r < rows_here)
+                                        *reinterpret_cast<vec_t *>(c_panel + (size_t)r * ldn) = acc[r];
+                            }
+                        }
+                        row += rows_here;
+                        rows_left -= rows_here;
+#pragma unroll
+                        for (int r = 0; r < UFI; ++r) acc[r] = Vec<VW>::zero();
+                    }
+                    if (++c >= wc) {
+                        more = false;
+                        break;
+                    }
                 }
             }
+            hdrs += wc;
+            stream += ww;
         }
     }
 
@@ -245,31 +322,32 @@ spmm_chunks_kernel(const uint32_t *__restrict__ hdr_g, const uint32_t *__restric
         // Every wave of a block with split panels arrives here exactly once.
         __syncthreads();
         const uint32_t nseg = it[IT_RED_NSEG];
-        if (nseg != 0 && active) {
-            const uint32_t slot0 = it[IT_RED_SLOT0];
+        if (nseg != 0 && slice == 0 && active) {
+            const uint32_t first = it[IT_RED_SLOT0];
             const uint32_t r = it[IT_RED_R];
-            vec_t sum;
-            zero(sum);
-            for (uint32_t p = 0; p < nseg; ++p) add_to(sum, tiles[slot0 + p][r][lane]);
-            store_row<VW>(C + (size_t)it[IT_RED_ROW] * (size_t)ldn, lane, sum);
+            vec_t sum = Vec<VW>::zero();
+            for (uint32_t p = 0; p < nseg; ++p)
+                add_to(sum, *reinterpret_cast<const vec_t *>(&lds[first + p][(r * L + sl) * VW]));
+            *reinterpret_cast<vec_t *>(C + (size_t)it[IT_RED_ROW] * (size_t)ldn + sl * VW) = sum;
         }
     }
 }
 
 }  // namespace
 
-#define SPMM_LAUNCH(VW, WIDE)                                                                         \
-    hipLaunchKernelGGL((spmm_chunks_kernel<VW, WIDE>), dim3((unsigned)a.n_blocks),                    \
-                       dim3(64 * WAVES_PER_WG), 0, (hipStream_t)stream, a.hdr, a.cols, a.vals,        \
+#define SPMM_LAUNCH(S, VW, D, WIDE)                                                                   \
+    hipLaunchKernelGGL((spmm_chunks_kernel<S, VW, D, WIDE>), dim3((unsigned)a.n_blocks),              \
+                       dim3(64 * WAVES_PER_WG), 0, (hipStream_t)stream, a.hdr, a.stream, a.wins,      \
                        a.items, a.B, a.b_bytes, a.C, a.ldn, a.width)
 
-int spmm_launch_chunks(const spmm_launch_args &a, int vw, bool wide, void *stream)
+int spmm_launch_chunks(const spmm_launch_args &a, int slices, bool wide, void *stream)
 {
     if (a.n_blocks <= 0) return 0;
-    if (vw == 2) {
-        if (wide) SPMM_LAUNCH(2, true); else SPMM_LAUNCH(2, false);
-    } else {
-        if (wide) SPMM_LAUNCH(1, true); else SPMM_LAUNCH(1, false);
+    switch (slices) {
+    case 2: if (wide) SPMM_LAUNCH(2, 4, 3, true); else SPMM_LAUNCH(2, 4, 3, false); break;
+    case 4: if (wide) SPMM_LAUNCH(4, 4, 6, true); else SPMM_LAUNCH(4, 4, 6, false); break;
+    case 8: if (wide) SPMM_LAUNCH(8, 4, 8, true); else SPMM_LAUNCH(8, 4, 8, false); break;
+    default: if (wide) SPMM_LAUNCH(1, 1, 3, true); else SPMM_LAUNCH(1, 1, 3, false); break;
     }
     return (int)hipGetLastError();
 }

@@ -16,8 +16,9 @@ struct HostPlan {
     // Wave-slot descriptors, ITEM_WORDS per slot, WAVES_PER_WG slots per block.
     std::vector<uint32_t> items;
     int64_t n_blocks = 0;      // workgroups of one launch
-    // Chunk arrays (already padded for the kernels' look-ahead).
-    std::vector<uint32_t> hdr, cols, vals;
+    // Chunk headers, chunk records and staging windows (already padded for the
+    // kernels' look-ahead), launch order.
+    std::vector<uint32_t> hdr, stream, wins;
     int64_t n_chunks = 0;      // real chunks (without the padding)
     int64_t n_enum = 0;        // enumerated columns (real column slots)
     int64_t n_split = 0;       // groups that are pieces of split panels

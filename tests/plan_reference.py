@@ -10,6 +10,7 @@ import numpy as np
 UFI = 4
 UFK = 8
 ITEM_WORDS = 16
+WIN_WORDS = 1024
 
 
 WAVES_PER_WG = 16
@@ -99,7 +100,31 @@ def check_blocks(items):
                 assert int(blk[w, 0]) + r in rows_written
 
 
-def decode_plan(items, hdr, cols, vals):
+def walk_chunks(it, hdr, stream, wins):
+    """Yields (header word, column slots, [value block per set row]) for every chunk
+    of one wave slot, following the records and checking the window table."""
+    row0, nrows, chunk0, nchunks, stream0, flags = (int(x) for x in it[:6])
+    win0, nwins = int(it[10]), int(it[11])
+    at = stream0
+    c = chunk0
+    for w in range(win0, win0 + nwins):
+        wc, ww = int(wins[w]) & 0xFFFF, int(wins[w]) >> 16
+        assert 1 <= wc and ww <= WIN_WORDS and ww % UFK == 0
+        start = at
+        for _ in range(wc):
+            h = int(hdr[c])
+            pattern = h & 15
+            pc = bin(pattern).count("1")
+            cc = stream[at:at + UFK]
+            blocks = [stream[at + UFK * (1 + t):at + UFK * (2 + t)] for t in range(pc)]
+            yield h, cc, blocks
+            at += UFK * (1 + pc)
+            c += 1
+        assert at - start == ww, "window table disagrees with the record sizes"
+    assert c == chunk0 + nchunks
+
+
+def decode_plan(items, hdr, stream, wins):
     """Chunk arrays -> (row, col, value bits) arrays in the order the kernel
     consumes them.  Also checks the structural invariants of the format and
     raises AssertionError on any violation."""
@@ -107,14 +132,13 @@ def decode_plan(items, hdr, cols, vals):
     items = items.reshape(-1, ITEM_WORDS)
     out_rows, out_cols, out_bits = [], [], []
     for it in items:
-        row0, nrows, chunk0, nchunks, vals0, flags = (int(x) for x in it[:6])
+        row0, nrows, chunk0, nchunks, stream0, flags = (int(x) for x in it[:6])
         if flags & FLAG_IDLE:
+            assert int(it[11]) == 0
             continue
-        v = vals0
         row = row0
         rows_left = nrows
-        for c in range(chunk0, chunk0 + nchunks):
-            h = int(hdr[c])
+        for h, cc, blocks in walk_chunks(it, hdr, stream, wins):
             pattern, count, end = h & 15, (h >> 4) & 15, (h >> 8) & 1
             assert h >> 9 == 0 and count <= UFK
             assert (count == 0) == (pattern == 0)
@@ -123,19 +147,19 @@ def decode_plan(items, hdr, cols, vals):
             assert rows_left > 0, "chunks after the last panel of the group"
             rows_here = min(UFI, rows_left)
             assert pattern < (1 << rows_here), "pattern names a row beyond the panel"
-            cc = cols[c * UFK:(c + 1) * UFK]
             if count:
                 assert np.all(cc[count:] == cc[count - 1]), "unused slots repeat the last real column"
+            t = 0
             for r in range(UFI):
                 if not (pattern >> r) & 1:
                     continue
-                block = vals[v:v + UFK]
+                block = blocks[t]
+                t += 1
                 assert not block[count:].any(), "unused value slots must be zero"
                 for u in range(count):
                     out_rows.append(row + r)
                     out_cols.append(int(cc[u]))
                     out_bits.append(int(block[u]))
-                v += UFK
             if end:
                 row += rows_here
                 rows_left -= rows_here
@@ -146,35 +170,35 @@ def decode_plan(items, hdr, cols, vals):
             np.array(out_bits, dtype=np.uint32))
 
 
-def interpret_plan(items, hdr, cols, vals, B, M):
+def interpret_plan(items, hdr, stream, wins, B, M):
     """Evaluates C from the chunk arrays in float32, block by block, chunk by
-    chunk, FMA by FMA in the kernel's order (row blocks in ascending row, slots in
-    ascending order; pieces of a split panel added in slot order by the wave slot
-    the table names)."""
+    chunk, FMA by FMA (row blocks in ascending row, slots in ascending order;
+    pieces of a split panel added in slot order by the wave slot the table names).
+    The kernel's slices add the same terms in a different order."""
     blocks = items.reshape(-1, WAVES_PER_WG, ITEM_WORDS)
     N = B.shape[1]
     C = np.full((M, N), np.nan, dtype=np.float32)
-    fvals = vals.view(np.float32)
     B64 = B.astype(np.float64)
     for blk in blocks:
         tiles = np.zeros((WAVES_PER_WG, UFI, N), dtype=np.float32)
         for w, it in enumerate(blk):
-            row0, nrows, chunk0, nchunks, vals0, flags = (int(x) for x in it[:6])
+            row0, nrows, chunk0, nchunks, stream0, flags = (int(x) for x in it[:6])
+            if flags & FLAG_IDLE:
+                continue
             acc = np.zeros((UFI, N), dtype=np.float32)
-            v = vals0
             row, rows_left = row0, nrows
-            for c in range(chunk0, chunk0 + nchunks):
-                h = int(hdr[c])
+            for h, cc, vblocks in walk_chunks(it, hdr, stream, wins):
                 pattern, end = h & 15, (h >> 8) & 1
-                cc = cols[c * UFK:(c + 1) * UFK]
+                t = 0
                 for r in range(UFI):
                     if not (pattern >> r) & 1:
                         continue
+                    fv = vblocks[t].view(np.float32)
+                    t += 1
                     for u in range(UFK):
-                        a = np.float64(fvals[v + u])
+                        a = np.float64(fv[u])
                         # fused multiply-add: exact product and sum in double, one rounding
                         acc[r] = (a * B64[cc[u]] + acc[r].astype(np.float64)).astype(np.float32)
-                    v += UFK
                 if end:
                     rows_here = min(UFI, rows_left)
                     if flags & FLAG_SPLIT:

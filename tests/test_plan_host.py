@@ -28,7 +28,7 @@ def host_plan(csr, **kw):
 
 def arrays(plan):
     return (plan.get_array(spmm.ARRAY_ITEMS), plan.get_array(spmm.ARRAY_HDR),
-            plan.get_array(spmm.ARRAY_COLS), plan.get_array(spmm.ARRAY_VALS))
+            plan.get_array(spmm.ARRAY_STREAM), plan.get_array(spmm.ARRAY_WINS))
 
 
 def heavy_tail_matrix(M, K, seed, heavy_rows=(3, 10), empty_rows=(0, 5, 6, 7, 8)):
@@ -127,8 +127,8 @@ def test_default_group_budget_rule():
 def test_format_round_trip_is_bit_exact(name, group_nnz):
     csr = CASES[name]()
     plan = host_plan(csr, group_nnz=group_nnz)
-    items, hdr, cols, vals = arrays(plan)
-    rows, cc, bits = decode_plan(items, hdr, cols, vals)
+    items, hdr, stream, wins = arrays(plan)
+    rows, cc, bits = decode_plan(items, hdr, stream, wins)
     assert len(rows) == csr.row_ptr[-1] == plan.describe()["nnz"]
     order = np.lexsort((cc, rows))
     want_rows, want_cols, want_bits = canonical_csr(csr.row_ptr, csr.col_idx, csr.vals)
@@ -138,8 +138,9 @@ def test_format_round_trip_is_bit_exact(name, group_nnz):
     info = plan.describe()
     counts = (hdr[:info["n_chunks"]] >> 4) & 15
     assert int(counts.sum()) == info["n_enum"]
-    assert len(hdr) >= info["n_chunks"] + 2 and not hdr[info["n_chunks"]:].any()
-    assert len(cols) == len(hdr) * UFK and len(vals) == info["vals_words"]
+    assert len(hdr) >= info["n_chunks"] + 10 and not hdr[info["n_chunks"]:].any()
+    pc = np.array([bin(int(h) & 15).count("1") for h in hdr[:info["n_chunks"]]])
+    assert len(stream) == info["stream_words"] >= UFK * int((1 + pc).sum())
 
 
 def test_unsorted_and_duplicate_columns_are_canonicalised():
@@ -148,19 +149,24 @@ def test_unsorted_and_duplicate_columns_are_canonicalised():
     vals = np.array([1, 2, 3, 4, 5, 6, 7, 8, 9], dtype=np.float32)
     csr = gen.Csr(4, 8, row_ptr, col_idx, vals)
     plan = host_plan(csr)
-    items, hdr, cols, v = arrays(plan)
-    rows, cc, bits = decode_plan(items, hdr, cols, v)
+    items, hdr, stream, wins = arrays(plan)
+    rows, cc, bits = decode_plan(items, hdr, stream, wins)
     got = sorted(zip(rows.tolist(), cc.tolist(), bits.view(np.float32).tolist()))
     want = sorted(zip([0, 0, 0, 0, 0, 2, 2, 2, 3], col_idx.tolist(), vals.tolist()))
     assert got == want
     # column 7 is stored twice in row 0: its second occurrence cannot share an
     # enumerated column with the first, so 7 appears in two different column slots
-    n = plan.describe()["n_chunks"]
-    slots = [int(cols[c * UFK + u]) for c in range(n) for u in range((int(hdr[c]) >> 4) & 15)]
+    assert cc.tolist().count(7) == 4 and len(rows) == 9
+    from plan_reference import walk_chunks
+    slots = []
+    for it in items.reshape(-1, 16):
+        if not int(it[5]) & 2:
+            for h, cols, _ in walk_chunks(it, hdr, stream, wins):
+                slots += [int(c) for c in cols[:(h >> 4) & 15]]
     assert slots.count(7) == 2 and slots.count(2) == 2
     # within a row, duplicates keep their stored order (3 after 1 for column 7 of row 0)
     B = np.eye(8, dtype=np.float32)
-    C = interpret_plan(items, hdr, cols, v, B, 4)
+    C = interpret_plan(items, hdr, stream, wins, B, 4)
     assert C[0, 7] == 4.0 and C[0, 2] == 7.0 and C[2, 2] == 6.0 and C[3, 7] == 9.0
     assert not C[1].any()
 
@@ -173,9 +179,13 @@ def test_every_pattern_of_a_four_row_panel_is_enumerated():
             if (p >> r) & 1:
                 W[r, p - 1] = 10 * p + r
     plan = host_plan(gen.csr_from_dense(W))
-    items, hdr, cols, vals = arrays(plan)
-    n = plan.describe()["n_chunks"]
-    seen = {int(h) & 15: int(cols[c * UFK]) for c, h in enumerate(hdr[:n])}
+    items, hdr, stream, wins = arrays(plan)
+    from plan_reference import walk_chunks
+    seen = {}
+    for it in items.reshape(-1, 16):
+        if not int(it[5]) & 2:
+            for h, cols, _ in walk_chunks(it, hdr, stream, wins):
+                seen[h & 15] = int(cols[0])
     assert sorted(seen) == list(range(1, 16)) and len(seen) == 2 ** UFI - 1
     assert all(col == p - 1 for p, col in seen.items())
     # three rows give 2^3 - 1 = 7 patterns (caption of the paper's Figure 4)
@@ -197,7 +207,7 @@ def test_pattern_histogram_of_uniform_sparsity_matches_closed_form():
         csr = gen.csr_from_dense(W)
         plan = host_plan(csr, group_nnz=1 << 20, group_panels=1 << 20)
         info = plan.describe()
-        items, hdr, cols, vals = arrays(plan)
+        items, hdr, stream, wins = arrays(plan)
         n = info["n_chunks"]
         pat = hdr[:n] & 15
         cnt = (hdr[:n] >> 4) & 15
@@ -227,12 +237,12 @@ def test_chunk_arrays_evaluate_to_the_product(oracle, name, group_nnz):
 def test_plan_bytes_against_csr_bytes_trend():
     # Paper Section 4.4: the transformed format is smaller than CSR at moderate
     # sparsity (one index per merged column instead of one per nonzero) and larger
-    # at extreme sparsity (metadata).  Here: 4 bytes per value slot, 4 per column
-    # slot, 4 per chunk header.
+    # at extreme sparsity (metadata).  Here: 4 bytes per value slot and per column
+    # slot of the chunk records, 4 per chunk header.
     def ratio(sparsity):
         csr = gen.uniform_positions(512, 512, sparsity, 31)
         info = host_plan(csr).describe()
-        plan_bytes = 4 * (info["vals_words"] + info["n_chunks"] * (UFK + 1))
+        plan_bytes = 4 * (info["stream_words"] + info["n_chunks"])
         csr_bytes = 8 * info["nnz"] + 4 * (csr.M + 1)
         return plan_bytes / csr_bytes
     assert ratio(0.5) < ratio(0.9) < ratio(0.99)
@@ -273,7 +283,7 @@ def test_error_codes_of_the_boundary():
     plan = spmm.plan_create(2, 2, ok_rp, ci, v, host_only=True)
     assert lib.spmm_execute(plan.handle, None, 32, None, None) == spmm.SPMM_ERR_INVALID_ARG
     small = np.zeros(1, dtype=np.uint32)
-    assert lib.spmm_plan_get_array(plan.handle, spmm.ARRAY_COLS, small.ctypes.data, 1, None) \
+    assert lib.spmm_plan_get_array(plan.handle, spmm.ARRAY_STREAM, small.ctypes.data, 1, None) \
         == spmm.SPMM_ERR_INVALID_ARG
     assert lib.spmm_plan_get_array(plan.handle, 9, None, 0, None) == spmm.SPMM_ERR_INVALID_ARG
     out = np.zeros(5, dtype=np.int32)
