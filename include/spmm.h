@@ -48,7 +48,7 @@ typedef struct {
     int64_t n_split;       /* row groups that are pieces of a panel too heavy for one group */
     int64_t n_enum;        /* enumerated columns: B rows a column tile must fetch per execute */
     int64_t n_chunks;      /* chunks: runs of at most ufk enumerated columns of one pattern */
-    int64_t stream_words;  /* 32-bit words of the chunk records (column indices and values, with padding) */
+    int64_t stream_words;  /* 32-bit words of the staged stream (headers, column indices, values, padding) */
     int64_t device_bytes;  /* device memory the plan holds (0 for a host-only plan) */
 } spmm_plan_info_t;
 
@@ -131,15 +131,16 @@ spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_
 /*
  * Raw copies of the plan's schedule-ordered arrays (host mirror), for format
  * round-trip tests and byte accounting.  Layouts are those the kernels read:
- *   SPMM_ARRAY_HDR     one word per chunk: bits 0-3 pattern (panel rows present in
- *                      every column of the chunk), bits 4-7 number of real columns,
- *                      bit 8 last chunk of its panel
- *   SPMM_ARRAY_STREAM  one record per chunk, back to back: ufk column indices (unused
- *                      slots repeat a real column), then one block of ufk float bit
- *                      patterns per set pattern row in ascending row order (zeros in
- *                      unused slots)
+ *   SPMM_ARRAY_HDR     one word per chunk, launch order (host-side copy): bits 0-3
+ *                      pattern (panel rows present in every column of the chunk),
+ *                      bits 4-7 number of real columns, bit 8 last chunk of its panel
  *   SPMM_ARRAY_WINS    one word per LDS staging window of a group: bits 0-15 chunks,
- *                      bits 16-31 record words (at most 1024)
+ *                      bits 16-31 words (at most 1024)
+ *   SPMM_ARRAY_STREAM  the windows back to back, each as: the headers of its chunks
+ *                      (zero-padded to a multiple of 8 words); ufk column indices per
+ *                      chunk (unused slots repeat a real column); per chunk one block
+ *                      of ufk float bit patterns per set pattern row in ascending row
+ *                      order (zeros in unused slots)
  *   SPMM_ARRAY_ITEMS   16 words per wave slot, 16 slots per workgroup, launch order:
  *                      first row, rows, first chunk, chunks, first record word, flags
  *                      (1 piece of a split panel, 2 idle slot, 4 workgroup with split

@@ -18,7 +18,7 @@ struct spmm_plan {
     HostPlan host;
     bool on_device = false;
     int device = -1;
-    uint32_t *d_hdr = nullptr, *d_stream = nullptr, *d_wins = nullptr, *d_items = nullptr;
+    uint32_t *d_stream = nullptr, *d_wins = nullptr, *d_items = nullptr;
     int64_t device_bytes = 0;
     bool force_wide = false;  // test hook: exercise the 64-bit addressing kernels on small inputs
 };
@@ -61,11 +61,10 @@ spmm_status_t upload(T **dst, const void *src, size_t bytes, int64_t &total)
 
 void release_device(spmm_plan *p)
 {
-    if (p->d_hdr) (void)hipFree(p->d_hdr);
     if (p->d_stream) (void)hipFree(p->d_stream);
     if (p->d_wins) (void)hipFree(p->d_wins);
     if (p->d_items) (void)hipFree(p->d_items);
-    p->d_hdr = p->d_stream = p->d_wins = p->d_items = nullptr;
+    p->d_stream = p->d_wins = p->d_items = nullptr;
     (void)hipGetLastError();
 }
 
@@ -103,7 +102,6 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
         }
         const HostPlan &h = p->host;
         spmm_status_t st = SPMM_OK;
-        if (st == SPMM_OK) st = upload(&p->d_hdr, h.hdr.data(), h.hdr.size() * 4, p->device_bytes);
         if (st == SPMM_OK) st = upload(&p->d_stream, h.stream.data(), h.stream.size() * 4, p->device_bytes);
         if (st == SPMM_OK) st = upload(&p->d_wins, h.wins.data(), h.wins.size() * 4, p->device_bytes);
         if (st == SPMM_OK) st = upload(&p->d_items, h.items.data(), h.items.size() * 4, p->device_bytes);
@@ -141,7 +139,6 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
     // Four columns per lane need 16-byte aligned rows.
     const bool quads = (N % 4 == 0) && !((uintptr_t)B & 15u) && !((uintptr_t)C & 15u);
     spmm_launch_args a;
-    a.hdr = plan->d_hdr;
     a.stream = plan->d_stream;
     a.wins = plan->d_wins;
     a.items = plan->d_items;

@@ -26,25 +26,29 @@ constexpr int N_PATTERNS = (1 << UFI) - 1;  // 15 nonzero patterns (paper Sectio
 // Enumerated columns per chunk (the paper's UFk).
 constexpr int UFK = 8;
 
-// The chunks of a row group are described by two arrays, in launch order of
-// their groups:
+// A chunk is described by
 //
-//   hdr[c]     one word:  bits 0..3  pattern (rows of the panel that own a value in
+//   header     one word:  bits 0..3  pattern (rows of the panel that own a value in
 //                                    every column of the chunk), 0 only for the
 //                                    single chunk of a panel without nonzeros
 //                         bits 4..7  count of real columns, 0..UFK
 //                         bit  8     last chunk of its panel (write the tile)
-//   stream     one record per chunk, records back to back:
-//                UFK column indices (slots >= count repeat a valid column of the
-//                chunk, or 0, and carry zero values), then for every set row of
-//                the pattern in ascending row order UFK value words (float bits,
-//                value of that row in column slot u; zero in unused slots).
-//              A record therefore has UFK * (1 + popcount(pattern)) words and a
-//              chunk's record offset is the running sum of those sizes.
+//   columns    UFK column indices (slots >= count repeat a valid column of the
+//              chunk, or 0, and carry zero values)
+//   values     for every set row of the pattern in ascending row order UFK value
+//              words (float bits, value of that row in column slot u; zero in
+//              unused slots)
 //
-// A group's records are staged through LDS in *windows* of at most WIN_WORDS
-// words; a record never straddles two windows.
+// The chunks of a row group are cut into *windows*, the unit a wave stages through
+// LDS: as many consecutive chunks as fit WIN_WORDS words.  `stream` holds the
+// windows back to back, each laid out as
+//   [ headers of its chunks, zero-padded to a multiple of 8 words ]
+//   [ columns of its chunks, UFK words each ]
+//   [ values of its chunks, back to back ]
+// so a chunk's header and columns sit at fixed strides and only its value offset
+// is a running sum (UFK * popcount(pattern) per chunk).
 //   wins[i]    one word per window: bits 0..15 chunks, bits 16..31 words
+//   hdr[c]     host-side copy of all headers in launch order (introspection only)
 constexpr uint32_t HDR_PATTERN_MASK = 0xFu;
 constexpr int HDR_COUNT_SHIFT = 4;
 constexpr uint32_t HDR_COUNT_MASK = 0xFu;

@@ -6,9 +6,8 @@
 #include <stdint.h>
 
 struct spmm_launch_args {
-    const uint32_t *hdr;    // DEVICE chunk headers
-    const uint32_t *stream; // DEVICE chunk records (column indices and value bits)
-    const uint32_t *wins;   // DEVICE staging windows
+    const uint32_t *stream; // DEVICE staging windows: headers, column indices, value bits
+    const uint32_t *wins;   // DEVICE window table
     const uint32_t *items;  // DEVICE wave-slot descriptors, 16 per block
     int32_t n_blocks;       // workgroups to launch
     const float *B;         // DEVICE first column of the column tile

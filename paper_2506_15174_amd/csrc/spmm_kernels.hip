@@ -18,11 +18,11 @@
 //     indices and values are staged through LDS, a window of the group's stream
 //     at a time, with coalesced 16-byte loads (the scalar data path tops out far
 //     below what the stream needs); a slice reads its own slots back with one
-//     broadcast LDS read per row of the pattern.  Only the one-word chunk headers
-//     travel through scalar loads: the pattern selects, with wave-uniform
-//     branches, which of the UFI row blocks run, so no lane ever tests a
-//     sparsity condition (Section 3.2.2: enumerated blocks carry no
-//     conditionals).
+//     broadcast LDS read per row of the pattern.  The one-word chunk header comes
+//     from the same window: its pattern selects, with wave-uniform branches,
+//     which of the UFI row blocks run, so no lane ever tests a sparsity condition
+//     (Section 3.2.2: enumerated blocks carry no conditionals).  No scalar load
+//     sits inside the chunk loop, so its LDS waits are counted, not drained.
 //   * The chunk loop is software-pipelined D chunks deep (the paper's
 //     unroll(k, UFk) for loads in flight, Section 3.3.2): while chunk c is
 //     multiplied the B rows of chunks c+1 .. c+D-1 are in flight.
@@ -154,7 +154,7 @@ template <int Q> __device__ __forceinline__ void lds_read(uint32_t (&out)[Q], co
 // WIDE  64-bit addressing of B
 template <int S, int VW, int D, bool WIDE>
 __global__ __launch_bounds__(64 * WAVES_PER_WG) void
-spmm_chunks_kernel(const uint32_t *__restrict__ hdr_g, const uint32_t *__restrict__ stream_g,
+spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                    const uint32_t *__restrict__ wins_g, const uint32_t *__restrict__ items_g,
                    const float *__restrict__ B, uint32_t b_bytes, float *__restrict__ C, int32_t ldn,
                    int32_t width)
@@ -184,7 +184,6 @@ spmm_chunks_kernel(const uint32_t *__restrict__ hdr_g, const uint32_t *__restric
     if (n_wins != 0) {
         uint32_t row = it[IT_ROW0];
         uint32_t rows_left = it[IT_NROWS];
-        cword_t *hdrs = (cword_t *)(hdr_g) + it[IT_CHUNK0];
         cword_t *wins = (cword_t *)(wins_g) + it[IT_WIN0];
         const uint32_t *stream = stream_g + (size_t)it[IT_STREAM0];
         const uint32_t ld_bytes = (uint32_t)ldn * 4u;
@@ -209,33 +208,30 @@ spmm_chunks_kernel(const uint32_t *__restrict__ hdr_g, const uint32_t *__restric
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-            // ---- pipeline over the window's chunks.  Record of a chunk: 8 column
-            //      words, then 8 value words per row of its pattern.
+            // ---- pipeline over the window's chunks.  Window layout: headers
+            //      (padded to 8 words), UFK column words per chunk, then the value
+            //      blocks back to back.
+            const uint32_t cols_base = ((wc + 7u) & ~7u) + slot0;
+            uint32_t at_val = ((wc + 7u) & ~7u) + wc * (uint32_t)UFK + slot0;  // values of the chunk multiplied next
             vec_t b[D][Q];
             off_t voff[Q];
-            uint32_t at_look = 0;   // record of the chunk whose columns are read next
-            uint32_t at_mul = 0;    // record of the chunk multiplied next
 #pragma unroll
             for (int j = 0; j < D - 1; ++j) {
-                const uint32_t hj = hdrs[j];
                 uint32_t cv[Q];
-                lds_read<Q>(cv, win, at_look + slot0);
+                lds_read<Q>(cv, win, cols_base + (uint32_t)(j * UFK));
                 const uint32_t ld_eff = (uint32_t)j < wc ? ld_bytes : 0u;
 #pragma unroll
                 for (int q = 0; q < Q; ++q)
                     b[j][q] = src.load(BSource<WIDE>::offset(cv[q], ld_eff, lane_off), vec_t());
-                at_look += (uint32_t)UFK * (1u + (uint32_t)__builtin_popcount(hj & HDR_PATTERN_MASK));
             }
             {
                 uint32_t cv[Q];
-                lds_read<Q>(cv, win, at_look + slot0);
+                lds_read<Q>(cv, win, cols_base + (uint32_t)((D - 1) * UFK));
                 const uint32_t ld_eff = (uint32_t)(D - 1) < wc ? ld_bytes : 0u;
 #pragma unroll
                 for (int q = 0; q < Q; ++q) voff[q] = BSource<WIDE>::offset(cv[q], ld_eff, lane_off);
-                at_look += (uint32_t)UFK * (1u + (uint32_t)__builtin_popcount(hdrs[D - 1] & HDR_PATTERN_MASK));
             }
-            uint32_t h_look = hdrs[D];  // header of the chunk whose columns are read in the next step
-            uint32_t h_mul = hdrs[0];   // header of the chunk multiplied in the next step
+            uint32_t h_next = win[0];  // header of the chunk multiplied in the next step (same in all lanes)
 
             uint32_t c = 0;
             bool more = true;
@@ -248,16 +244,13 @@ spmm_chunks_kernel(const uint32_t *__restrict__ hdr_g, const uint32_t *__restric
                     // columns of chunk c+D for the next step; a chunk past the window's
                     // end reads row 0 through a zero pitch (its columns are never used)
                     uint32_t cv[Q];
-                    lds_read<Q>(cv, win, at_look + slot0);
-                    at_look += (uint32_t)UFK * (1u + (uint32_t)__builtin_popcount(h_look & HDR_PATTERN_MASK));
+                    lds_read<Q>(cv, win, cols_base + (c + (uint32_t)D) * (uint32_t)UFK);
                     const uint32_t ld_next = c + (uint32_t)D < wc ? ld_bytes : 0u;
-                    const uint32_t h_now = h_mul;
-                    h_look = hdrs[c + D + 1];
-                    h_mul = hdrs[c + 1];
+                    const uint32_t h_now = __builtin_amdgcn_readfirstlane(h_next);
+                    h_next = win[c + 1];
 
                     // the enumerated block of chunk c (paper Listing 7)
                     const uint32_t pattern = h_now & HDR_PATTERN_MASK;
-                    uint32_t at_val = at_mul + (uint32_t)UFK + slot0;
 #pragma unroll
                     for (int r = 0; r < UFI; ++r) {
                         if (pattern & (1u << r)) {
@@ -268,7 +261,6 @@ spmm_chunks_kernel(const uint32_t *__restrict__ hdr_g, const uint32_t *__restric
                             at_val += (uint32_t)UFK;
                         }
                     }
-                    at_mul += (uint32_t)UFK * (1u + (uint32_t)__builtin_popcount(pattern));
 
 #pragma unroll
                     for (int q = 0; q < Q; ++q) voff[q] = BSource<WIDE>::offset(cv[q], ld_next, lane_off);
@@ -313,7 +305,6 @@ spmm_chunks_kernel(const uint32_t *__restrict__ hdr_g, const uint32_t *__restric
                     }
                 }
             }
-            hdrs += wc;
             stream += ww;
         }
     }
@@ -337,7 +328,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ hdr_g, const uint32_t *__restric
 
 #define SPMM_LAUNCH(S, VW, D, WIDE)                                                                   \
     hipLaunchKernelGGL((spmm_chunks_kernel<S, VW, D, WIDE>), dim3((unsigned)a.n_blocks),              \
-                       dim3(64 * WAVES_PER_WG), 0, (hipStream_t)stream, a.hdr, a.stream, a.wins,      \
+                       dim3(64 * WAVES_PER_WG), 0, (hipStream_t)stream, a.stream, a.wins,             \
                        a.items, a.B, a.b_bytes, a.C, a.ldn, a.width)
 
 int spmm_launch_chunks(const spmm_launch_args &a, int slices, bool wide, void *stream)

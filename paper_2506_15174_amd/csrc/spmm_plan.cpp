@@ -50,11 +50,12 @@ int32_t choose_group_nnz(int64_t nnz)
 }
 
 struct Emitter {
-    std::vector<uint32_t> hdr, stream;  // creation order
+    // creation order: one header per chunk, UFK column slots per chunk, and the
+    // chunks' value blocks back to back (UFK words per set pattern row)
+    std::vector<uint32_t> hdr, cols, vals;
     int64_t n_enum = 0;
 
-    // Emits one chunk of `count` entries (all of pattern `pattern`): its header
-    // and its record (column slots, then one value block per set row).
+    // Emits one chunk of `count` entries (all of pattern `pattern`).
     void chunk(const Entry *e, int count, uint32_t pattern, bool end_panel)
     {
         uint32_t h = pattern | ((uint32_t)count << HDR_COUNT_SHIFT);
@@ -63,14 +64,14 @@ struct Emitter {
         for (int u = 0; u < UFK; ++u) {
             int32_t c = 0;
             if (count > 0) c = e[u < count ? u : count - 1].col;
-            stream.push_back((uint32_t)c);
+            cols.push_back((uint32_t)c);
         }
         for (int r = 0; r < UFI; ++r) {
             if (!(pattern & (1u << r))) continue;
             for (int u = 0; u < UFK; ++u) {
                 uint32_t bits = 0;
                 if (u < count) std::memcpy(&bits, &e[u].v[r], 4);
-                stream.push_back(bits);
+                vals.push_back(bits);
             }
         }
         n_enum += count;
@@ -178,7 +179,8 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         // ---- 2. enumeration and emission, panel by panel ----------------------
         Emitter em;
         em.hdr.reserve((size_t)(nnz / 4 + P + 16));
-        em.stream.reserve((size_t)(3 * nnz + 8 * P + 64));
+        em.cols.reserve((size_t)(nnz / 4 + P + 16) * UFK);
+        em.vals.reserve((size_t)(nnz + nnz / 2 + 64));
 
         std::vector<int32_t> order;                  // canonical order of one row
         std::vector<int32_t> ccol[UFI];              // canonical columns per panel row
@@ -194,7 +196,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
             const int64_t g_last = split ? gi + g0.nseg - 1 : gi;  // pieces of a panel are adjacent
             if (!split) {
                 g0.chunk0 = (int64_t)em.hdr.size();
-                g0.words0 = (int64_t)em.stream.size();
+                g0.words0 = (int64_t)em.vals.size();
             }
             const int64_t first_panel = g0.row_begin / UFI;
             const int64_t last_panel = (g0.row_end + UFI - 1) / UFI;  // exclusive
@@ -283,7 +285,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                 for (int64_t s = gi; s <= g_last; ++s) {
                     Group &gs = groups[s];
                     gs.chunk0 = (int64_t)em.hdr.size();
-                    gs.words0 = (int64_t)em.stream.size();
+                    gs.words0 = (int64_t)em.vals.size();
                     piece.clear();
                     for (int64_t q = gs.nnz_begin - base; q < gs.nnz_end - base; ++q) {
                         const Flat &f = flat[(size_t)q];
@@ -298,12 +300,12 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                     }
                     em.panel(piece);
                     gs.n_chunks = (int64_t)em.hdr.size() - gs.chunk0;
-                    gs.n_words = (int64_t)em.stream.size() - gs.words0;
+                    gs.n_words = (int64_t)em.vals.size() - gs.words0;
                 }
             }
             if (!split) {
                 g0.n_chunks = (int64_t)em.hdr.size() - g0.chunk0;
-                g0.n_words = (int64_t)em.stream.size() - g0.words0;
+                g0.n_words = (int64_t)em.vals.size() - g0.words0;
             }
             gi = g_last + 1;
         }
@@ -332,51 +334,62 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         });
 
         const int64_t total_chunks = (int64_t)em.hdr.size();
-        const int64_t total_words = (int64_t)em.stream.size();
-        if (total_chunks + CHUNK_TAIL_PAD >= ((int64_t)1 << 31) - 8 ||
-            total_words + STREAM_TAIL_PAD >= ((int64_t)1 << 32) || n_groups >= ((int64_t)1 << 31) - WAVES_PER_WG)
+        // upper bound of the stream: headers (padded per window), columns, values
+        const int64_t bound_words = total_chunks * (1 + UFK) + (int64_t)em.vals.size() + 8 * total_chunks / 4 + 64;
+        if (total_chunks + CHUNK_TAIL_PAD >= ((int64_t)1 << 31) - 8 || bound_words >= ((int64_t)1 << 32) ||
+            n_groups >= ((int64_t)1 << 31) - WAVES_PER_WG)
             return ST_UNSUPPORTED;
 
         out.hdr.resize((size_t)(total_chunks + CHUNK_TAIL_PAD), 0u);
-        out.stream.resize((size_t)(total_words + STREAM_TAIL_PAD), 0u);
+        out.stream.reserve((size_t)(total_chunks * (2 + UFK) + (int64_t)em.vals.size() + STREAM_TAIL_PAD));
         out.groups.reserve((size_t)n_groups * 5);
-        int64_t c_at = 0, w_at = 0;
+        int64_t c_at = 0;
 
-        // appends one group to the launch-ordered arrays, cuts its records into
-        // staging windows and fills its descriptor
+        // appends one group to the launch-ordered arrays: cuts its chunks into
+        // staging windows, lays every window out as [headers | column slots |
+        // value blocks] and fills the group's descriptor
         auto place = [&](const Group &g, uint32_t *it) {
             std::copy(em.hdr.begin() + g.chunk0, em.hdr.begin() + g.chunk0 + g.n_chunks, out.hdr.begin() + c_at);
-            std::copy(em.stream.begin() + g.words0, em.stream.begin() + g.words0 + g.n_words,
-                      out.stream.begin() + w_at);
             out.groups.push_back(g.row_begin);
             out.groups.push_back(g.row_end);
             out.groups.push_back(g.nnz_begin);
             out.groups.push_back(g.nnz_end);
             out.groups.push_back(g.flags);
             const uint32_t win0 = (uint32_t)out.wins.size();
-            uint32_t wc = 0, ww = 0;
-            for (int64_t c = 0; c < g.n_chunks; ++c) {
-                const uint32_t pattern = em.hdr[(size_t)(g.chunk0 + c)] & HDR_PATTERN_MASK;
-                const uint32_t rec = (uint32_t)UFK * (1u + (uint32_t)__builtin_popcount(pattern));
-                if (ww + rec > (uint32_t)WIN_WORDS) {
-                    out.wins.push_back(wc | (ww << 16));
-                    wc = 0;
-                    ww = 0;
+            const uint64_t stream0 = out.stream.size();
+            int64_t c = 0;
+            int64_t v_at = g.words0;
+            while (c < g.n_chunks) {
+                // widest run of chunks whose window still fits
+                int64_t wc = 0, vw = 0;
+                while (c + wc < g.n_chunks) {
+                    const uint32_t pattern = em.hdr[(size_t)(g.chunk0 + c + wc)] & HDR_PATTERN_MASK;
+                    const int64_t add = (int64_t)UFK * __builtin_popcount(pattern);
+                    const int64_t words = ((wc + 1 + 7) / 8) * 8 + (wc + 1) * UFK + vw + add;
+                    if (words > WIN_WORDS) break;
+                    wc += 1;
+                    vw += add;
                 }
-                wc += 1;
-                ww += rec;
+                const int64_t hdr_words = ((wc + 7) / 8) * 8;
+                const int64_t ww = hdr_words + wc * UFK + vw;
+                for (int64_t k = 0; k < hdr_words; ++k)
+                    out.stream.push_back(k < wc ? em.hdr[(size_t)(g.chunk0 + c + k)] : 0u);
+                out.stream.insert(out.stream.end(), em.cols.begin() + (g.chunk0 + c) * UFK,
+                                  em.cols.begin() + (g.chunk0 + c + wc) * UFK);
+                out.stream.insert(out.stream.end(), em.vals.begin() + v_at, em.vals.begin() + v_at + vw);
+                out.wins.push_back((uint32_t)wc | ((uint32_t)ww << 16));
+                c += wc;
+                v_at += vw;
             }
-            if (wc) out.wins.push_back(wc | (ww << 16));
             it[IT_ROW0] = (uint32_t)g.row_begin;
             it[IT_NROWS] = (uint32_t)(g.row_end - g.row_begin);
             it[IT_CHUNK0] = (uint32_t)c_at;
             it[IT_NCHUNKS] = (uint32_t)g.n_chunks;
-            it[IT_STREAM0] = (uint32_t)w_at;
+            it[IT_STREAM0] = (uint32_t)stream0;
             it[IT_FLAGS] = (uint32_t)g.flags;
             it[IT_WIN0] = win0;
             it[IT_NWINS] = (uint32_t)out.wins.size() - win0;
             c_at += g.n_chunks;
-            w_at += g.n_words;
         };
         auto new_block = [&](uint32_t flags) {
             const size_t at = out.items.size();
@@ -430,6 +443,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
             }
         }
         out.wins.push_back(0u);  // look-ahead slot
+        out.stream.resize(out.stream.size() + STREAM_TAIL_PAD, 0u);
         out.n_chunks = total_chunks;
         out.n_enum = em.n_enum;
     } catch (const std::bad_alloc &) {

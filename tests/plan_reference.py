@@ -102,7 +102,8 @@ def check_blocks(items):
 
 def walk_chunks(it, hdr, stream, wins):
     """Yields (header word, column slots, [value block per set row]) for every chunk
-    of one wave slot, following the records and checking the window table."""
+    of one wave slot, following the windows and checking the window table and the
+    host-side header copy."""
     row0, nrows, chunk0, nchunks, stream0, flags = (int(x) for x in it[:6])
     win0, nwins = int(it[10]), int(it[11])
     at = stream0
@@ -110,17 +111,21 @@ def walk_chunks(it, hdr, stream, wins):
     for w in range(win0, win0 + nwins):
         wc, ww = int(wins[w]) & 0xFFFF, int(wins[w]) >> 16
         assert 1 <= wc and ww <= WIN_WORDS and ww % UFK == 0
-        start = at
-        for _ in range(wc):
-            h = int(hdr[c])
-            pattern = h & 15
-            pc = bin(pattern).count("1")
-            cc = stream[at:at + UFK]
-            blocks = [stream[at + UFK * (1 + t):at + UFK * (2 + t)] for t in range(pc)]
+        hdr_words = -(-wc // 8) * 8
+        assert not stream[at + wc:at + hdr_words].any()
+        cols_at = at + hdr_words
+        vals_at = cols_at + wc * UFK
+        for k in range(wc):
+            h = int(stream[at + k])
+            assert h == int(hdr[c]), "window header differs from the header list"
+            pc = bin(h & 15).count("1")
+            cc = stream[cols_at + k * UFK:cols_at + (k + 1) * UFK]
+            blocks = [stream[vals_at + UFK * t:vals_at + UFK * (t + 1)] for t in range(pc)]
             yield h, cc, blocks
-            at += UFK * (1 + pc)
+            vals_at += UFK * pc
             c += 1
-        assert at - start == ww, "window table disagrees with the record sizes"
+        assert vals_at - at == ww, "window table disagrees with the window's content"
+        at += ww
     assert c == chunk0 + nchunks
 
 
