@@ -51,47 +51,58 @@ template <> struct Vec<1> {
     typedef float type;
     static __device__ __forceinline__ type zero() { return 0.0f; }
 };
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 template <> struct Vec<4> {
-    typedef float4 type;
-    static __device__ __forceinline__ type zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+    typedef f32x4_t type;
+    static __device__ __forceinline__ type zero() { return type{0.f, 0.f, 0.f, 0.f}; }
 };
 
 __device__ __forceinline__ void fma_acc(float &acc, float a, float b) { acc = __builtin_fmaf(a, b, acc); }
-__device__ __forceinline__ void fma_acc(float4 &acc, float a, const float4 &b)
+__device__ __forceinline__ void fma_acc(f32x4_t &acc, float a, const f32x4_t &b)
 {
-    acc.x = __builtin_fmaf(a, b.x, acc.x);
-    acc.y = __builtin_fmaf(a, b.y, acc.y);
-    acc.z = __builtin_fmaf(a, b.z, acc.z);
-    acc.w = __builtin_fmaf(a, b.w, acc.w);
+    acc[0] = __builtin_fmaf(a, b[0], acc[0]);
+    acc[1] = __builtin_fmaf(a, b[1], acc[1]);
+    acc[2] = __builtin_fmaf(a, b[2], acc[2]);
+    acc[3] = __builtin_fmaf(a, b[3], acc[3]);
 }
 __device__ __forceinline__ void add_to(float &a, float b) { a += b; }
-__device__ __forceinline__ void add_to(float4 &a, const float4 &b)
-{
-    a.x += b.x;
-    a.y += b.y;
-    a.z += b.z;
-    a.w += b.w;
-}
+__device__ __forceinline__ void add_to(f32x4_t &a, const f32x4_t &b) { a += b; }
 template <int MASK> __device__ __forceinline__ void add_across(float &a) { a += __shfl_xor(a, MASK); }
-template <int MASK> __device__ __forceinline__ void add_across(float4 &a)
+template <int MASK> __device__ __forceinline__ void add_across(f32x4_t &a)
 {
-    a.x += __shfl_xor(a.x, MASK);
-    a.y += __shfl_xor(a.y, MASK);
-    a.z += __shfl_xor(a.z, MASK);
-    a.w += __shfl_xor(a.w, MASK);
+    a[0] += __shfl_xor(a[0], MASK);
+    a[1] += __shfl_xor(a[1], MASK);
+    a[2] += __shfl_xor(a[2], MASK);
+    a[3] += __shfl_xor(a[3], MASK);
 }
 
 // Source of B rows.  Narrow: a raw buffer descriptor over the column tile's
 // bytes (hardware range check, 32-bit per-lane byte offset).  Wide: plain 64-bit
 // addressing for B beyond the narrow limits.
+//
+// The loads are issued from inline assembly and their completion is awaited
+// with explicit s_waitcnt vmcnt(n) (wait_for below): the compiler's own wait
+// insertion treats every load that is still in flight at a loop back edge as if
+// it were the newest one, which would drain the software pipeline once per trip.
+// Vector memory operations complete in issue order, so "at most n younger
+// operations outstanding" is a sufficient condition whatever else (stores of C,
+// window staging) the compiler has in flight.
 template <bool WIDE> struct BSource;
 
 template <> struct BSource<false> {
-    __amdgpu_buffer_rsrc_t rsrc;
+    u32x4 rsrc;
     __device__ __forceinline__ void init(const float *B, uint32_t n_bytes)
     {
-        // word 3: 32-bit data format, raw (untyped, stride 0) addressing
-        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(B), 0, (int)n_bytes, 0x00020000);
+        const uint64_t p = reinterpret_cast<uint64_t>(B);
+        rsrc[0] = (uint32_t)p;
+        rsrc[1] = (uint32_t)(p >> 32) & 0xFFFFu;  // 48-bit base, stride 0
+        rsrc[2] = n_bytes;                        // raw buffer: range in bytes
+        rsrc[3] = 0x00020000u;                    // 32-bit data format, untyped
+        // the descriptor must live in SGPRs
+        rsrc[0] = __builtin_amdgcn_readfirstlane(rsrc[0]);
+        rsrc[1] = __builtin_amdgcn_readfirstlane(rsrc[1]);
+        rsrc[2] = __builtin_amdgcn_readfirstlane(rsrc[2]);
+        rsrc[3] = __builtin_amdgcn_readfirstlane(rsrc[3]);
     }
     // byte offset of a lane's segment: row pitch and column index both below 2^24
     static __device__ __forceinline__ uint32_t offset(uint32_t col, uint32_t ld_bytes, uint32_t lane_off)
@@ -99,15 +110,13 @@ template <> struct BSource<false> {
         return __umul24(col, ld_bytes) + lane_off;
     }
     typedef uint32_t off_t;
-    __device__ __forceinline__ float load(uint32_t off, float) const
+    __device__ __forceinline__ void load(float &dst, uint32_t off) const
     {
-        return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, 0));
+        asm volatile("buffer_load_dword %0, %1, %2, 0 offen" : "=v"(dst) : "v"(off), "s"(rsrc));
     }
-    __device__ __forceinline__ float4 load(uint32_t off, float4) const
+    __device__ __forceinline__ void load(f32x4_t &dst, uint32_t off) const
     {
-        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
-        return make_float4(__uint_as_float(v[0]), __uint_as_float(v[1]), __uint_as_float(v[2]),
-                           __uint_as_float(v[3]));
+        asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dst) : "v"(off), "s"(rsrc));
     }
 };
 
@@ -119,15 +128,34 @@ template <> struct BSource<true> {
         return (uint64_t)col * (uint64_t)ld_bytes + lane_off;
     }
     typedef uint64_t off_t;
-    __device__ __forceinline__ float load(uint64_t off, float) const
+    __device__ __forceinline__ void load(float &dst, uint64_t off) const
     {
-        return *reinterpret_cast<const float *>(base + off);
+        const char *p = base + off;
+        asm volatile("global_load_dword %0, %1, off" : "=v"(dst) : "v"(p));
     }
-    __device__ __forceinline__ float4 load(uint64_t off, float4) const
+    __device__ __forceinline__ void load(f32x4_t &dst, uint64_t off) const
     {
-        return *reinterpret_cast<const float4 *>(base + off);
+        const char *p = base + off;
+        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p));
     }
 };
+
+// Blocks until at most N vector memory operations younger than the Q loads of
+// `b` are outstanding, and tells the compiler that `b` is defined from here on.
+template <int N, typename T, int Q> __device__ __forceinline__ void wait_for(T (&b)[Q])
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    if constexpr (Q == 8)
+        asm volatile("s_waitcnt vmcnt(%8)"
+                     : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7])
+                     : "n"(N));
+    else if constexpr (Q == 4)
+        asm volatile("s_waitcnt vmcnt(%4)" : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]) : "n"(N));
+    else if constexpr (Q == 2)
+        asm volatile("s_waitcnt vmcnt(%2)" : "+v"(b[0]), "+v"(b[1]) : "n"(N));
+    else
+        asm volatile("s_waitcnt vmcnt(%1)" : "+v"(b[0]) : "n"(N));
+}
 
 // Q consecutive words of this wave's LDS window, starting at word `at`.
 template <int Q> __device__ __forceinline__ void lds_read(uint32_t (&out)[Q], const uint32_t *win, uint32_t at)
@@ -221,8 +249,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                 lds_read<Q>(cv, win, cols_base + (uint32_t)(j * UFK));
                 const uint32_t ld_eff = (uint32_t)j < wc ? ld_bytes : 0u;
 #pragma unroll
-                for (int q = 0; q < Q; ++q)
-                    b[j][q] = src.load(BSource<WIDE>::offset(cv[q], ld_eff, lane_off), vec_t());
+                for (int q = 0; q < Q; ++q) src.load(b[j][q], BSource<WIDE>::offset(cv[q], ld_eff, lane_off));
             }
             {
                 uint32_t cv[Q];
@@ -240,7 +267,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                 for (int s = 0; s < D; ++s) {
                     // step for chunk c (c % D == s): voff holds the offsets of chunk c+D-1
 #pragma unroll
-                    for (int q = 0; q < Q; ++q) b[(s + D - 1) % D][q] = src.load(voff[q], vec_t());
+                    for (int q = 0; q < Q; ++q) src.load(b[(s + D - 1) % D][q], voff[q]);
                     // columns of chunk c+D for the next step; a chunk past the window's
                     // end reads row 0 through a zero pitch (its columns are never used)
                     uint32_t cv[Q];
@@ -249,8 +276,10 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                     const uint32_t h_now = __builtin_amdgcn_readfirstlane(h_next);
                     h_next = win[c + 1];
 
-                    // the enumerated block of chunk c (paper Listing 7)
+                    // the enumerated block of chunk c (paper Listing 7); its B rows are
+                    // older than the (D - 1) * Q loads issued since
                     const uint32_t pattern = h_now & HDR_PATTERN_MASK;
+                    wait_for<(D - 1) * Q>(b[s]);
 #pragma unroll
                     for (int r = 0; r < UFI; ++r) {
                         if (pattern & (1u << r)) {
@@ -305,6 +334,9 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                     }
                 }
             }
+            // The look-ahead loads of chunks past the window's end are still in
+            // flight into registers the compiler considers free from here on.
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             stream += ww;
         }
     }
