@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: fp32 CSR SpMM C = A x B on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conv|stress|ffn]
+
+A step is one pass of the whole hot path (spmm_execute, every kernel it
+launches) over the workload's column counts, with the plan and all operands
+resident in HBM before the timed region.  Plan creation is timed separately
+(it is amortised over inferences) and never part of a step.
+
+Prints ONE JSON line:
+  value         GFLOP/s = 2 nnz sum(bCols) / step time
+  roofline      dominant kernel (the widest column count of the workload):
+                algorithmic bytes 4(M+1) + 8 nnz + 4 K N + 4 M N per launch over
+                the kernel's average duration, measured with HIP events on the
+                launch stream inside the timed region, against 8 TB/s
+  cpu_baseline  the CPU oracle timed on the host cores for the same products
+  baselines     rocSPARSE/hipSPARSE CSR SpMM (through torch.sparse) and dense
+                rocBLAS SGEMM (through torch.mm) on the same inputs, as effective
+                GFLOP/s with the same numerator
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz, no packed-fp32 forms
+FP32_VALU_PEAK_TFLOPS = 78.6
+
+
+def bytes_min(M, K, nnz, N):
+    return 4 * (M + 1) + 8 * nnz + 4 * K * N + 4 * M * N
+
+
+def build_workload(name):
+    from workloads import generators as gen
+    if name == "conv":
+        return ("conv1x1 512x2048 @80% magnitude-pruned N(0,1), bCols 32/64/128 (configs[1])",
+                gen.conv_layer(), (32, 64, 128))
+    if name == "stress":
+        return ("stress 16384x16384 @95% Zipf(1.5) rows, 5% empty, bCols 128 (configs[3])",
+                gen.stress(), (128,))
+    if name == "ffn":
+        return ("ffn 4096x1024 @70% lognormal rows, bCols 32/64/128 (configs[2])",
+                gen.ffn(0, 0), (32, 64, 128))
+    raise SystemExit("unknown workload %r" % name)
+
+
+def time_kernel_events(torch, fn, reps, batch=20):
+    """Average and median duration (ms) of one fn() launch: `reps` samples, each
+    `batch` back-to-back launches between two HIP events recorded on the current
+    stream (the stream spmm_execute launches on).  Microsecond kernels cannot be
+    timed one launch per event pair: the pair itself costs several microseconds."""
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+    for i in range(reps):
+        starts[i].record()
+        for _ in range(batch):
+            fn()
+        ends[i].record()
+    torch.cuda.synchronize()
+    ts = sorted(s.elapsed_time(e) / batch for s, e in zip(starts, ends))
+    return sum(ts) / len(ts), ts[len(ts) // 2]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="conv")
+    ap.add_argument("--no-baselines", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("this build runs on one GPU only: the path shards by rows of A "
+                         "(see DESIGN.md) but no multi-GPU run exists; use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_2506_15174_amd as spmm
+    from workloads import generators as gen
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    label, csr, cols = build_workload(args.workload)
+    nnz = int(csr.row_ptr[-1])
+    t0 = time.perf_counter()
+    plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals)
+    plan_s = time.perf_counter() - t0
+    info = plan.describe()
+
+    Bs = {N: torch.from_numpy(gen.activations_for(csr, N)).cuda() for N in cols}
+    Cs = {N: torch.empty((csr.M, N), dtype=torch.float32, device="cuda") for N in cols}
+
+    def step():
+        for N in cols:
+            plan.execute(Bs[N], Cs[N])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    flops_step = 2.0 * nnz * sum(cols)
+    value = flops_step / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel: the widest column count; one launch per execute there
+    Nd = max(cols)
+    avg_ms, med_ms = time_kernel_events(torch, lambda: plan.execute(Bs[Nd], Cs[Nd]), 20)
+    bmin = bytes_min(csr.M, csr.K, nnz, Nd)
+    achieved = bmin / (avg_ms * 1e-3) / 1e9
+    kernel_tflops = 2.0 * nnz * Nd / (avg_ms * 1e-3) / 1e12
+    roofline = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                "kernel": "spmm_chunks_kernel<S=2,VW=4,D=3> (bCols %d)" % Nd,
+                "avg_launch_us": round(avg_ms * 1e3, 3), "median_launch_us": round(med_ms * 1e3, 3),
+                "algorithmic_bytes": bmin, "kernel_tflops": round(kernel_tflops, 3),
+                "frac_of_fp32_valu_peak": round(kernel_tflops / FP32_VALU_PEAK_TFLOPS, 5)}
+
+    per_cols = {}
+    for N in cols:
+        a, m = time_kernel_events(torch, lambda N=N: plan.execute(Bs[N], Cs[N]), 20)
+        per_cols[str(N)] = {"us": round(m * 1e3, 3), "gflops": round(2.0 * nnz * N / (m * 1e-3) / 1e9, 1),
+                            "hbm_model_gbs": round(bytes_min(csr.M, csr.K, nnz, N) / (m * 1e-3) / 1e9, 1)}
+
+    baselines = {}
+    if not args.no_baselines:
+        try:
+            A_sp = torch.sparse_csr_tensor(torch.from_numpy(csr.row_ptr.astype(np.int64)),
+                                           torch.from_numpy(csr.col_idx.astype(np.int64)),
+                                           torch.from_numpy(csr.vals), size=(csr.M, csr.K)).cuda()
+            dense_ok = csr.M * csr.K <= (1 << 28)
+            A_dn = A_sp.to_dense() if dense_ok else None
+            for N in cols:
+                for _ in range(3):
+                    torch.sparse.mm(A_sp, Bs[N])
+                _, m = time_kernel_events(torch, lambda N=N: torch.sparse.mm(A_sp, Bs[N]), 10, batch=5)
+                entry = {"rocsparse_csr_spmm_us": round(m * 1e3, 3),
+                         "rocsparse_gflops": round(2.0 * nnz * N / (m * 1e-3) / 1e9, 1)}
+                if A_dn is not None:
+                    for _ in range(3):
+                        torch.mm(A_dn, Bs[N])
+                    _, m2 = time_kernel_events(torch, lambda N=N: torch.mm(A_dn, Bs[N]), 10, batch=5)
+                    entry["rocblas_sgemm_us"] = round(m2 * 1e3, 3)
+                    entry["rocblas_effective_gflops"] = round(2.0 * nnz * N / (m2 * 1e-3) / 1e9, 1)
+                baselines[str(N)] = entry
+        except Exception as exc:  # comparison systems are context, never a reason to fail the bench
+            baselines = {"error": repr(exc)}
+
+    if args.copy_calibration:
+        src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    # CPU baseline: the oracle as it stands (row-parallel build of the same
+    # source), same products, host cores of this machine.
+    from oracle import spmm_oracle
+    host_B = {N: gen.activations_for(csr, N) for N in cols}
+    cap_rows = csr.M
+    sample = "full workload"
+    if nnz * sum(cols) > 4e9:  # bound the CPU work to roughly 10-30 s
+        cap_rows = max(4, int(csr.M * 4e9 / (nnz * sum(cols))) // 4 * 4)
+        sample = "first %d of %d rows" % (cap_rows, csr.M)
+    sub_ptr = csr.row_ptr[:cap_rows + 1]
+    sub_nnz = int(sub_ptr[-1])
+    best = None
+    for _ in range(0 if args.no_cpu else 3):
+        t0 = time.perf_counter()
+        for N in cols:
+            spmm_oracle.spmm(sub_ptr, csr.col_idx[:sub_nnz], csr.vals[:sub_nnz], host_B[N],
+                             K=csr.K, want_abs=False, parallel=True)
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    cpu = {"value": round(2.0 * sub_nnz * sum(cols) / best / 1e9, 3) if best else None, "unit": "GFLOP/s",
+           "cores": spmm_oracle.threads(True), "kind": "oracle",
+           "sample": "%s, best of 3, double accumulation, OpenMP over rows" % sample}
+
+    out = {"metric": "fp32 CSR SpMM GFLOP/s (2*nnz*bCols)", "value": round(value, 2), "unit": "GFLOP/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+           "data": "synthetic",
+           "config": {"workload": label, "M": csr.M, "K": csr.K, "nnz": nnz, "bCols": list(cols),
+                      "plan": {k: info[k] for k in ("ufi", "ufk", "group_nnz", "n_groups", "n_blocks",
+                                                    "n_split", "n_enum", "n_chunks", "device_bytes")},
+                      "plan_create_s": round(plan_s, 4), "row_stats": gen.row_stats(csr)},
+           "roofline": roofline, "cpu_baseline": cpu, "per_bcols": per_cols, "baselines": baselines}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

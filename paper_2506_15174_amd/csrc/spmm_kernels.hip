@@ -279,15 +279,37 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                     // the enumerated block of chunk c (paper Listing 7); its B rows are
                     // older than the (D - 1) * Q loads issued since
                     const uint32_t pattern = h_now & HDR_PATTERN_MASK;
-                    wait_for<(D - 1) * Q>(b[s]);
+                    if constexpr (S <= 2) {
+                        // wide slices: request the value blocks of all UFI rows before
+                        // the wait for the B rows (blocks of rows outside the pattern
+                        // are never used), so the LDS latency hides behind it
+                        uint32_t a[UFI][Q];
 #pragma unroll
-                    for (int r = 0; r < UFI; ++r) {
-                        if (pattern & (1u << r)) {
-                            uint32_t a[Q];
-                            lds_read<Q>(a, win, at_val);
+                        for (int r = 0; r < UFI; ++r)
+                            lds_read<Q>(a[r], win,
+                                        at_val + (uint32_t)UFK *
+                                                     (uint32_t)__builtin_popcount(pattern & ((1u << r) - 1u)));
+                        at_val += (uint32_t)UFK * (uint32_t)__builtin_popcount(pattern);
+                        wait_for<(D - 1) * Q>(b[s]);
 #pragma unroll
-                            for (int q = 0; q < Q; ++q) fma_acc(acc[r], __uint_as_float(a[q]), b[s][q]);
-                            at_val += (uint32_t)UFK;
+                        for (int r = 0; r < UFI; ++r) {
+                            if (pattern & (1u << r)) {
+#pragma unroll
+                                for (int q = 0; q < Q; ++q) fma_acc(acc[r], __uint_as_float(a[r][q]), b[s][q]);
+                            }
+                        }
+                    } else {
+                        // narrow slices: one small LDS read per row of the pattern
+                        wait_for<(D - 1) * Q>(b[s]);
+#pragma unroll
+                        for (int r = 0; r < UFI; ++r) {
+                            if (pattern & (1u << r)) {
+                                uint32_t a[Q];
+                                lds_read<Q>(a, win, at_val);
+#pragma unroll
+                                for (int q = 0; q < Q; ++q) fma_acc(acc[r], __uint_as_float(a[q]), b[s][q]);
+                                at_val += (uint32_t)UFK;
+                            }
                         }
                     }
 
