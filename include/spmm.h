@@ -39,12 +39,12 @@ typedef enum {
 /* Schedule constants and sizes of a plan (all read-only facts). */
 typedef struct {
     int64_t M, K, nnz;
-    int32_t ufi;           /* rows per panel: height of the register tile (the paper's UFi) */
+    int32_t ufi;           /* rows per panel: height of the register tile (the paper's UFi): 4, 2 or 1 */
     int32_t ufk;           /* enumerated columns in flight per wave (the paper's UFk) */
     int32_t group_nnz;     /* nonzero budget of one row group (one wave's work item) */
     int32_t group_panels;  /* most panels a row group may hold */
     int64_t n_groups;      /* row groups = wave-level work items, in launch order */
-    int64_t n_blocks;      /* workgroups of one launch (16 wave slots each) */
+    int64_t n_blocks;      /* workgroups of one launch (8 wave slots each) */
     int64_t n_split;       /* row groups that are pieces of a panel too heavy for one group */
     int64_t n_enum;        /* enumerated columns: B rows a column tile must fetch per execute */
     int64_t n_chunks;      /* chunks: runs of at most ufk enumerated columns of one pattern */
@@ -58,7 +58,7 @@ typedef struct {
     int32_t group_panels;  /* override the panel cap per row group (>= 1) */
     int32_t host_only;     /* nonzero: build the plan in host memory only (no device needed;
                               such a plan can be described and exported but not executed) */
-    int32_t reserved;
+    int32_t ufi;           /* force the rows per panel: 1, 2 or 4 (0 = choose) */
 } spmm_options_t;
 
 /*
@@ -141,7 +141,7 @@ spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_
  *                      chunk (unused slots repeat a real column); per chunk one block
  *                      of ufk float bit patterns per set pattern row in ascending row
  *                      order (zeros in unused slots)
- *   SPMM_ARRAY_ITEMS   16 words per wave slot, 16 slots per workgroup, launch order:
+ *   SPMM_ARRAY_ITEMS   16 words per wave slot, 8 slots per workgroup, launch order:
  *                      first row, rows, first chunk, chunks, first record word, flags
  *                      (1 piece of a split panel, 2 idle slot, 4 workgroup with split
  *                      panels), the slot's share of the split-panel sums (pieces to

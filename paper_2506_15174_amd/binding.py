@@ -41,7 +41,7 @@ class PlanInfo(ctypes.Structure):
 
 class Options(ctypes.Structure):
     _fields_ = [("group_nnz", ctypes.c_int32), ("group_panels", ctypes.c_int32),
-                ("host_only", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("host_only", ctypes.c_int32), ("ufi", ctypes.c_int32)]
 
 
 class SpmmError(RuntimeError):
@@ -107,15 +107,18 @@ class Plan:
 
     def __init__(self, handle):
         self._h = handle
+        self._info = None
 
     @property
     def handle(self):
         return self._h
 
     def describe(self):
-        info = PlanInfo()
-        _check(load().spmm_plan_describe(self._h, ctypes.byref(info)), "spmm_plan_describe")
-        return info.as_dict()
+        if self._info is None:  # a plan is immutable: ask once
+            info = PlanInfo()
+            _check(load().spmm_plan_describe(self._h, ctypes.byref(info)), "spmm_plan_describe")
+            self._info = info.as_dict()
+        return dict(self._info)
 
     def get_groups(self):
         n = self.describe()["n_groups"]
@@ -134,7 +137,9 @@ class Plan:
 
     def execute_raw(self, B_ptr, N, C_ptr, stream_ptr=None):
         """spmm_execute with raw device addresses (ints)."""
-        _check(load().spmm_execute(self._h, B_ptr, int(N), C_ptr, stream_ptr), "spmm_execute")
+        st = _lib.spmm_execute(self._h, B_ptr, N, C_ptr, stream_ptr)
+        if st != SPMM_OK:
+            raise SpmmError(st, "spmm_execute")
 
     def execute(self, B, C=None, stream=None):
         """spmm_execute on torch tensors (device memory and stream plumbing only).
@@ -146,7 +151,7 @@ class Plan:
         import torch
         if not (B.is_cuda and B.dtype == torch.float32 and B.is_contiguous() and B.dim() == 2):
             raise ValueError("B must be a contiguous 2-D float32 device tensor")
-        info = self.describe()
+        info = self._info or self.describe()
         if B.shape[0] != info["K"]:
             raise ValueError("B has %d rows, A has %d columns" % (B.shape[0], info["K"]))
         N = B.shape[1]
@@ -171,15 +176,15 @@ class Plan:
             pass
 
 
-def plan_create(M, K, row_ptr, col_idx, vals, group_nnz=0, group_panels=0, host_only=False):
+def plan_create(M, K, row_ptr, col_idx, vals, group_nnz=0, group_panels=0, host_only=False, ufi=0):
     """spmm_plan_create / spmm_plan_create_ex on numpy host arrays."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
     vals = np.ascontiguousarray(vals, dtype=np.float32)
     handle = ctypes.c_void_p()
     lib = load()
-    if group_nnz or group_panels or host_only:
-        opts = Options(int(group_nnz), int(group_panels), 1 if host_only else 0, 0)
+    if group_nnz or group_panels or host_only or ufi:
+        opts = Options(int(group_nnz), int(group_panels), 1 if host_only else 0, int(ufi))
         st = lib.spmm_plan_create_ex(ctypes.byref(handle), int(M), int(K), _ptr(row_ptr),
                                      _ptr(col_idx), _ptr(vals), ctypes.byref(opts))
     else:

@@ -80,9 +80,12 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
     InspectorOptions io;
     io.group_nnz = env_int("SPMM_GROUP_NNZ");
     io.group_panels = env_int("SPMM_GROUP_PANELS");
+    io.ufi = env_int("SPMM_UFI");
     bool host_only = false;
     if (opts) {
         if (opts->group_nnz < 0 || opts->group_panels < 0) return SPMM_ERR_INVALID_ARG;
+        if (opts->ufi != 0 && opts->ufi != 1 && opts->ufi != 2 && opts->ufi != 4) return SPMM_ERR_INVALID_ARG;
+        if (opts->ufi > 0) io.ufi = opts->ufi;
         if (opts->group_nnz > 0) io.group_nnz = opts->group_nnz;
         if (opts->group_panels > 0) io.group_panels = opts->group_panels;
         host_only = opts->host_only != 0;
@@ -161,7 +164,7 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
         a.C = C + j0;
         a.width = left < tile ? left : tile;
         a.b_bytes = wide ? 0u : (uint32_t)(b_total - (uint64_t)j0 * 4u);
-        const int e = spmm_launch_chunks(a, slices, wide, stream);
+        const int e = spmm_launch_chunks(a, h.ufi, slices, wide, stream);
         if (e != 0) return SPMM_ERR_HIP;
         j0 += a.width;
     }
@@ -184,7 +187,7 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
     out->M = h.M;
     out->K = h.K;
     out->nnz = h.nnz;
-    out->ufi = UFI;
+    out->ufi = h.ufi;
     out->ufk = UFK;
     out->group_nnz = h.group_nnz;
     out->group_panels = h.group_panels;

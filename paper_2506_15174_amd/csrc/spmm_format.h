@@ -19,9 +19,9 @@
 
 namespace spmm_fmt {
 
-// Rows per panel: height of the register tile (the paper's UFi).
-constexpr int UFI = 4;
-constexpr int N_PATTERNS = (1 << UFI) - 1;  // 15 nonzero patterns (paper Section 2)
+// Rows per panel: height of the register tile (the paper's UFi).  A plan uses
+// 4, 2 or 1; a panel of u rows has 2^u - 1 nonzero patterns (paper Section 2).
+constexpr int MAX_UFI = 4;
 
 // Enumerated columns per chunk (the paper's UFk).
 constexpr int UFK = 8;
@@ -66,10 +66,9 @@ constexpr int STREAM_TAIL_PAD = 16;
 // Waves per workgroup.  One wave executes one row group; a workgroup ("block")
 // holds up to WAVES_PER_WG of them.  A panel too heavy for one wave is cut into
 // at most WAVES_PER_WG pieces that sit in one block and meet in LDS.
-constexpr int WAVES_PER_WG = 16;
-// Most split panels one block may hold: WAVES_PER_WG / UFI, so that every
+constexpr int WAVES_PER_WG = 8;
+// A block holds at most WAVES_PER_WG / ufi split panels, so that every
 // (panel, row) sum after the barrier has a wave of its own.
-constexpr int SPLIT_PANELS_PER_WG = WAVES_PER_WG / UFI;
 
 // Wave-slot descriptor: WAVES_PER_WG per block, launch order.
 constexpr int ITEM_WORDS = 16;

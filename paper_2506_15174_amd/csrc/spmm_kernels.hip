@@ -2,7 +2,8 @@
 // the inspector (paper Section 3.3 "Sparse Coarsen", Listings 5-7, re-derived
 // for wave64 and for the memory paths of a CDNA4 compute unit).
 //
-// One wave executes one row group; up to 16 waves form a workgroup.
+// One wave executes one row group; up to 8 waves form a workgroup, and the
+// register budget (at most 128 VGPRs) lets two workgroups share a compute unit.
 //
 //   * Lanes run along j, the columns of B and C (the paper's map(j, .),
 //     Listing 5).  A vector load costs the compute unit's address path the same
@@ -176,12 +177,13 @@ template <int Q> __device__ __forceinline__ void lds_read(uint32_t (&out)[Q], co
     }
 }
 
+// UFI   rows per panel (1, 2, 4): height of the register tile
 // S     slices per wave (1, 2, 4, 8); a slice has 64 / S lanes and UFK / S column slots per chunk
 // VW    columns per lane (4 with 16-byte loads; 1 for the generic path, S == 1 only)
 // D     chunks of B rows in flight per wave
 // WIDE  64-bit addressing of B
-template <int S, int VW, int D, bool WIDE>
-__global__ __launch_bounds__(64 * WAVES_PER_WG) void
+template <int UFI, int S, int VW, int D, bool WIDE>
+__global__ __launch_bounds__(64 * WAVES_PER_WG, 4) void
 spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                    const uint32_t *__restrict__ wins_g, const uint32_t *__restrict__ items_g,
                    const float *__restrict__ B, uint32_t b_bytes, float *__restrict__ C, int32_t ldn,
@@ -380,19 +382,27 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
 
 }  // namespace
 
-#define SPMM_LAUNCH(S, VW, D, WIDE)                                                                   \
-    hipLaunchKernelGGL((spmm_chunks_kernel<S, VW, D, WIDE>), dim3((unsigned)a.n_blocks),              \
-                       dim3(64 * WAVES_PER_WG), 0, (hipStream_t)stream, a.stream, a.wins,             \
-                       a.items, a.B, a.b_bytes, a.C, a.ldn, a.width)
+#define SPMM_LAUNCH(U, S, VW, D, WIDE)                                                                \
+    hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE>), dim3((unsigned)a.n_blocks),           \
+                       dim3(64 * WAVES_PER_WG), 0, (hipStream_t)stream, a.stream, a.wins, a.items,    \
+                       a.B, a.b_bytes, a.C, a.ldn, a.width)
 
-int spmm_launch_chunks(const spmm_launch_args &a, int slices, bool wide, void *stream)
+#define SPMM_LAUNCH_SLICES(U)                                                                         \
+    switch (slices) {                                                                                 \
+    case 2: if (wide) SPMM_LAUNCH(U, 2, 4, 3, true); else SPMM_LAUNCH(U, 2, 4, 3, false); break;      \
+    case 4: if (wide) SPMM_LAUNCH(U, 4, 4, 6, true); else SPMM_LAUNCH(U, 4, 4, 6, false); break;      \
+    case 8: if (wide) SPMM_LAUNCH(U, 8, 4, 8, true); else SPMM_LAUNCH(U, 8, 4, 8, false); break;      \
+    default: if (wide) SPMM_LAUNCH(U, 1, 1, 3, true); else SPMM_LAUNCH(U, 1, 1, 3, false); break;     \
+    }
+
+int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int slices, bool wide, void *stream)
 {
     if (a.n_blocks <= 0) return 0;
-    switch (slices) {
-    case 2: if (wide) SPMM_LAUNCH(2, 4, 3, true); else SPMM_LAUNCH(2, 4, 3, false); break;
-    case 4: if (wide) SPMM_LAUNCH(4, 4, 6, true); else SPMM_LAUNCH(4, 4, 6, false); break;
-    case 8: if (wide) SPMM_LAUNCH(8, 4, 8, true); else SPMM_LAUNCH(8, 4, 8, false); break;
-    default: if (wide) SPMM_LAUNCH(1, 1, 3, true); else SPMM_LAUNCH(1, 1, 3, false); break;
+    switch (ufi) {
+    case 4: SPMM_LAUNCH_SLICES(4) break;
+    case 2: SPMM_LAUNCH_SLICES(2) break;
+    case 1: SPMM_LAUNCH_SLICES(1) break;
+    default: return (int)hipErrorInvalidValue;
     }
     return (int)hipGetLastError();
 }

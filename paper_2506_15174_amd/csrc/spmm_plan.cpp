@@ -35,16 +35,16 @@ struct Group {
 struct Entry {
     int32_t col;
     uint32_t pattern;
-    float v[UFI];  // indexed by row inside the panel
+    float v[MAX_UFI];  // indexed by row inside the panel
 };
 
-// Nonzero budget of a row group: aim at about 8192 groups (256 compute units x
-// 32 resident waves), in steps of 32, never below 128 nor above 1024 nonzeros.
+// Nonzero budget of a row group: aim at about 4096 groups (256 compute units x
+// 16 resident waves), in steps of 32, never below 32 nor above 1024 nonzeros.
 int32_t choose_group_nnz(int64_t nnz)
 {
-    int64_t g = (nnz + 8191) / 8192;
+    int64_t g = (nnz + 4095) / 4096;
     g = (g + 31) / 32 * 32;
-    if (g < 128) g = 128;
+    if (g < 32) g = 32;
     if (g > 1024) g = 1024;
     return (int32_t)g;
 }
@@ -54,6 +54,7 @@ struct Emitter {
     // chunks' value blocks back to back (UFK words per set pattern row)
     std::vector<uint32_t> hdr, cols, vals;
     int64_t n_enum = 0;
+    int ufi = MAX_UFI;
 
     // Emits one chunk of `count` entries (all of pattern `pattern`).
     void chunk(const Entry *e, int count, uint32_t pattern, bool end_panel)
@@ -66,7 +67,7 @@ struct Emitter {
             if (count > 0) c = e[u < count ? u : count - 1].col;
             cols.push_back((uint32_t)c);
         }
-        for (int r = 0; r < UFI; ++r) {
+        for (int r = 0; r < ufi; ++r) {
             if (!(pattern & (1u << r))) continue;
             for (int u = 0; u < UFK; ++u) {
                 uint32_t bits = 0;
@@ -96,6 +97,95 @@ struct Emitter {
     }
 };
 
+// Row groups in creation order, from row_ptr alone.  Panels (ufi consecutive
+// rows) are taken in order.  A panel heavier than the budget G is cut into
+// nseg pieces of equal size of its schedule order: want = min(8, ceil(pn / G)),
+// size = ceil(pn / want), nseg = ceil(pn / size); the last piece takes the rest.
+// Lighter panels are packed greedily: a group closes when the next panel would
+// exceed the budget or the panel cap.
+std::vector<Group> make_groups(const int32_t *row_ptr, int64_t M, int ufi, int64_t G, int64_t GP)
+{
+    std::vector<Group> groups;
+    const int64_t P = (M + ufi - 1) / ufi;
+    bool open = false;
+    Group cur{};
+    int64_t cur_panels = 0;
+    auto flush = [&]() {
+        if (open) groups.push_back(cur);
+        open = false;
+    };
+    for (int64_t p = 0; p < P; ++p) {
+        const int64_t r0 = p * ufi, r1 = std::min<int64_t>(M, r0 + ufi);
+        const int64_t a = row_ptr[r0], b = row_ptr[r1];
+        const int64_t pn = b - a;
+        if (pn > G) {
+            flush();
+            const int64_t want = std::min<int64_t>(WAVES_PER_WG, (pn + G - 1) / G);
+            const int64_t size = (pn + want - 1) / want;
+            const int64_t nseg = (pn + size - 1) / size;
+            for (int64_t s = 0; s < nseg; ++s) {
+                Group g{};
+                g.row_begin = (int32_t)r0;
+                g.row_end = (int32_t)r1;
+                g.nnz_begin = (int32_t)(a + s * size);
+                g.nnz_end = (int32_t)std::min<int64_t>(b, a + (s + 1) * size);
+                g.flags = FLAG_SPLIT;
+                g.seg = (int32_t)s;
+                g.nseg = (int32_t)nseg;
+                groups.push_back(g);
+            }
+            continue;
+        }
+        if (open && ((int64_t)cur.nnz_end - cur.nnz_begin + pn > G || cur_panels == GP)) flush();
+        if (!open) {
+            cur = Group{};
+            cur.row_begin = (int32_t)r0;
+            cur.nnz_begin = (int32_t)a;
+            cur.flags = 0;
+            cur_panels = 0;
+            open = true;
+        }
+        cur.row_end = (int32_t)r1;
+        cur.nnz_end = (int32_t)b;
+        cur_panels += 1;
+    }
+    flush();
+    return groups;
+}
+
+// Workgroups the groups will occupy: split panels are packed in order of
+// decreasing weight (at most 8 / ufi per workgroup, pieces never straddle a
+// workgroup), whole-panel groups 8 per workgroup.
+int64_t count_blocks(const std::vector<Group> &groups, int ufi)
+{
+    std::vector<std::pair<int64_t, int>> heads;  // (panel nnz, pieces)
+    int64_t whole = 0;
+    for (size_t i = 0; i < groups.size(); ++i) {
+        const Group &g = groups[i];
+        if (!(g.flags & FLAG_SPLIT)) whole += 1;
+        else if (g.seg == 0)
+            heads.push_back({(int64_t)groups[i + (size_t)g.nseg - 1].nnz_end - g.nnz_begin, g.nseg});
+    }
+    std::stable_sort(heads.begin(), heads.end(),
+                     [](const std::pair<int64_t, int> &x, const std::pair<int64_t, int> &y) { return x.first > y.first; });
+    int64_t blocks = (whole + WAVES_PER_WG - 1) / WAVES_PER_WG;
+    int used = WAVES_PER_WG, panels = WAVES_PER_WG / ufi;
+    for (const auto &h : heads) {
+        if (used + h.second > WAVES_PER_WG || panels == WAVES_PER_WG / ufi) {
+            blocks += 1;
+            used = 0;
+            panels = 0;
+        }
+        used += h.second;
+        panels += 1;
+    }
+    return blocks;
+}
+
+// Workgroups wanted before a shorter panel is considered: three quarters of two
+// per compute unit.
+constexpr int64_t MIN_BLOCKS = 384;
+
 }  // namespace
 
 int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *col_idx,
@@ -121,70 +211,49 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         const int64_t G = out.group_nnz;
         const int64_t GP = out.group_panels;
 
-        // ---- 1. row groups, from row_ptr alone -------------------------------
-        // Panels (UFI consecutive rows) are taken in order.  A panel heavier than
-        // the budget G is cut into nseg = min(16, ceil(nnz / G)) pieces of
-        // ceil(nnz / nseg) nonzeros of its schedule order (the last piece takes
-        // the rest).  Lighter panels are packed greedily: a group closes when the
-        // next panel would exceed the budget or the panel cap.
+        // ---- 1. row groups and the panel height, from row_ptr alone ------------
+        // The tallest panel (most B reuse) that still yields enough workgroups to
+        // occupy the chip is taken; a forced height skips the search.
+        int ufi = opts.ufi;
         std::vector<Group> groups;
-        const int64_t P = (M + UFI - 1) / UFI;
-        {
-            bool open = false;
-            Group cur{};
-            int64_t cur_panels = 0;
-            auto flush = [&]() {
-                if (open) groups.push_back(cur);
-                open = false;
-            };
-            for (int64_t p = 0; p < P; ++p) {
-                const int64_t r0 = p * UFI, r1 = std::min<int64_t>(M, r0 + UFI);
-                const int64_t a = row_ptr[r0], b = row_ptr[r1];
-                const int64_t pn = b - a;
-                if (pn > G) {
-                    flush();
-                    const int64_t want = std::min<int64_t>(WAVES_PER_WG, (pn + G - 1) / G);
-                    const int64_t size = (pn + want - 1) / want;
-                    const int64_t nseg = (pn + size - 1) / size;
-                    for (int64_t s = 0; s < nseg; ++s) {
-                        Group g{};
-                        g.row_begin = (int32_t)r0;
-                        g.row_end = (int32_t)r1;
-                        g.nnz_begin = (int32_t)(a + s * size);
-                        g.nnz_end = (int32_t)std::min<int64_t>(b, a + (s + 1) * size);
-                        g.flags = FLAG_SPLIT;
-                        g.seg = (int32_t)s;
-                        g.nseg = (int32_t)nseg;
-                        groups.push_back(g);
-                    }
-                    continue;
+        if (ufi != 1 && ufi != 2 && ufi != 4) {
+            ufi = 1;
+            int64_t best_blocks = -1;
+            for (int cand = MAX_UFI; cand >= 1; cand /= 2) {
+                std::vector<Group> g = make_groups(row_ptr, M, cand, G, GP);
+                const int64_t blocks = count_blocks(g, cand);
+                if (blocks >= MIN_BLOCKS) {
+                    ufi = cand;
+                    groups.swap(g);
+                    best_blocks = blocks;
+                    break;
                 }
-                if (open && ((int64_t)cur.nnz_end - cur.nnz_begin + pn > G || cur_panels == GP)) flush();
-                if (!open) {
-                    cur = Group{};
-                    cur.row_begin = (int32_t)r0;
-                    cur.nnz_begin = (int32_t)a;
-                    cur.flags = 0;
-                    cur_panels = 0;
-                    open = true;
+                if (blocks > best_blocks) {
+                    best_blocks = blocks;
+                    ufi = cand;
+                    groups.swap(g);
                 }
-                cur.row_end = (int32_t)r1;
-                cur.nnz_end = (int32_t)b;
-                cur_panels += 1;
             }
-            flush();
+        } else {
+            groups = make_groups(row_ptr, M, ufi, G, GP);
         }
+        out.ufi = ufi;
+        const int UFI = ufi;  // panel height of this plan
+        const int N_PATTERNS = (1 << UFI) - 1;
+        const int SPLIT_PANELS_PER_WG = WAVES_PER_WG / UFI;
+        const int64_t P = (M + UFI - 1) / UFI;
         const int64_t n_groups = (int64_t)groups.size();
 
         // ---- 2. enumeration and emission, panel by panel ----------------------
         Emitter em;
+        em.ufi = UFI;
         em.hdr.reserve((size_t)(nnz / 4 + P + 16));
         em.cols.reserve((size_t)(nnz / 4 + P + 16) * UFK);
         em.vals.reserve((size_t)(nnz + nnz / 2 + 64));
 
         std::vector<int32_t> order;                  // canonical order of one row
-        std::vector<int32_t> ccol[UFI];              // canonical columns per panel row
-        std::vector<float> cval[UFI];
+        std::vector<int32_t> ccol[MAX_UFI];          // canonical columns per panel row
+        std::vector<float> cval[MAX_UFI];
         std::vector<Entry> merged, by_pattern, piece;
         struct Flat { int32_t entry; int32_t row; };
         std::vector<Flat> flat;
@@ -231,8 +300,8 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                 // a row meets the t-th occurrences in the other rows, so a column
                 // stored twice in one row yields two enumerated columns.
                 merged.clear();
-                size_t head[UFI] = {0, 0, 0, 0};
-                uint32_t layer[UFI] = {0, 0, 0, 0};
+                size_t head[MAX_UFI] = {0, 0, 0, 0};
+                uint32_t layer[MAX_UFI] = {0, 0, 0, 0};
                 for (;;) {
                     int32_t best_col = INT32_MAX;
                     uint32_t best_layer = UINT32_MAX;
@@ -265,7 +334,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                 // list columns of equal pattern together (stable: ascending column inside a pattern)
                 by_pattern.resize(merged.size());
                 {
-                    size_t count[N_PATTERNS + 2] = {0};
+                    size_t count[(1 << MAX_UFI) + 1] = {0};
                     for (const Entry &e : merged) count[e.pattern + 1]++;
                     for (int q = 1; q <= N_PATTERNS + 1; ++q) count[q] += count[q - 1];
                     for (const Entry &e : merged) by_pattern[count[e.pattern]++] = e;

@@ -8,6 +8,7 @@
 
 struct HostPlan {
     int64_t M = 0, K = 0, nnz = 0;
+    int32_t ufi = 0;           // rows per panel (4, 2 or 1)
     int32_t group_nnz = 0;     // nonzero budget per row group
     int32_t group_panels = 0;  // panel cap per row group
 
@@ -27,6 +28,7 @@ struct HostPlan {
 struct InspectorOptions {
     int32_t group_nnz = 0;     // 0 = choose
     int32_t group_panels = 0;  // 0 = choose
+    int32_t ufi = 0;           // 0 = choose; else 1, 2 or 4
 };
 
 // Status codes follow spmm_status_t (0 ok, 1 invalid argument, 2 invalid CSR,

@@ -7,25 +7,24 @@ evaluates the product from the chunk arrays the way the kernel consumes them.
 """
 import numpy as np
 
-UFI = 4
+MAX_UFI = 4
 UFK = 8
+MIN_BLOCKS = 384
 ITEM_WORDS = 16
 WIN_WORDS = 1024
 
 
-WAVES_PER_WG = 16
+WAVES_PER_WG = 8
 FLAG_SPLIT, FLAG_IDLE, FLAG_SYNC = 1, 2, 4
 
 
-def derive_groups(row_ptr, M, group_nnz, group_panels):
-    """Row groups in launch order as an (n, 5) int32 array, from row_ptr only."""
-    rp = [int(x) for x in row_ptr]
+def _groups_for(rp, M, ufi, group_nnz, group_panels):
     whole, split = [], []          # split: list of panels, each a list of pieces
     cur = None
     cur_panels = 0
-    P = (M + UFI - 1) // UFI
+    P = (M + ufi - 1) // ufi
     for p in range(P):
-        r0, r1 = p * UFI, min(M, p * UFI + UFI)
+        r0, r1 = p * ufi, min(M, p * ufi + ufi)
         a, b = rp[r0], rp[r1]
         pn = b - a
         if pn > group_nnz:
@@ -51,8 +50,43 @@ def derive_groups(row_ptr, M, group_nnz, group_panels):
     # first; ties keep row order
     split.sort(key=lambda pieces: -(pieces[-1][3] - pieces[0][2]))
     whole.sort(key=lambda g: -(g[3] - g[2]))
+    return split, whole
+
+
+def _blocks_for(split, whole, ufi):
+    blocks = -(-len(whole) // WAVES_PER_WG)
+    used, panels = WAVES_PER_WG, WAVES_PER_WG // ufi
+    for pieces in split:
+        if used + len(pieces) > WAVES_PER_WG or panels == WAVES_PER_WG // ufi:
+            blocks += 1
+            used, panels = 0, 0
+        used += len(pieces)
+        panels += 1
+    return blocks
+
+
+def derive_groups(row_ptr, M, group_nnz, group_panels, ufi=0):
+    """(panel height, row groups in launch order as an (n, 5) int32 array, workgroups),
+    from row_ptr only.  ufi = 0 re-derives the inspector's choice: the tallest
+    panel of 4, 2, 1 rows that yields at least MIN_BLOCKS workgroups, else the one
+    that yields the most (the taller on ties)."""
+    rp = [int(x) for x in row_ptr]
+    if ufi:
+        split, whole = _groups_for(rp, M, ufi, group_nnz, group_panels)
+        best = (ufi, split, whole, _blocks_for(split, whole, ufi))
+    else:
+        best = None
+        for cand in (4, 2, 1):
+            split, whole = _groups_for(rp, M, cand, group_nnz, group_panels)
+            blocks = _blocks_for(split, whole, cand)
+            if blocks >= MIN_BLOCKS:
+                best = (cand, split, whole, blocks)
+                break
+            if best is None or blocks > best[3]:
+                best = (cand, split, whole, blocks)
+    ufi, split, whole, blocks = best
     out = [piece for pieces in split for piece in pieces] + whole
-    return np.array(out, dtype=np.int32).reshape(-1, 5)
+    return ufi, np.array(out, dtype=np.int32).reshape(-1, 5), blocks
 
 
 def canonical_csr(row_ptr, col_idx, vals):
@@ -62,7 +96,7 @@ def canonical_csr(row_ptr, col_idx, vals):
     return rows[order], np.asarray(col_idx)[order], np.asarray(vals, dtype=np.float32).view(np.uint32)[order]
 
 
-def check_blocks(items):
+def check_blocks(items, ufi):
     """Structural invariants of the wave-slot table."""
     items = items.reshape(-1, WAVES_PER_WG, ITEM_WORDS)
     for blk in items:
@@ -129,11 +163,11 @@ def walk_chunks(it, hdr, stream, wins):
     assert c == chunk0 + nchunks
 
 
-def decode_plan(items, hdr, stream, wins):
+def decode_plan(items, hdr, stream, wins, ufi):
     """Chunk arrays -> (row, col, value bits) arrays in the order the kernel
     consumes them.  Also checks the structural invariants of the format and
     raises AssertionError on any violation."""
-    check_blocks(items)
+    check_blocks(items, ufi)
     items = items.reshape(-1, ITEM_WORDS)
     out_rows, out_cols, out_bits = [], [], []
     for it in items:
@@ -150,12 +184,12 @@ def decode_plan(items, hdr, stream, wins):
             if count == 0:
                 assert end, "an empty chunk is the only chunk of an empty panel"
             assert rows_left > 0, "chunks after the last panel of the group"
-            rows_here = min(UFI, rows_left)
+            rows_here = min(ufi, rows_left)
             assert pattern < (1 << rows_here), "pattern names a row beyond the panel"
             if count:
                 assert np.all(cc[count:] == cc[count - 1]), "unused slots repeat the last real column"
             t = 0
-            for r in range(UFI):
+            for r in range(ufi):
                 if not (pattern >> r) & 1:
                     continue
                 block = blocks[t]
@@ -170,12 +204,12 @@ def decode_plan(items, hdr, stream, wins):
                 rows_left -= rows_here
         assert rows_left == 0
         if flags & FLAG_SPLIT:
-            assert nrows <= UFI
+            assert nrows <= ufi
     return (np.array(out_rows, dtype=np.int64), np.array(out_cols, dtype=np.int64),
             np.array(out_bits, dtype=np.uint32))
 
 
-def interpret_plan(items, hdr, stream, wins, B, M):
+def interpret_plan(items, hdr, stream, wins, B, M, ufi):
     """Evaluates C from the chunk arrays in float32, block by block, chunk by
     chunk, FMA by FMA (row blocks in ascending row, slots in ascending order;
     pieces of a split panel added in slot order by the wave slot the table names).
@@ -185,17 +219,17 @@ def interpret_plan(items, hdr, stream, wins, B, M):
     C = np.full((M, N), np.nan, dtype=np.float32)
     B64 = B.astype(np.float64)
     for blk in blocks:
-        tiles = np.zeros((WAVES_PER_WG, UFI, N), dtype=np.float32)
+        tiles = np.zeros((WAVES_PER_WG, ufi, N), dtype=np.float32)
         for w, it in enumerate(blk):
             row0, nrows, chunk0, nchunks, stream0, flags = (int(x) for x in it[:6])
             if flags & FLAG_IDLE:
                 continue
-            acc = np.zeros((UFI, N), dtype=np.float32)
+            acc = np.zeros((ufi, N), dtype=np.float32)
             row, rows_left = row0, nrows
             for h, cc, vblocks in walk_chunks(it, hdr, stream, wins):
                 pattern, end = h & 15, (h >> 8) & 1
                 t = 0
-                for r in range(UFI):
+                for r in range(ufi):
                     if not (pattern >> r) & 1:
                         continue
                     fv = vblocks[t].view(np.float32)
@@ -205,7 +239,7 @@ def interpret_plan(items, hdr, stream, wins, B, M):
                         # fused multiply-add: exact product and sum in double, one rounding
                         acc[r] = (a * B64[cc[u]] + acc[r].astype(np.float64)).astype(np.float32)
                 if end:
-                    rows_here = min(UFI, rows_left)
+                    rows_here = min(ufi, rows_left)
                     if flags & FLAG_SPLIT:
                         tiles[w] = acc
                     else:

@@ -79,6 +79,7 @@ def test_conv_config(torch_gpu, oracle, N):
     C, plan = gpu_product(torch_gpu, csr, B, guard_rows=4)
     check(oracle, csr, B, C)
     assert plan.describe()["n_split"] > 0  # 410 nonzeros per row: every panel is split
+    assert plan.describe()["ufi"] < 4      # 512 rows: shorter panels give the chip enough workgroups
 
 
 @pytest.mark.parametrize("shape_index,sparsity_index,N", [
@@ -94,9 +95,10 @@ def test_ffn_config(torch_gpu, oracle, shape_index, sparsity_index, N):
 def test_any_column_count_with_ragged_rows_and_split_panels(torch_gpu, oracle, N):
     csr = heavy_tail(39, 1500, 40 + N)   # M % 4 != 0, dense rows, empty rows
     B = gen.dense_activations(csr.K, N, 50 + N)
-    C, plan = gpu_product(torch_gpu, csr, B, guard_rows=3, group_nnz=96)
-    assert plan.describe()["n_split"] > 0
-    check(oracle, csr, B, C)
+    for ufi in (4, 2, 1):
+        C, plan = gpu_product(torch_gpu, csr, B, guard_rows=3, group_nnz=96, ufi=ufi)
+        assert plan.describe()["n_split"] > 0 and plan.describe()["ufi"] == ufi
+        check(oracle, csr, B, C)
 
 
 @pytest.mark.parametrize("group_nnz", [32, 64, 1000, 100000])
@@ -107,15 +109,16 @@ def test_group_budget_does_not_change_the_result_class(torch_gpu, oracle, group_
     check(oracle, csr, B, C)
 
 
+@pytest.mark.parametrize("ufi", [0, 1, 2, 4])
 @pytest.mark.parametrize("N", [32, 64, 128, 100])
-def test_small_integer_data_is_bit_exact(torch_gpu, oracle, N):
+def test_small_integer_data_is_bit_exact(torch_gpu, oracle, N, ufi):
     rng = np.random.default_rng(70 + N)
     M, K = 203, 900
     W = np.where(rng.random((M, K)) < 0.2, rng.integers(-8, 9, (M, K)), 0).astype(np.float32)
     W[17] = rng.integers(1, 9, K)          # a dense row: split panel, partial sums meet in scratch
     csr = gen.csr_from_dense(W)
     B = rng.integers(-16, 17, (K, N)).astype(np.float32)
-    C, plan = gpu_product(torch_gpu, csr, B, group_nnz=128)
+    C, plan = gpu_product(torch_gpu, csr, B, group_nnz=128, ufi=ufi)
     assert plan.describe()["n_split"] > 0
     C_ref, _ = oracle.spmm(csr.row_ptr, csr.col_idx, csr.vals, B)
     assert np.abs(C_ref).max() < 2 ** 24
@@ -182,6 +185,22 @@ def test_wide_addressing_kernels(torch_gpu, oracle):
             check(oracle, csr, B, C)
     finally:
         del os.environ["SPMM_FORCE_WIDE"]
+
+
+def test_unaligned_rows_take_the_one_column_per_lane_kernels(torch_gpu, oracle):
+    """N a multiple of 4 but B and C only 4-byte aligned: the 16-byte kernels
+    do not apply and the generic kernel must give the same class of result."""
+    csr = heavy_tail(45, 600, 97)
+    N = 64
+    B = gen.dense_activations(csr.K, N, 98)
+    plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, group_nnz=64)
+    flatB = torch_gpu.zeros(csr.K * N + 1, dtype=torch_gpu.float32, device="cuda")
+    flatC = torch_gpu.full((csr.M * N + 1,), float("nan"), dtype=torch_gpu.float32, device="cuda")
+    flatB[1:] = torch_gpu.from_numpy(B).cuda().reshape(-1)
+    plan.execute_raw(flatB.data_ptr() + 4, N, flatC.data_ptr() + 4, None)
+    torch_gpu.cuda.synchronize()
+    assert np.isnan(flatC[0].item())
+    check(oracle, csr, B, flatC[1:].reshape(csr.M, N).cpu().numpy())
 
 
 def test_execute_rejects_bad_arguments(torch_gpu):

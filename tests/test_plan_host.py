@@ -16,8 +16,8 @@ import pytest
 import paper_2506_15174_amd as spmm
 from workloads import generators as gen
 
-from plan_reference import (UFI, UFK, canonical_csr, decode_plan, derive_groups,
-                            interpret_plan)
+from plan_reference import (UFK, canonical_csr, decode_plan, derive_groups, interpret_plan,
+                            walk_chunks)
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -68,19 +68,23 @@ def test_library_exports_every_declared_symbol():
 
 @pytest.mark.parametrize("name", sorted(CASES))
 @pytest.mark.parametrize("group_nnz", [0, 32, 200])
-def test_row_groups_match_python_rederivation(name, group_nnz):
+@pytest.mark.parametrize("force_ufi", [0, 1, 2, 4])
+def test_row_groups_match_python_rederivation(name, group_nnz, force_ufi):
     csr = CASES[name]()
-    plan = host_plan(csr, group_nnz=group_nnz)
+    plan = host_plan(csr, group_nnz=group_nnz, ufi=force_ufi)
     info = plan.describe()
     assert (info["M"], info["K"], info["nnz"]) == (csr.M, csr.K, int(csr.row_ptr[-1]))
-    assert (info["ufi"], info["ufk"]) == (UFI, UFK)
+    assert info["ufk"] == UFK and info["ufi"] in (1, 2, 4)
     if group_nnz:
         assert info["group_nnz"] == group_nnz
+    if force_ufi:
+        assert info["ufi"] == force_ufi
     got = plan.get_groups()
-    want = derive_groups(csr.row_ptr, csr.M, info["group_nnz"], info["group_panels"])
+    UFI, want, blocks = derive_groups(csr.row_ptr, csr.M, info["group_nnz"], info["group_panels"], force_ufi)
+    assert UFI == info["ufi"] and blocks == info["n_blocks"]
     assert got.shape == want.shape and np.array_equal(got, want)
     assert info["n_groups"] == len(want) and info["n_split"] == int((want[:, 4] & 1).sum())
-    assert info["n_blocks"] * 16 * 16 == len(plan.get_array(spmm.ARRAY_ITEMS))
+    assert info["n_blocks"] * 8 * 16 == len(plan.get_array(spmm.ARRAY_ITEMS))
     # invariants: whole rows and the whole nonzero range are covered exactly once
     by_row = got[np.lexsort((got[:, 2], got[:, 0]))]
     nnz_cover = 0
@@ -92,7 +96,7 @@ def test_row_groups_match_python_rederivation(name, group_nnz):
             assert rb in (next_row, next_row - (re_ - rb))  # pieces share their panel's rows
             pn = int(csr.row_ptr[re_] - csr.row_ptr[rb])
             assert pn > info["group_nnz"]
-            assert ne - nb <= max(info["group_nnz"], -(-pn // 16))
+            assert ne - nb <= max(info["group_nnz"], -(-pn // 8))
         else:
             assert rb == next_row and rb % UFI == 0
             assert (nb, ne) == (csr.row_ptr[rb], csr.row_ptr[re_])
@@ -108,7 +112,7 @@ def test_row_groups_match_python_rederivation(name, group_nnz):
 
 
 def test_default_group_budget_rule():
-    for nnz, want in ((0, 128), (6554, 128), (1258291, 160), (13330308, 1024), (8192 * 512, 512)):
+    for nnz, want in ((0, 32), (6554, 32), (209715, 64), (1258291, 320), (13330308, 1024), (4096 * 512, 512)):
         row_ptr = np.array([0], dtype=np.int32)
         # the rule depends on nnz only: one row of that many entries is enough
         if nnz:
@@ -124,11 +128,12 @@ def test_default_group_budget_rule():
 
 @pytest.mark.parametrize("name", sorted(CASES))
 @pytest.mark.parametrize("group_nnz", [0, 32, 200])
-def test_format_round_trip_is_bit_exact(name, group_nnz):
+@pytest.mark.parametrize("force_ufi", [0, 1, 2, 4])
+def test_format_round_trip_is_bit_exact(name, group_nnz, force_ufi):
     csr = CASES[name]()
-    plan = host_plan(csr, group_nnz=group_nnz)
+    plan = host_plan(csr, group_nnz=group_nnz, ufi=force_ufi)
     items, hdr, stream, wins = arrays(plan)
-    rows, cc, bits = decode_plan(items, hdr, stream, wins)
+    rows, cc, bits = decode_plan(items, hdr, stream, wins, plan.describe()["ufi"])
     assert len(rows) == csr.row_ptr[-1] == plan.describe()["nnz"]
     order = np.lexsort((cc, rows))
     want_rows, want_cols, want_bits = canonical_csr(csr.row_ptr, csr.col_idx, csr.vals)
@@ -148,16 +153,15 @@ def test_unsorted_and_duplicate_columns_are_canonicalised():
     col_idx = np.array([7, 2, 7, 0, 2, 2, 7, 1, 7], dtype=np.int32)
     vals = np.array([1, 2, 3, 4, 5, 6, 7, 8, 9], dtype=np.float32)
     csr = gen.Csr(4, 8, row_ptr, col_idx, vals)
-    plan = host_plan(csr)
+    plan = host_plan(csr, ufi=4)
     items, hdr, stream, wins = arrays(plan)
-    rows, cc, bits = decode_plan(items, hdr, stream, wins)
+    rows, cc, bits = decode_plan(items, hdr, stream, wins, plan.describe()["ufi"])
     got = sorted(zip(rows.tolist(), cc.tolist(), bits.view(np.float32).tolist()))
     want = sorted(zip([0, 0, 0, 0, 0, 2, 2, 2, 3], col_idx.tolist(), vals.tolist()))
     assert got == want
     # column 7 is stored twice in row 0: its second occurrence cannot share an
     # enumerated column with the first, so 7 appears in two different column slots
     assert cc.tolist().count(7) == 4 and len(rows) == 9
-    from plan_reference import walk_chunks
     slots = []
     for it in items.reshape(-1, 16):
         if not int(it[5]) & 2:
@@ -166,7 +170,7 @@ def test_unsorted_and_duplicate_columns_are_canonicalised():
     assert slots.count(7) == 2 and slots.count(2) == 2
     # within a row, duplicates keep their stored order (3 after 1 for column 7 of row 0)
     B = np.eye(8, dtype=np.float32)
-    C = interpret_plan(items, hdr, stream, wins, B, 4)
+    C = interpret_plan(items, hdr, stream, wins, B, 4, 4)
     assert C[0, 7] == 4.0 and C[0, 2] == 7.0 and C[2, 2] == 6.0 and C[3, 7] == 9.0
     assert not C[1].any()
 
@@ -178,18 +182,17 @@ def test_every_pattern_of_a_four_row_panel_is_enumerated():
         for r in range(4):
             if (p >> r) & 1:
                 W[r, p - 1] = 10 * p + r
-    plan = host_plan(gen.csr_from_dense(W))
+    plan = host_plan(gen.csr_from_dense(W), ufi=4)
     items, hdr, stream, wins = arrays(plan)
-    from plan_reference import walk_chunks
     seen = {}
     for it in items.reshape(-1, 16):
         if not int(it[5]) & 2:
             for h, cols, _ in walk_chunks(it, hdr, stream, wins):
                 seen[h & 15] = int(cols[0])
-    assert sorted(seen) == list(range(1, 16)) and len(seen) == 2 ** UFI - 1
+    assert sorted(seen) == list(range(1, 16)) and len(seen) == 2 ** 4 - 1
     assert all(col == p - 1 for p, col in seen.items())
     # three rows give 2^3 - 1 = 7 patterns (caption of the paper's Figure 4)
-    plan3 = host_plan(gen.csr_from_dense(W[:3]))
+    plan3 = host_plan(gen.csr_from_dense(W[:3]), ufi=4)
     _, hdr3, _, _ = arrays(plan3)
     pats3 = {int(h) & 15 for h in hdr3[:plan3.describe()["n_chunks"]]}
     assert pats3 == set(range(1, 8))
@@ -205,13 +208,14 @@ def test_pattern_histogram_of_uniform_sparsity_matches_closed_form():
         rng = np.random.default_rng(seed)
         W = np.where(rng.random((M, K)) < d, 1.0, 0.0).astype(np.float32)
         csr = gen.csr_from_dense(W)
-        plan = host_plan(csr, group_nnz=1 << 20, group_panels=1 << 20)
+        plan = host_plan(csr, group_nnz=1 << 20, group_panels=1 << 20, ufi=4)
         info = plan.describe()
         items, hdr, stream, wins = arrays(plan)
         n = info["n_chunks"]
         pat = hdr[:n] & 15
         cnt = (hdr[:n] >> 4) & 15
         hist = np.bincount(pat, weights=cnt, minlength=16)
+        UFI = 4
         total_columns = (M // UFI) * K
         for p in range(1, 16):
             r = bin(p).count("1")
@@ -224,11 +228,12 @@ def test_pattern_histogram_of_uniform_sparsity_matches_closed_form():
 
 @pytest.mark.parametrize("name", ["tiny", "ragged_rows", "heavy_tail", "all_empty", "single_row"])
 @pytest.mark.parametrize("group_nnz", [0, 32])
-def test_chunk_arrays_evaluate_to_the_product(oracle, name, group_nnz):
+@pytest.mark.parametrize("force_ufi", [0, 1, 2, 4])
+def test_chunk_arrays_evaluate_to_the_product(oracle, name, group_nnz, force_ufi):
     csr = CASES[name]()
     B = gen.dense_activations(csr.K, 5, 99)
-    plan = host_plan(csr, group_nnz=group_nnz)
-    C = interpret_plan(*arrays(plan), B, csr.M)
+    plan = host_plan(csr, group_nnz=group_nnz, ufi=force_ufi)
+    C = interpret_plan(*arrays(plan), B, csr.M, plan.describe()["ufi"])
     C_ref, S = oracle.spmm(csr.row_ptr, csr.col_idx, csr.vals, B)
     err, bad_zero = oracle.parity_error(C, C_ref, S)
     assert err <= 1e-5 and bad_zero == 0
@@ -241,7 +246,7 @@ def test_plan_bytes_against_csr_bytes_trend():
     # slot and per chunk header of the staged stream.
     def ratio(sparsity):
         csr = gen.uniform_positions(512, 512, sparsity, 31)
-        info = host_plan(csr).describe()
+        info = host_plan(csr, ufi=4, group_nnz=4096).describe()  # whole panels, as in the paper's format
         plan_bytes = 4 * info["stream_words"]
         csr_bytes = 8 * info["nnz"] + 4 * (csr.M + 1)
         return plan_bytes / csr_bytes
@@ -270,6 +275,7 @@ def test_error_codes_of_the_boundary():
     assert status(2, 2, ok_rp, np.array([0, 2], np.int32), v) == spmm.SPMM_ERR_INVALID_CSR
     assert status(2, 2, ok_rp, np.array([0, -1], np.int32), v) == spmm.SPMM_ERR_INVALID_CSR
     assert status(2, 2, ok_rp, ci, v, group_nnz=-5) == spmm.SPMM_ERR_INVALID_ARG
+    assert status(2, 2, ok_rp, ci, v, ufi=3) == spmm.SPMM_ERR_INVALID_ARG
     lib = spmm.load()
     h = ctypes.c_void_p(123)
     assert lib.spmm_plan_create(ctypes.byref(h), 2, 2, None, None, None) == spmm.SPMM_ERR_INVALID_ARG
