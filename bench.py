@@ -69,6 +69,129 @@ def time_kernel_events(torch, fn, reps, batch=20):
     return sum(ts) / len(ts), ts[len(ts) // 2]
 
 
+_BASE = None
+
+
+def _baseline_lib():
+    """The comparison-system shim (hipSPARSE CSR SpMM with every algorithm the
+    header offers, rocBLAS SGEMM); built on demand, loaded after torch so that it
+    shares torch's HIP runtime."""
+    global _BASE
+    if _BASE is None:
+        import ctypes
+        from baselines import build as bbuild
+        if not os.path.exists(bbuild.LIB):
+            bbuild.build()
+        lib = ctypes.CDLL(bbuild.LIB)
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        lib.baseline_hipsparse_spmm.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, vp, ci, ci, vp]
+        lib.baseline_rocblas_sgemm.argtypes = [ci, ci, ci, vp, vp, vp, ci, ci, vp]
+        _BASE = lib
+    return _BASE
+
+
+def measure_baselines(torch, np, csr, cols, Bs, dense_limit=1 << 28):
+    """hipSPARSE CSR SpMM (best of its algorithms) and rocBLAS SGEMM on the same
+    device-resident inputs; times in microseconds, rates with the same numerator
+    2 nnz N as the library's own figure."""
+    import ctypes
+    out = {}
+    try:
+        lib = _baseline_lib()
+        nnz = int(csr.row_ptr[-1])
+        d_rp = torch.from_numpy(csr.row_ptr.astype(np.int32)).cuda()
+        d_ci = torch.from_numpy(csr.col_idx.astype(np.int32)).cuda()
+        d_v = torch.from_numpy(csr.vals).cuda()
+        A_dn = None
+        if csr.M * csr.K <= dense_limit:
+            A_dn = torch.zeros((csr.M, csr.K), dtype=torch.float32, device="cuda")
+            rows = torch.repeat_interleave(torch.arange(csr.M, device="cuda"),
+                                           torch.from_numpy(np.diff(csr.row_ptr).astype(np.int64)).cuda())
+            A_dn.index_put_((rows, d_ci.long()), d_v, accumulate=True)
+        for N in cols:
+            C = torch.empty((csr.M, N), dtype=torch.float32, device="cuda")
+            torch.cuda.synchronize()
+            ms = (ctypes.c_float * 4)(-1, -1, -1, -1)
+            entry = {}
+            if nnz > 0:
+                rc = lib.baseline_hipsparse_spmm(csr.M, csr.K, N, nnz, d_rp.data_ptr(), d_ci.data_ptr(),
+                                                 d_v.data_ptr(), Bs[N].data_ptr(), C.data_ptr(), 7, 5, ms)
+                good = [m for m in ms if m > 0]
+                if rc == 0 and good:
+                    best = min(good)
+                    entry["hipsparse_us_by_alg"] = [round(m * 1e3, 2) for m in ms]
+                    entry["hipsparse_best_us"] = round(best * 1e3, 3)
+                    entry["hipsparse_gflops"] = round(2.0 * nnz * N / (best * 1e-3) / 1e9, 1)
+            if A_dn is not None:
+                one = ctypes.c_float(-1)
+                rc = lib.baseline_rocblas_sgemm(csr.M, csr.K, N, A_dn.data_ptr(), Bs[N].data_ptr(), C.data_ptr(),
+                                                7, 5, ctypes.byref(one))
+                if rc == 0 and one.value > 0:
+                    entry["rocblas_sgemm_us"] = round(one.value * 1e3, 3)
+                    entry["rocblas_effective_gflops"] = round(2.0 * nnz * N / (one.value * 1e-3) / 1e9, 1)
+            out[str(N)] = entry
+    except Exception as exc:  # comparison systems are context, never a reason to fail the bench
+        out["error"] = repr(exc)
+    return out
+
+
+def run_sweep(args):
+    """Configuration 4: 48 magnitude-pruned matrices x bCols 32/64/128 against
+    hipSPARSE CSR SpMM and rocBLAS SGEMM; geometric means of the speedups and the
+    share of points where this library is faster (the shape of the paper's Table 1)."""
+    import math
+    import numpy as np
+    import torch
+    import paper_2506_15174_amd as spmm
+    from workloads import generators as gen
+    torch.cuda.set_device(0)
+    cols = (32, 64, 128)
+    rows_out = []
+    t_start = time.perf_counter()
+    for entry in gen.sweep_entries():
+        csr = gen.sweep_matrix(entry)
+        nnz = int(csr.row_ptr[-1])
+        plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals)
+        info = plan.describe()
+        Bs = {N: torch.from_numpy(gen.activations_for(csr, N)).cuda() for N in cols}
+        Cs = {N: torch.empty((csr.M, N), dtype=torch.float32, device="cuda") for N in cols}
+        base = measure_baselines(torch, np, csr, cols, Bs)
+        for N in cols:
+            pb, pc = Bs[N].data_ptr(), Cs[N].data_ptr()
+            st = torch.cuda.current_stream().cuda_stream or None
+            fn = lambda: plan.execute_raw(pb, N, pc, st)
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
+            _, med = time_kernel_events(torch, fn, 10, batch=20)
+            b = base.get(str(N), {})
+            rows_out.append({"index": entry["index"], "M": csr.M, "K": csr.K, "sparsity": entry["sparsity"],
+                             "nnz": nnz, "N": N, "ufi": info["ufi"], "us": round(med * 1e3, 3),
+                             "gflops": round(2.0 * nnz * N / (med * 1e-3) / 1e9, 1),
+                             "hbm_model_gbs": round(bytes_min(csr.M, csr.K, nnz, N) / (med * 1e-3) / 1e9, 1),
+                             "hipsparse_us": b.get("hipsparse_best_us"), "rocblas_us": b.get("rocblas_sgemm_us")})
+            print(json.dumps(rows_out[-1]), file=sys.stderr, flush=True)
+        del plan, Bs, Cs
+    summary = {}
+    for N in cols + ("all",):
+        sel = [r for r in rows_out if N == "all" or r["N"] == N]
+        for key in ("hipsparse_us", "rocblas_us"):
+            sp = [r[key] / r["us"] for r in sel if r[key]]
+            if sp:
+                summary["%s_%s" % (key[:-3], N)] = {
+                    "geomean_speedup": round(math.exp(sum(math.log(x) for x in sp) / len(sp)), 3),
+                    "faster_pct": round(100.0 * sum(1 for x in sp if x > 1.0) / len(sp), 1), "points": len(sp)}
+    total_flops = sum(2.0 * r["nnz"] * r["N"] for r in rows_out)
+    total_s = sum(r["us"] for r in rows_out) * 1e-6
+    out = {"metric": "fp32 CSR SpMM GFLOP/s (2*nnz*bCols)", "value": round(total_flops / total_s / 1e9, 2),
+           "unit": "GFLOP/s", "n_gpus": 1, "steps": 1, "warmup": 10, "ms_per_step": round(total_s * 1e3, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "sweep: 48 magnitude-pruned matrices x bCols 32/64/128 (configs[4])",
+                      "wall_s": round(time.perf_counter() - t_start, 1)},
+           "summary": summary, "points": rows_out}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -80,6 +203,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
+    if args.workload == "sweep" and args.gpus == 1:
+        return run_sweep(args)
     if args.gpus != 1:
         raise SystemExit("this build runs on one GPU only: the path shards by rows of A "
                          "(see DESIGN.md) but no multi-GPU run exists; use --gpus 1")
@@ -138,27 +263,7 @@ def main():
 
     baselines = {}
     if not args.no_baselines:
-        try:
-            A_sp = torch.sparse_csr_tensor(torch.from_numpy(csr.row_ptr.astype(np.int64)),
-                                           torch.from_numpy(csr.col_idx.astype(np.int64)),
-                                           torch.from_numpy(csr.vals), size=(csr.M, csr.K)).cuda()
-            dense_ok = csr.M * csr.K <= (1 << 28)
-            A_dn = A_sp.to_dense() if dense_ok else None
-            for N in cols:
-                for _ in range(3):
-                    torch.sparse.mm(A_sp, Bs[N])
-                _, m = time_kernel_events(torch, lambda N=N: torch.sparse.mm(A_sp, Bs[N]), 10, batch=5)
-                entry = {"rocsparse_csr_spmm_us": round(m * 1e3, 3),
-                         "rocsparse_gflops": round(2.0 * nnz * N / (m * 1e-3) / 1e9, 1)}
-                if A_dn is not None:
-                    for _ in range(3):
-                        torch.mm(A_dn, Bs[N])
-                    _, m2 = time_kernel_events(torch, lambda N=N: torch.mm(A_dn, Bs[N]), 10, batch=5)
-                    entry["rocblas_sgemm_us"] = round(m2 * 1e3, 3)
-                    entry["rocblas_effective_gflops"] = round(2.0 * nnz * N / (m2 * 1e-3) / 1e9, 1)
-                baselines[str(N)] = entry
-        except Exception as exc:  # comparison systems are context, never a reason to fail the bench
-            baselines = {"error": repr(exc)}
+        baselines = measure_baselines(torch, np, csr, cols, Bs)
 
     if args.copy_calibration:
         src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()

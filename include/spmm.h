@@ -54,7 +54,7 @@ typedef struct {
 
 /* Optional inspector settings; zero in a field means "let the inspector choose". */
 typedef struct {
-    int32_t group_nnz;     /* override the nonzero budget per row group (>= 32) */
+    int32_t group_nnz;     /* override the nonzero budget per row group (>= 8) */
     int32_t group_panels;  /* override the panel cap per row group (>= 1) */
     int32_t host_only;     /* nonzero: build the plan in host memory only (no device needed;
                               such a plan can be described and exported but not executed) */

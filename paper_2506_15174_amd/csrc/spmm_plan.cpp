@@ -206,7 +206,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         out.M = M;
         out.K = K;
         out.nnz = nnz;
-        out.group_nnz = opts.group_nnz > 0 ? std::max(32, opts.group_nnz) : choose_group_nnz(nnz);
+        out.group_nnz = opts.group_nnz > 0 ? std::max(8, opts.group_nnz) : choose_group_nnz(nnz);
         out.group_panels = opts.group_panels > 0 ? opts.group_panels : 16;
         const int64_t G = out.group_nnz;
         const int64_t GP = out.group_panels;
