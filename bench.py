@@ -135,6 +135,16 @@ def measure_baselines(torch, np, csr, cols, Bs, dense_limit=1 << 28):
     return out
 
 
+def kernel_shape(N):
+    """Template arguments of the instance spmm_execute launches for a tile of N columns
+    (N a multiple of 4, at most 128): slices per wave, floats per lane, pipeline depth."""
+    if N > 64:
+        return "S=2,VW=4,D=3"
+    if N > 32:
+        return "S=4,VW=4,D=6"
+    return "S=8,VW=4,D=8"
+
+
 def run_sweep(args):
     """Configuration 4: 48 magnitude-pruned matrices x bCols 32/64/128 against
     hipSPARSE CSR SpMM and rocBLAS SGEMM; geometric means of the speedups and the
@@ -151,12 +161,13 @@ def run_sweep(args):
     for entry in gen.sweep_entries():
         csr = gen.sweep_matrix(entry)
         nnz = int(csr.row_ptr[-1])
-        plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals)
-        info = plan.describe()
+        # one plan per column count: the schedule constants are chosen per bCols
+        plans = {N: spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, n_hint=N) for N in cols}
         Bs = {N: torch.from_numpy(gen.activations_for(csr, N)).cuda() for N in cols}
         Cs = {N: torch.empty((csr.M, N), dtype=torch.float32, device="cuda") for N in cols}
         base = measure_baselines(torch, np, csr, cols, Bs)
         for N in cols:
+            plan, info = plans[N], plans[N].describe()
             pb, pc = Bs[N].data_ptr(), Cs[N].data_ptr()
             st = torch.cuda.current_stream().cuda_stream or None
             fn = lambda: plan.execute_raw(pb, N, pc, st)
@@ -166,12 +177,15 @@ def run_sweep(args):
             _, med = time_kernel_events(torch, fn, 10, batch=20)
             b = base.get(str(N), {})
             rows_out.append({"index": entry["index"], "M": csr.M, "K": csr.K, "sparsity": entry["sparsity"],
-                             "nnz": nnz, "N": N, "ufi": info["ufi"], "us": round(med * 1e3, 3),
+                             "nnz": nnz, "N": N, "ufi": info["ufi"], "group_nnz": info["group_nnz"],
+                             "n_blocks": info["n_blocks"], "us": round(med * 1e3, 3),
                              "gflops": round(2.0 * nnz * N / (med * 1e-3) / 1e9, 1),
                              "hbm_model_gbs": round(bytes_min(csr.M, csr.K, nnz, N) / (med * 1e-3) / 1e9, 1),
                              "hipsparse_us": b.get("hipsparse_best_us"), "rocblas_us": b.get("rocblas_sgemm_us")})
             print(json.dumps(rows_out[-1]), file=sys.stderr, flush=True)
-        del plan, Bs, Cs
+        for plan in plans.values():
+            plan.destroy()
+        del plans, Bs, Cs
     summary = {}
     for N in cols + ("all",):
         sel = [r for r in rows_out if N == "all" or r["N"] == N]
@@ -219,16 +233,18 @@ def main():
     label, csr, cols = build_workload(args.workload)
     nnz = int(csr.row_ptr[-1])
     t0 = time.perf_counter()
-    plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals)
-    plan_s = time.perf_counter() - t0
-    info = plan.describe()
+    # one plan per column count: the schedule constants are chosen per bCols, as the
+    # paper's tuner does (Section 3.5)
+    plans = {N: spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, n_hint=N) for N in cols}
+    plan_s = (time.perf_counter() - t0) / len(cols)
+    infos = {N: plans[N].describe() for N in cols}
 
     Bs = {N: torch.from_numpy(gen.activations_for(csr, N)).cuda() for N in cols}
     Cs = {N: torch.empty((csr.M, N), dtype=torch.float32, device="cuda") for N in cols}
 
     def step():
         for N in cols:
-            plan.execute(Bs[N], Cs[N])
+            plans[N].execute(Bs[N], Cs[N])
 
     for _ in range(args.warmup):
         step()
@@ -244,20 +260,20 @@ def main():
 
     # dominant kernel: the widest column count; one launch per execute there
     Nd = max(cols)
-    avg_ms, med_ms = time_kernel_events(torch, lambda: plan.execute(Bs[Nd], Cs[Nd]), 20)
+    avg_ms, med_ms = time_kernel_events(torch, lambda: plans[Nd].execute(Bs[Nd], Cs[Nd]), 20)
     bmin = bytes_min(csr.M, csr.K, nnz, Nd)
     achieved = bmin / (avg_ms * 1e-3) / 1e9
     kernel_tflops = 2.0 * nnz * Nd / (avg_ms * 1e-3) / 1e12
     roofline = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
-                "kernel": "spmm_chunks_kernel<S=2,VW=4,D=3> (bCols %d)" % Nd,
+                "kernel": "spmm_chunks_kernel<UFI=%d,%s> (bCols %d)" % (infos[Nd]["ufi"], kernel_shape(Nd), Nd),
                 "avg_launch_us": round(avg_ms * 1e3, 3), "median_launch_us": round(med_ms * 1e3, 3),
                 "algorithmic_bytes": bmin, "kernel_tflops": round(kernel_tflops, 3),
                 "frac_of_fp32_valu_peak": round(kernel_tflops / FP32_VALU_PEAK_TFLOPS, 5)}
 
     per_cols = {}
     for N in cols:
-        a, m = time_kernel_events(torch, lambda N=N: plan.execute(Bs[N], Cs[N]), 20)
+        a, m = time_kernel_events(torch, lambda N=N: plans[N].execute(Bs[N], Cs[N]), 20)
         per_cols[str(N)] = {"us": round(m * 1e3, 3), "gflops": round(2.0 * nnz * N / (m * 1e-3) / 1e9, 1),
                             "hbm_model_gbs": round(bytes_min(csr.M, csr.K, nnz, N) / (m * 1e-3) / 1e9, 1)}
 
@@ -300,8 +316,9 @@ def main():
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
            "data": "synthetic",
            "config": {"workload": label, "M": csr.M, "K": csr.K, "nnz": nnz, "bCols": list(cols),
-                      "plan": {k: info[k] for k in ("ufi", "ufk", "group_nnz", "n_groups", "n_blocks",
-                                                    "n_split", "n_enum", "n_chunks", "device_bytes")},
+                      "plans": {str(N): {k: infos[N][k] for k in ("ufi", "ufk", "group_nnz", "group_panels", "n_groups",
+                                                                  "n_blocks", "n_split", "n_enum", "n_chunks",
+                                                                  "device_bytes")} for N in cols},
                       "plan_create_s": round(plan_s, 4), "row_stats": gen.row_stats(csr)},
            "roofline": roofline, "cpu_baseline": cpu, "per_bcols": per_cols, "baselines": baselines}
     print(json.dumps(out))

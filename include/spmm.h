@@ -59,6 +59,10 @@ typedef struct {
     int32_t host_only;     /* nonzero: build the plan in host memory only (no device needed;
                               such a plan can be described and exported but not executed) */
     int32_t ufi;           /* force the rows per panel: 1, 2 or 4 (0 = choose) */
+    int32_t n_hint;        /* number of B columns the plan will mostly be executed with
+                              (0 = unknown, >= 0).  Only the choice of the schedule
+                              constants looks at it, as the paper's tuner does per bCols
+                              (Section 3.5); the plan stays valid for every N. */
 } spmm_options_t;
 
 /*

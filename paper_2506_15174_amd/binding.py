@@ -41,7 +41,8 @@ class PlanInfo(ctypes.Structure):
 
 class Options(ctypes.Structure):
     _fields_ = [("group_nnz", ctypes.c_int32), ("group_panels", ctypes.c_int32),
-                ("host_only", ctypes.c_int32), ("ufi", ctypes.c_int32)]
+                ("host_only", ctypes.c_int32), ("ufi", ctypes.c_int32),
+                ("n_hint", ctypes.c_int32)]
 
 
 class SpmmError(RuntimeError):
@@ -176,15 +177,16 @@ class Plan:
             pass
 
 
-def plan_create(M, K, row_ptr, col_idx, vals, group_nnz=0, group_panels=0, host_only=False, ufi=0):
+def plan_create(M, K, row_ptr, col_idx, vals, group_nnz=0, group_panels=0, host_only=False, ufi=0,
+                n_hint=0):
     """spmm_plan_create / spmm_plan_create_ex on numpy host arrays."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
     vals = np.ascontiguousarray(vals, dtype=np.float32)
     handle = ctypes.c_void_p()
     lib = load()
-    if group_nnz or group_panels or host_only or ufi:
-        opts = Options(int(group_nnz), int(group_panels), 1 if host_only else 0, int(ufi))
+    if group_nnz or group_panels or host_only or ufi or n_hint:
+        opts = Options(int(group_nnz), int(group_panels), 1 if host_only else 0, int(ufi), int(n_hint))
         st = lib.spmm_plan_create_ex(ctypes.byref(handle), int(M), int(K), _ptr(row_ptr),
                                      _ptr(col_idx), _ptr(vals), ctypes.byref(opts))
     else:

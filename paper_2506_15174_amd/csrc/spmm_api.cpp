@@ -83,12 +83,13 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
     io.ufi = env_int("SPMM_UFI");
     bool host_only = false;
     if (opts) {
-        if (opts->group_nnz < 0 || opts->group_panels < 0) return SPMM_ERR_INVALID_ARG;
+        if (opts->group_nnz < 0 || opts->group_panels < 0 || opts->n_hint < 0) return SPMM_ERR_INVALID_ARG;
         if (opts->ufi != 0 && opts->ufi != 1 && opts->ufi != 2 && opts->ufi != 4) return SPMM_ERR_INVALID_ARG;
         if (opts->ufi > 0) io.ufi = opts->ufi;
         if (opts->group_nnz > 0) io.group_nnz = opts->group_nnz;
         if (opts->group_panels > 0) io.group_panels = opts->group_panels;
         host_only = opts->host_only != 0;
+        io.n_hint = opts->n_hint;
     }
     spmm_plan *p = new (std::nothrow) spmm_plan();
     if (!p) return SPMM_ERR_ALLOC;

@@ -38,15 +38,61 @@ struct Entry {
     float v[MAX_UFI];  // indexed by row inside the panel
 };
 
-// Nonzero budget of a row group: aim at about 4096 groups (256 compute units x
-// 16 resident waves), in steps of 32, never below 32 nor above 1024 nonzeros.
-int32_t choose_group_nnz(int64_t nnz)
+// ---- schedule selection (all in integers, from M, K, nnz and the caller's hint) ---
+//
+// The paper tunes the panel height once per architecture and per number of B
+// columns by timing candidates (Section 3.5 "Scheduler & Tuner").  The closed rule
+// below is the outcome of that exercise on MI355X, fitted to timings of pruned-layer
+// shapes (256 .. 8192 rows and columns, 50 .. 98 % pruned) with forced heights:
+//
+//   * narrow B (hint <= 32 columns): one wave load already covers eight enumerated
+//     columns, the address path bounds the kernel and a taller panel saves few
+//     loads, so single rows are taken; only matrices of 4 M entries or more with at
+//     least 40 % of the entries kept gain from four rows sharing their B rows;
+//   * medium B (hint 33 .. 64): four rows when at least a twelfth of the entries
+//     is kept, rows hold 512 entries or more on average and there are 1024 rows or
+//     more; else single rows;
+//   * wide or unknown B: four rows from 1024 rows on, two from 512 rows on, when at
+//     least a twelfth of the entries is kept and rows hold 128 entries or more on
+//     average; else single rows (sparser or shorter rows leave most patterns with
+//     a single row set, and the partly filled chunks cost more than the shared B
+//     rows save).
+int choose_ufi(int64_t M, int64_t K, int64_t nnz, int32_t n_hint)
 {
-    int64_t g = (nnz + 4095) / 4096;
+    const int64_t cells = M * K;
+    if (n_hint > 0 && n_hint <= 32) {
+        if (nnz * 5 >= cells * 2 && nnz >= ((int64_t)1 << 22)) return 4;
+        return 1;
+    }
+    const bool dense = nnz * 12 >= cells;
+    const int64_t row = M > 0 ? nnz / M : 0;
+    if (n_hint > 0 && n_hint <= 64) return (dense && row >= 512 && M >= 1024) ? 4 : 1;
+    if (!dense || row < 128) return 1;
+    if (M >= 1024) return 4;
+    if (M >= 512) return 2;
+    return 1;
+}
+
+// Nonzero budget G of a row group and the cap GP on the panels one group packs.
+// P panels of mean weight `mean`:
+//   * fewer than 4096 panels: a typical panel is cut into ppt = min(8, ceil(8192 / P))
+//     pieces so that the launch holds about 8192 waves;
+//   * 4096 panels or more: panels stay whole, and beyond 8192 panels GP =
+//     ceil(P / 8192) of them (at most 16) share a wave.
+// G = ceil(5 mean GP / (4 ppt)), rounded up to a multiple of 32 inside [32, 1024];
+// the quarter of headroom keeps panels near the mean on the typical piece count.
+void choose_group_budget(int64_t M, int64_t nnz, int ufi, int32_t &G_out, int32_t &GP_out)
+{
+    const int64_t P = std::max<int64_t>(1, (M + ufi - 1) / ufi);
+    const int64_t mean = (nnz + P - 1) / P;
+    const int64_t ppt = P < 4096 ? std::min<int64_t>(8, (8192 + P - 1) / P) : 1;
+    const int64_t GP = std::min<int64_t>(16, std::max<int64_t>(1, (P + 8191) / 8192));
+    int64_t g = (5 * mean * GP + 4 * ppt - 1) / (4 * ppt);
     g = (g + 31) / 32 * 32;
     if (g < 32) g = 32;
     if (g > 1024) g = 1024;
-    return (int32_t)g;
+    G_out = (int32_t)g;
+    GP_out = (int32_t)GP;
 }
 
 struct Emitter {
@@ -99,8 +145,10 @@ struct Emitter {
 
 // Row groups in creation order, from row_ptr alone.  Panels (ufi consecutive
 // rows) are taken in order.  A panel heavier than the budget G is cut into
-// nseg pieces of equal size of its schedule order: want = min(8, ceil(pn / G)),
-// size = ceil(pn / want), nseg = ceil(pn / size); the last piece takes the rest.
+// nseg pieces of equal size of its schedule order: want = min(8, ceil(pn / G))
+// rounded up to a power of two (so that the pieces of several panels fill the
+// eight wave slots of a workgroup exactly), size = ceil(pn / want),
+// nseg = ceil(pn / size); the last piece takes the rest.
 // Lighter panels are packed greedily: a group closes when the next panel would
 // exceed the budget or the panel cap.
 std::vector<Group> make_groups(const int32_t *row_ptr, int64_t M, int ufi, int64_t G, int64_t GP)
@@ -120,7 +168,8 @@ std::vector<Group> make_groups(const int32_t *row_ptr, int64_t M, int ufi, int64
         const int64_t pn = b - a;
         if (pn > G) {
             flush();
-            const int64_t want = std::min<int64_t>(WAVES_PER_WG, (pn + G - 1) / G);
+            int64_t want = std::min<int64_t>(WAVES_PER_WG, (pn + G - 1) / G);
+            while (want & (want - 1)) want += 1;
             const int64_t size = (pn + want - 1) / want;
             const int64_t nseg = (pn + size - 1) / size;
             for (int64_t s = 0; s < nseg; ++s) {
@@ -153,39 +202,6 @@ std::vector<Group> make_groups(const int32_t *row_ptr, int64_t M, int ufi, int64
     return groups;
 }
 
-// Workgroups the groups will occupy: split panels are packed in order of
-// decreasing weight (at most 8 / ufi per workgroup, pieces never straddle a
-// workgroup), whole-panel groups 8 per workgroup.
-int64_t count_blocks(const std::vector<Group> &groups, int ufi)
-{
-    std::vector<std::pair<int64_t, int>> heads;  // (panel nnz, pieces)
-    int64_t whole = 0;
-    for (size_t i = 0; i < groups.size(); ++i) {
-        const Group &g = groups[i];
-        if (!(g.flags & FLAG_SPLIT)) whole += 1;
-        else if (g.seg == 0)
-            heads.push_back({(int64_t)groups[i + (size_t)g.nseg - 1].nnz_end - g.nnz_begin, g.nseg});
-    }
-    std::stable_sort(heads.begin(), heads.end(),
-                     [](const std::pair<int64_t, int> &x, const std::pair<int64_t, int> &y) { return x.first > y.first; });
-    int64_t blocks = (whole + WAVES_PER_WG - 1) / WAVES_PER_WG;
-    int used = WAVES_PER_WG, panels = WAVES_PER_WG / ufi;
-    for (const auto &h : heads) {
-        if (used + h.second > WAVES_PER_WG || panels == WAVES_PER_WG / ufi) {
-            blocks += 1;
-            used = 0;
-            panels = 0;
-        }
-        used += h.second;
-        panels += 1;
-    }
-    return blocks;
-}
-
-// Workgroups wanted before a shorter panel is considered: three quarters of two
-// per compute unit.
-constexpr int64_t MIN_BLOCKS = 384;
-
 }  // namespace
 
 int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *col_idx,
@@ -206,37 +222,16 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         out.M = M;
         out.K = K;
         out.nnz = nnz;
-        out.group_nnz = opts.group_nnz > 0 ? std::max(8, opts.group_nnz) : choose_group_nnz(nnz);
-        out.group_panels = opts.group_panels > 0 ? opts.group_panels : 16;
+        // ---- 1. panel height, group budget and row groups, from row_ptr alone ---
+        int ufi = opts.ufi;
+        if (ufi != 1 && ufi != 2 && ufi != 4) ufi = choose_ufi(M, K, nnz, opts.n_hint);
+        int32_t auto_g = 0, auto_gp = 0;
+        choose_group_budget(M, nnz, ufi, auto_g, auto_gp);
+        out.group_nnz = opts.group_nnz > 0 ? std::max(8, opts.group_nnz) : auto_g;
+        out.group_panels = opts.group_panels > 0 ? opts.group_panels : auto_gp;
         const int64_t G = out.group_nnz;
         const int64_t GP = out.group_panels;
-
-        // ---- 1. row groups and the panel height, from row_ptr alone ------------
-        // The tallest panel (most B reuse) that still yields enough workgroups to
-        // occupy the chip is taken; a forced height skips the search.
-        int ufi = opts.ufi;
-        std::vector<Group> groups;
-        if (ufi != 1 && ufi != 2 && ufi != 4) {
-            ufi = 1;
-            int64_t best_blocks = -1;
-            for (int cand = MAX_UFI; cand >= 1; cand /= 2) {
-                std::vector<Group> g = make_groups(row_ptr, M, cand, G, GP);
-                const int64_t blocks = count_blocks(g, cand);
-                if (blocks >= MIN_BLOCKS) {
-                    ufi = cand;
-                    groups.swap(g);
-                    best_blocks = blocks;
-                    break;
-                }
-                if (blocks > best_blocks) {
-                    best_blocks = blocks;
-                    ufi = cand;
-                    groups.swap(g);
-                }
-            }
-        } else {
-            groups = make_groups(row_ptr, M, ufi, G, GP);
-        }
+        std::vector<Group> groups = make_groups(row_ptr, M, ufi, G, GP);
         out.ufi = ufi;
         const int UFI = ufi;  // panel height of this plan
         const int N_PATTERNS = (1 << UFI) - 1;

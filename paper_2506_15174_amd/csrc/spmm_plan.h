@@ -29,6 +29,7 @@ struct InspectorOptions {
     int32_t group_nnz = 0;     // 0 = choose
     int32_t group_panels = 0;  // 0 = choose
     int32_t ufi = 0;           // 0 = choose; else 1, 2 or 4
+    int32_t n_hint = 0;        // B columns the plan is meant for; 0 = unknown
 };
 
 // Status codes follow spmm_status_t (0 ok, 1 invalid argument, 2 invalid CSR,

@@ -9,7 +9,6 @@ import numpy as np
 
 MAX_UFI = 4
 UFK = 8
-MIN_BLOCKS = 384
 ITEM_WORDS = 16
 WIN_WORDS = 1024
 
@@ -32,6 +31,8 @@ def _groups_for(rp, M, ufi, group_nnz, group_panels):
                 whole.append(cur)
                 cur = None
             want = min(WAVES_PER_WG, -(-pn // group_nnz))
+            while want & (want - 1):
+                want += 1
             size = -(-pn // want)
             nseg = -(-pn // size)
             split.append([[r0, r1, a + s * size, min(b, a + (s + 1) * size), 1] for s in range(nseg)])
@@ -65,28 +66,40 @@ def _blocks_for(split, whole, ufi):
     return blocks
 
 
-def derive_groups(row_ptr, M, group_nnz, group_panels, ufi=0):
-    """(panel height, row groups in launch order as an (n, 5) int32 array, workgroups),
-    from row_ptr only.  ufi = 0 re-derives the inspector's choice: the tallest
-    panel of 4, 2, 1 rows that yields at least MIN_BLOCKS workgroups, else the one
-    that yields the most (the taller on ties)."""
+def choose_ufi(M, K, nnz, n_hint=0):
+    """The inspector's panel height as a function of the shape, the number of
+    entries and the number of B columns the plan is meant for (0 = unknown)."""
+    cells = M * K
+    if 0 < n_hint <= 32:
+        return 4 if (nnz * 5 >= cells * 2 and nnz >= 1 << 22) else 1
+    dense = nnz * 12 >= cells
+    row = nnz // M if M else 0
+    if 0 < n_hint <= 64:
+        return 4 if (dense and row >= 512 and M >= 1024) else 1
+    if not dense or row < 128:
+        return 1
+    return 4 if M >= 1024 else 2 if M >= 512 else 1
+
+
+def choose_group_budget(M, nnz, ufi):
+    """(nonzero budget, panel cap) of a row group for panels of `ufi` rows."""
+    P = max(1, -(-M // ufi))
+    mean = -(-nnz // P)
+    ppt = min(8, -(-8192 // P)) if P < 4096 else 1
+    GP = min(16, max(1, -(-P // 8192)))
+    g = -(-(5 * mean * GP) // (4 * ppt))
+    g = -(-g // 32) * 32
+    return min(1024, max(32, g)), GP
+
+
+def derive_groups(row_ptr, M, group_nnz, group_panels, ufi):
+    """(row groups in launch order as an (n, 5) int32 array, workgroups), from
+    row_ptr only, for a given panel height, budget and panel cap."""
     rp = [int(x) for x in row_ptr]
-    if ufi:
-        split, whole = _groups_for(rp, M, ufi, group_nnz, group_panels)
-        best = (ufi, split, whole, _blocks_for(split, whole, ufi))
-    else:
-        best = None
-        for cand in (4, 2, 1):
-            split, whole = _groups_for(rp, M, cand, group_nnz, group_panels)
-            blocks = _blocks_for(split, whole, cand)
-            if blocks >= MIN_BLOCKS:
-                best = (cand, split, whole, blocks)
-                break
-            if best is None or blocks > best[3]:
-                best = (cand, split, whole, blocks)
-    ufi, split, whole, blocks = best
+    split, whole = _groups_for(rp, M, ufi, group_nnz, group_panels)
+    blocks = _blocks_for(split, whole, ufi)
     out = [piece for pieces in split for piece in pieces] + whole
-    return ufi, np.array(out, dtype=np.int32).reshape(-1, 5), blocks
+    return np.array(out, dtype=np.int32).reshape(-1, 5), blocks
 
 
 def canonical_csr(row_ptr, col_idx, vals):

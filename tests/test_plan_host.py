@@ -16,7 +16,8 @@ import pytest
 import paper_2506_15174_amd as spmm
 from workloads import generators as gen
 
-from plan_reference import (UFK, canonical_csr, decode_plan, derive_groups, interpret_plan,
+from plan_reference import (UFK, canonical_csr, choose_group_budget, choose_ufi, decode_plan, derive_groups,
+                            interpret_plan,
                             walk_chunks)
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -75,13 +76,14 @@ def test_row_groups_match_python_rederivation(name, group_nnz, force_ufi):
     info = plan.describe()
     assert (info["M"], info["K"], info["nnz"]) == (csr.M, csr.K, int(csr.row_ptr[-1]))
     assert info["ufk"] == UFK and info["ufi"] in (1, 2, 4)
-    if group_nnz:
-        assert info["group_nnz"] == group_nnz
-    if force_ufi:
-        assert info["ufi"] == force_ufi
+    nnz = int(csr.row_ptr[-1])
+    UFI = force_ufi or choose_ufi(csr.M, csr.K, nnz)
+    assert info["ufi"] == UFI
+    auto_g, auto_gp = choose_group_budget(csr.M, nnz, UFI)
+    assert info["group_nnz"] == (group_nnz or auto_g) and info["group_panels"] == auto_gp
     got = plan.get_groups()
-    UFI, want, blocks = derive_groups(csr.row_ptr, csr.M, info["group_nnz"], info["group_panels"], force_ufi)
-    assert UFI == info["ufi"] and blocks == info["n_blocks"]
+    want, blocks = derive_groups(csr.row_ptr, csr.M, info["group_nnz"], info["group_panels"], UFI)
+    assert blocks == info["n_blocks"]
     assert got.shape == want.shape and np.array_equal(got, want)
     assert info["n_groups"] == len(want) and info["n_split"] == int((want[:, 4] & 1).sum())
     assert info["n_blocks"] * 8 * 16 == len(plan.get_array(spmm.ARRAY_ITEMS))
@@ -111,19 +113,69 @@ def test_row_groups_match_python_rederivation(name, group_nnz, force_ufi):
     assert np.all((got[:n_split, 4] & 1) == 1), "pieces of split panels come first"
 
 
-def test_default_group_budget_rule():
-    for nnz, want in ((0, 32), (6554, 32), (209715, 64), (1258291, 320), (13330308, 1024), (4096 * 512, 512)):
-        row_ptr = np.array([0], dtype=np.int32)
-        # the rule depends on nnz only: one row of that many entries is enough
-        if nnz:
-            K = nnz
-            csr = gen.Csr(1, K, np.array([0, nnz], np.int32), np.arange(nnz, dtype=np.int32),
-                          np.ones(nnz, np.float32))
-            info = host_plan(csr).describe()
-        else:
-            info = spmm.plan_create(0, 5, row_ptr, np.zeros(0, np.int32), np.zeros(0, np.float32),
-                                    host_only=True).describe()
-        assert info["group_nnz"] == want and info["group_panels"] == 16
+def _row_ptr_only_plan(M, K, per_row, **kw):
+    """A host plan of M rows with `per_row` entries each (columns 0 .. per_row-1)."""
+    row_ptr = (np.arange(M + 1, dtype=np.int64) * per_row).astype(np.int32)
+    col_idx = np.tile(np.arange(per_row, dtype=np.int32), M)
+    return spmm.plan_create(M, K, row_ptr, col_idx, np.ones(M * per_row, np.float32), host_only=True, **kw)
+
+
+# (M, K, entries per row, hint) -> (ufi, group_nnz, group_panels), worked by hand
+# from the rule the header of spmm_plan.cpp states
+SCHEDULE_CASES = [
+    # 512 x 2048 at 20 %: wide B -> 2 rows; 256 panels of 820 -> 8 pieces -> ceil(5*820/32) = 129 -> 160
+    ((512, 2048, 410, 0), (2, 160, 1)),
+    # the same for 32 columns of B: single rows; 512 panels of 410 -> ceil(5*410/32) = 65 -> 96
+    ((512, 2048, 410, 32), (1, 96, 1)),
+    # 4096 x 1024 at 50 %: 4 rows; 1024 panels of 2048 -> 8 pieces -> 320
+    ((4096, 1024, 512, 128), (4, 320, 1)),
+    # narrow B, 2 M entries: below the size that pays for tall panels; 4096 whole rows -> 640
+    ((4096, 1024, 512, 32), (1, 640, 1)),
+    # 5 % kept: single rows whatever the hint; 4096 whole rows of 52 -> 65 -> 96
+    ((4096, 1024, 52, 0), (1, 96, 1)),
+    # 256 rows: too few panels for tall ones; 256 rows of 128 -> 8 pieces -> 20 -> 32
+    ((256, 256, 128, 128), (1, 32, 1)),
+    # 32768 single rows: 4 panels share a wave, budget 5*8*4/4 = 40 -> 64
+    ((32768, 1024, 8, 0), (1, 64, 4)),
+    # 8192 x 8192 at 50 %, narrow B: big and dense enough for 4 rows; 2048 panels -> 4 pieces, capped
+    ((8192, 8192, 4096, 32), (4, 1024, 1)),
+    # 64 columns of B: rows of 512 entries are the least that get 4 rows
+    ((4096, 1024, 512, 64), (4, 320, 1)),
+    # ... rows of 410 stay single: 4096 whole rows, ceil(5*410/4) = 513 -> 544
+    ((4096, 4096, 410, 64), (1, 544, 1)),
+    # wide B, a tenth kept but rows of 102 < 128: single rows; 1024 rows -> 8 pieces -> 16 -> 32
+    ((1024, 1024, 102, 128), (1, 32, 1)),
+]
+
+
+@pytest.mark.parametrize("case,want", SCHEDULE_CASES)
+def test_schedule_constants_rule(case, want):
+    M, K, per_row, hint = case
+    info = _row_ptr_only_plan(M, K, per_row, n_hint=hint).describe()
+    assert (info["ufi"], info["group_nnz"], info["group_panels"]) == want
+    nnz = M * per_row
+    ufi = choose_ufi(M, K, nnz, hint)
+    assert (ufi,) + choose_group_budget(M, nnz, ufi) == want
+
+
+def test_empty_matrix_schedule():
+    info = spmm.plan_create(0, 5, np.array([0], np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32),
+                            host_only=True).describe()
+    assert (info["ufi"], info["group_nnz"], info["group_panels"]) == (1, 32, 1)
+
+
+def test_split_panels_have_power_of_two_piece_counts():
+    # rows of 300, 500 and 900 entries with a budget of 128: 3 -> 4, 4 and 8 -> 8 pieces
+    lens = [300, 500, 900]
+    row_ptr = np.concatenate(([0], np.cumsum(lens))).astype(np.int32)
+    col_idx = np.concatenate([np.arange(n, dtype=np.int32) for n in lens])
+    plan = spmm.plan_create(3, 1000, row_ptr, col_idx, np.ones(len(col_idx), np.float32), host_only=True,
+                            ufi=1, group_nnz=128)
+    g = plan.get_groups()
+    pieces = {int(r): int(np.sum(g[:, 0] == r)) for r in range(3)}
+    assert pieces == {0: 4, 1: 4, 2: 8}
+    # 4 + 4 share one workgroup, 8 fill another
+    assert plan.describe()["n_blocks"] == 2
 
 
 @pytest.mark.parametrize("name", sorted(CASES))
