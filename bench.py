@@ -135,6 +135,25 @@ def measure_baselines(torch, np, csr, cols, Bs, dense_limit=1 << 28):
     return out
 
 
+def measured_traffic(workload, N):
+    """HBM bytes per launch (scaled FETCH_SIZE + WRITE_SIZE) that the committed
+    rocprofv3 counter summaries record for this workload and column count, from their
+    `traffic_bytes_per_launch <workload> <bCols> <bytes>` lines; None if there is none.
+    Counters cannot be read from inside this process, so the figure is the last
+    profiled one, not a live measurement."""
+    import glob
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    for path in sorted(glob.glob(os.path.join(here, "profiles", "*.md"))):
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 4 and parts[0] == "traffic_bytes_per_launch" \
+                        and parts[1] == workload and parts[2] == str(N):
+                    return int(parts[3])
+    return None
+
+
 def kernel_shape(N):
     """Template arguments of the instance spmm_execute launches for a tile of N columns
     (N a multiple of 4, at most 128): slices per wave, floats per lane, pipeline depth."""
@@ -265,7 +284,7 @@ def main():
     achieved = bmin / (avg_ms * 1e-3) / 1e9
     kernel_tflops = 2.0 * nnz * Nd / (avg_ms * 1e-3) / 1e12
     roofline = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": measured_traffic(args.workload, Nd),
                 "kernel": "spmm_chunks_kernel<UFI=%d,%s> (bCols %d)" % (infos[Nd]["ufi"], kernel_shape(Nd), Nd),
                 "avg_launch_us": round(avg_ms * 1e3, 3), "median_launch_us": round(med_ms * 1e3, 3),
                 "algorithmic_bytes": bmin, "kernel_tflops": round(kernel_tflops, 3),
