@@ -84,7 +84,8 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
     bool host_only = false;
     if (opts) {
         if (opts->group_nnz < 0 || opts->group_panels < 0 || opts->n_hint < 0) return SPMM_ERR_INVALID_ARG;
-        if (opts->ufi != 0 && opts->ufi != 1 && opts->ufi != 2 && opts->ufi != 4) return SPMM_ERR_INVALID_ARG;
+        if (opts->ufi != 0 && opts->ufi != 1 && opts->ufi != 2 && opts->ufi != 4 && opts->ufi != 8)
+            return SPMM_ERR_INVALID_ARG;
         if (opts->ufi > 0) io.ufi = opts->ufi;
         if (opts->group_nnz > 0) io.group_nnz = opts->group_nnz;
         if (opts->group_panels > 0) io.group_panels = opts->group_panels;

@@ -20,19 +20,19 @@
 namespace spmm_fmt {
 
 // Rows per panel: height of the register tile (the paper's UFi).  A plan uses
-// 4, 2 or 1; a panel of u rows has 2^u - 1 nonzero patterns (paper Section 2).
-constexpr int MAX_UFI = 4;
+// 8, 4, 2 or 1; a panel of u rows has 2^u - 1 nonzero patterns (paper Section 2).
+constexpr int MAX_UFI = 8;
 
 // Enumerated columns per chunk (the paper's UFk).
 constexpr int UFK = 8;
 
 // A chunk is described by
 //
-//   header     one word:  bits 0..3  pattern (rows of the panel that own a value in
-//                                    every column of the chunk), 0 only for the
-//                                    single chunk of a panel without nonzeros
-//                         bits 4..7  count of real columns, 0..UFK
-//                         bit  8     last chunk of its panel (write the tile)
+//   header     one word:  bits 0..7   pattern (rows of the panel that own a value in
+//                                     every column of the chunk), 0 only for the
+//                                     single chunk of a panel without nonzeros
+//                         bits 8..11  count of real columns, 0..UFK
+//                         bit  12     last chunk of its panel (write the tile)
 //   columns    UFK column indices (slots >= count repeat a valid column of the
 //              chunk, or 0, and carry zero values)
 //   values     for every set row of the pattern in ascending row order UFK value
@@ -49,10 +49,10 @@ constexpr int UFK = 8;
 // is a running sum (UFK * popcount(pattern) per chunk).
 //   wins[i]    one word per window: bits 0..15 chunks, bits 16..31 words
 //   hdr[c]     host-side copy of all headers in launch order (introspection only)
-constexpr uint32_t HDR_PATTERN_MASK = 0xFu;
-constexpr int HDR_COUNT_SHIFT = 4;
+constexpr uint32_t HDR_PATTERN_MASK = 0xFFu;
+constexpr int HDR_COUNT_SHIFT = 8;
 constexpr uint32_t HDR_COUNT_MASK = 0xFu;
-constexpr uint32_t HDR_END_PANEL = 1u << 8;
+constexpr uint32_t HDR_END_PANEL = 1u << 12;
 
 // Words of LDS one wave owns (its window; later its partial tile).
 constexpr int WIN_WORDS = 1024;

@@ -177,13 +177,30 @@ template <int Q> __device__ __forceinline__ void lds_read(uint32_t (&out)[Q], co
     }
 }
 
-// UFI   rows per panel (1, 2, 4): height of the register tile
+// Word of a slice's value block for row r of a chunk with the given pattern whose
+// blocks start at `at`: the block index is the number of pattern rows below r.
+// Clamped to `limit` so that the request stays inside the wave's window for rows
+// the pattern does not hold.
+__device__ __forceinline__ uint32_t value_block(uint32_t at, uint32_t pattern, int r, uint32_t limit)
+{
+    const uint32_t w = at + (uint32_t)UFK * (uint32_t)__builtin_popcount(pattern & ((1u << r) - 1u));
+    return w < limit ? w : limit;
+}
+
+// UFI   rows per panel (1, 2, 4, 8): height of the register tile
 // S     slices per wave (1, 2, 4, 8); a slice has 64 / S lanes and UFK / S column slots per chunk
 // VW    columns per lane (4 with 16-byte loads; 1 for the generic path, S == 1 only)
 // D     chunks of B rows in flight per wave
 // WIDE  64-bit addressing of B
+// Waves per SIMD the register budget of an instance is sized for.  Narrow slices
+// keep few B rows in flight per wave and walk a long dependent chain per chunk
+// (header, row branches, LDS reads), so they need more resident waves to cover
+// it: 8 (64 VGPRs) with eight slices, 6 (80 VGPRs) with four, 4 (128 VGPRs)
+// otherwise.
+constexpr int waves_per_simd(int S, int UFI) { return UFI > 4 ? 4 : S >= 8 ? 8 : S >= 4 ? 6 : 4; }
+
 template <int UFI, int S, int VW, int D, bool WIDE>
-__global__ __launch_bounds__(64 * WAVES_PER_WG, 4) void
+__global__ __launch_bounds__(64 * WAVES_PER_WG, (waves_per_simd(S, UFI))) void
 spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                    const uint32_t *__restrict__ wins_g, const uint32_t *__restrict__ items_g,
                    const float *__restrict__ B, uint32_t b_bytes, float *__restrict__ C, int32_t ldn,
@@ -260,8 +277,11 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
 #pragma unroll
                 for (int q = 0; q < Q; ++q) voff[q] = BSource<WIDE>::offset(cv[q], ld_eff, lane_off);
             }
+            // last word a slice may start a value read at (blocks are requested for
+            // every row of the tile; those of rows outside the pattern are clamped
+            // into the window and never used)
+            const uint32_t val_limit = (uint32_t)(WIN_WORDS - UFK) + slot0;
             uint32_t h_next = win[0];  // header of the chunk multiplied in the next step (same in all lanes)
-
             uint32_t c = 0;
             bool more = true;
             while (more) {
@@ -281,16 +301,13 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                     // the enumerated block of chunk c (paper Listing 7); its B rows are
                     // older than the (D - 1) * Q loads issued since
                     const uint32_t pattern = h_now & HDR_PATTERN_MASK;
-                    if constexpr (S <= 2) {
+                    if constexpr (S <= 2 && UFI <= 4) {
                         // wide slices: request the value blocks of all UFI rows before
                         // the wait for the B rows (blocks of rows outside the pattern
                         // are never used), so the LDS latency hides behind it
                         uint32_t a[UFI][Q];
 #pragma unroll
-                        for (int r = 0; r < UFI; ++r)
-                            lds_read<Q>(a[r], win,
-                                        at_val + (uint32_t)UFK *
-                                                     (uint32_t)__builtin_popcount(pattern & ((1u << r) - 1u)));
+                        for (int r = 0; r < UFI; ++r) lds_read<Q>(a[r], win, value_block(at_val, pattern, r, val_limit));
                         at_val += (uint32_t)UFK * (uint32_t)__builtin_popcount(pattern);
                         wait_for<(D - 1) * Q>(b[s]);
 #pragma unroll
@@ -301,7 +318,8 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                             }
                         }
                     } else {
-                        // narrow slices: one small LDS read per row of the pattern
+                        // narrow slices, tall panels, generic tiles: one LDS read per row
+                        // of the pattern
                         wait_for<(D - 1) * Q>(b[s]);
 #pragma unroll
                         for (int r = 0; r < UFI; ++r) {
@@ -318,7 +336,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
 #pragma unroll
                     for (int q = 0; q < Q; ++q) voff[q] = BSource<WIDE>::offset(cv[q], ld_next, lane_off);
 
-                    if (h_now & HDR_END_PANEL) {
+                    if (__builtin_expect((h_now & HDR_END_PANEL) != 0, 0)) {
                         // add the slices' partial tiles across lanes
                         if constexpr (S >= 2) {
 #pragma unroll
@@ -387,11 +405,13 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                        dim3(64 * WAVES_PER_WG), 0, (hipStream_t)stream, a.stream, a.wins, a.items,    \
                        a.B, a.b_bytes, a.C, a.ldn, a.width)
 
-#define SPMM_LAUNCH_SLICES(U)                                                                         \
+// Pipeline depths: as deep as the 128 VGPRs of a wave allow.  The eight-row tile
+// holds 32 accumulators, which leaves room for fewer B rows in flight.
+#define SPMM_LAUNCH_SLICES(U, D2, D4, D8)                                                             \
     switch (slices) {                                                                                 \
-    case 2: if (wide) SPMM_LAUNCH(U, 2, 4, 3, true); else SPMM_LAUNCH(U, 2, 4, 3, false); break;      \
-    case 4: if (wide) SPMM_LAUNCH(U, 4, 4, 6, true); else SPMM_LAUNCH(U, 4, 4, 6, false); break;      \
-    case 8: if (wide) SPMM_LAUNCH(U, 8, 4, 8, true); else SPMM_LAUNCH(U, 8, 4, 8, false); break;      \
+    case 2: if (wide) SPMM_LAUNCH(U, 2, 4, D2, true); else SPMM_LAUNCH(U, 2, 4, D2, false); break;    \
+    case 4: if (wide) SPMM_LAUNCH(U, 4, 4, D4, true); else SPMM_LAUNCH(U, 4, 4, D4, false); break;    \
+    case 8: if (wide) SPMM_LAUNCH(U, 8, 4, D8, true); else SPMM_LAUNCH(U, 8, 4, D8, false); break;    \
     default: if (wide) SPMM_LAUNCH(U, 1, 1, 3, true); else SPMM_LAUNCH(U, 1, 1, 3, false); break;     \
     }
 
@@ -399,9 +419,10 @@ int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int slices, bool wide
 {
     if (a.n_blocks <= 0) return 0;
     switch (ufi) {
-    case 4: SPMM_LAUNCH_SLICES(4) break;
-    case 2: SPMM_LAUNCH_SLICES(2) break;
-    case 1: SPMM_LAUNCH_SLICES(1) break;
+    case 8: SPMM_LAUNCH_SLICES(8, 2, 4, 8) break;
+    case 4: SPMM_LAUNCH_SLICES(4, 3, 3, 4) break;
+    case 2: SPMM_LAUNCH_SLICES(2, 3, 4, 6) break;
+    case 1: SPMM_LAUNCH_SLICES(1, 3, 4, 8) break;
     default: return (int)hipErrorInvalidValue;
     }
     return (int)hipGetLastError();

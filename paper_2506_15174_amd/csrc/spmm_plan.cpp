@@ -43,31 +43,42 @@ struct Entry {
 // The paper tunes the panel height once per architecture and per number of B
 // columns by timing candidates (Section 3.5 "Scheduler & Tuner").  The closed rule
 // below is the outcome of that exercise on MI355X, fitted to timings of pruned-layer
-// shapes (256 .. 8192 rows and columns, 50 .. 98 % pruned) with forced heights:
+// shapes (256 .. 8192 rows and columns, 50 .. 98 % pruned) with forced heights.
+// `row` is the mean number of entries per row; "dense" means that at least a
+// twelfth of the entries is kept.
 //
 //   * narrow B (hint <= 32 columns): one wave load already covers eight enumerated
-//     columns, the address path bounds the kernel and a taller panel saves few
-//     loads, so single rows are taken; only matrices of 4 M entries or more with at
-//     least 40 % of the entries kept gain from four rows sharing their B rows;
-//   * medium B (hint 33 .. 64): four rows when at least a twelfth of the entries
-//     is kept, rows hold 512 entries or more on average and there are 1024 rows or
-//     more; else single rows;
-//   * wide or unknown B: four rows from 1024 rows on, two from 512 rows on, when at
-//     least a twelfth of the entries is kept and rows hold 128 entries or more on
-//     average; else single rows (sparser or shorter rows leave most patterns with
-//     a single row set, and the partly filled chunks cost more than the shared B
-//     rows save).
+//     columns, so tall panels save few loads and pay with a longer dependent chain
+//     per chunk: four rows only from 4096 rows on with row >= 1024; two rows for
+//     512 .. 4095 rows with row >= 256; else single rows;
+//   * medium B (hint 33 .. 64), dense and row >= 256: eight rows from 4096 rows on
+//     with row >= 2048, four rows from 2048 rows on, two from 512 on; else single
+//     rows;
+//   * wide or unknown B, dense and row >= 128: eight rows from 4096 rows on with
+//     row >= 1024, four rows from 1024 rows on, two from 512 on; else single rows.
+//
+// Sparser or shorter rows leave most patterns with one row set, and the partly
+// filled chunks of many patterns cost more than the shared B rows save; few rows
+// cannot fill the chip with tall panels (a split panel of eight rows owns a whole
+// workgroup).
 int choose_ufi(int64_t M, int64_t K, int64_t nnz, int32_t n_hint)
 {
-    const int64_t cells = M * K;
+    const int64_t row = M > 0 ? nnz / M : 0;
     if (n_hint > 0 && n_hint <= 32) {
-        if (nnz * 5 >= cells * 2 && nnz >= ((int64_t)1 << 22)) return 4;
+        if (M >= 4096) return row >= 1024 ? 4 : 1;
+        if (M >= 512) return row >= 256 ? 2 : 1;
         return 1;
     }
-    const bool dense = nnz * 12 >= cells;
-    const int64_t row = M > 0 ? nnz / M : 0;
-    if (n_hint > 0 && n_hint <= 64) return (dense && row >= 512 && M >= 1024) ? 4 : 1;
+    const bool dense = nnz * 12 >= M * K;
+    if (n_hint > 0 && n_hint <= 64) {
+        if (!dense || row < 256) return 1;
+        if (M >= 4096 && row >= 2048) return 8;
+        if (M >= 2048) return 4;
+        if (M >= 512) return 2;
+        return 1;
+    }
     if (!dense || row < 128) return 1;
+    if (M >= 4096 && row >= 1024) return 8;
     if (M >= 1024) return 4;
     if (M >= 512) return 2;
     return 1;
@@ -224,7 +235,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         out.nnz = nnz;
         // ---- 1. panel height, group budget and row groups, from row_ptr alone ---
         int ufi = opts.ufi;
-        if (ufi != 1 && ufi != 2 && ufi != 4) ufi = choose_ufi(M, K, nnz, opts.n_hint);
+        if (ufi != 1 && ufi != 2 && ufi != 4 && ufi != 8) ufi = choose_ufi(M, K, nnz, opts.n_hint);
         int32_t auto_g = 0, auto_gp = 0;
         choose_group_budget(M, nnz, ufi, auto_g, auto_gp);
         out.group_nnz = opts.group_nnz > 0 ? std::max(8, opts.group_nnz) : auto_g;
@@ -295,8 +306,8 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                 // a row meets the t-th occurrences in the other rows, so a column
                 // stored twice in one row yields two enumerated columns.
                 merged.clear();
-                size_t head[MAX_UFI] = {0, 0, 0, 0};
-                uint32_t layer[MAX_UFI] = {0, 0, 0, 0};
+                size_t head[MAX_UFI] = {};
+                uint32_t layer[MAX_UFI] = {};
                 for (;;) {
                     int32_t best_col = INT32_MAX;
                     uint32_t best_layer = UINT32_MAX;

@@ -7,7 +7,7 @@ evaluates the product from the chunk arrays the way the kernel consumes them.
 """
 import numpy as np
 
-MAX_UFI = 4
+MAX_UFI = 8
 UFK = 8
 ITEM_WORDS = 16
 WIN_WORDS = 1024
@@ -69,15 +69,24 @@ def _blocks_for(split, whole, ufi):
 def choose_ufi(M, K, nnz, n_hint=0):
     """The inspector's panel height as a function of the shape, the number of
     entries and the number of B columns the plan is meant for (0 = unknown)."""
-    cells = M * K
-    if 0 < n_hint <= 32:
-        return 4 if (nnz * 5 >= cells * 2 and nnz >= 1 << 22) else 1
-    dense = nnz * 12 >= cells
     row = nnz // M if M else 0
+    if 0 < n_hint <= 32:
+        if M >= 4096:
+            return 4 if row >= 1024 else 1
+        if M >= 512:
+            return 2 if row >= 256 else 1
+        return 1
+    dense = nnz * 12 >= M * K
     if 0 < n_hint <= 64:
-        return 4 if (dense and row >= 512 and M >= 1024) else 1
+        if not dense or row < 256:
+            return 1
+        if M >= 4096 and row >= 2048:
+            return 8
+        return 4 if M >= 2048 else 2 if M >= 512 else 1
     if not dense or row < 128:
         return 1
+    if M >= 4096 and row >= 1024:
+        return 8
     return 4 if M >= 1024 else 2 if M >= 512 else 1
 
 
@@ -165,7 +174,7 @@ def walk_chunks(it, hdr, stream, wins):
         for k in range(wc):
             h = int(stream[at + k])
             assert h == int(hdr[c]), "window header differs from the header list"
-            pc = bin(h & 15).count("1")
+            pc = bin(h & 255).count("1")
             cc = stream[cols_at + k * UFK:cols_at + (k + 1) * UFK]
             blocks = [stream[vals_at + UFK * t:vals_at + UFK * (t + 1)] for t in range(pc)]
             yield h, cc, blocks
@@ -191,8 +200,8 @@ def decode_plan(items, hdr, stream, wins, ufi):
         row = row0
         rows_left = nrows
         for h, cc, blocks in walk_chunks(it, hdr, stream, wins):
-            pattern, count, end = h & 15, (h >> 4) & 15, (h >> 8) & 1
-            assert h >> 9 == 0 and count <= UFK
+            pattern, count, end = h & 255, (h >> 8) & 15, (h >> 12) & 1
+            assert h >> 13 == 0 and count <= UFK
             assert (count == 0) == (pattern == 0)
             if count == 0:
                 assert end, "an empty chunk is the only chunk of an empty panel"
@@ -240,7 +249,7 @@ def interpret_plan(items, hdr, stream, wins, B, M, ufi):
             acc = np.zeros((ufi, N), dtype=np.float32)
             row, rows_left = row0, nrows
             for h, cc, vblocks in walk_chunks(it, hdr, stream, wins):
-                pattern, end = h & 15, (h >> 8) & 1
+                pattern, end = h & 255, (h >> 12) & 1
                 t = 0
                 for r in range(ufi):
                     if not (pattern >> r) & 1:

@@ -69,13 +69,13 @@ def test_library_exports_every_declared_symbol():
 
 @pytest.mark.parametrize("name", sorted(CASES))
 @pytest.mark.parametrize("group_nnz", [0, 32, 200])
-@pytest.mark.parametrize("force_ufi", [0, 1, 2, 4])
+@pytest.mark.parametrize("force_ufi", [0, 1, 2, 4, 8])
 def test_row_groups_match_python_rederivation(name, group_nnz, force_ufi):
     csr = CASES[name]()
     plan = host_plan(csr, group_nnz=group_nnz, ufi=force_ufi)
     info = plan.describe()
     assert (info["M"], info["K"], info["nnz"]) == (csr.M, csr.K, int(csr.row_ptr[-1]))
-    assert info["ufk"] == UFK and info["ufi"] in (1, 2, 4)
+    assert info["ufk"] == UFK and info["ufi"] in (1, 2, 4, 8)
     nnz = int(csr.row_ptr[-1])
     UFI = force_ufi or choose_ufi(csr.M, csr.K, nnz)
     assert info["ufi"] == UFI
@@ -125,11 +125,13 @@ def _row_ptr_only_plan(M, K, per_row, **kw):
 SCHEDULE_CASES = [
     # 512 x 2048 at 20 %: wide B -> 2 rows; 256 panels of 820 -> 8 pieces -> ceil(5*820/32) = 129 -> 160
     ((512, 2048, 410, 0), (2, 160, 1)),
-    # the same for 32 columns of B: single rows; 512 panels of 410 -> ceil(5*410/32) = 65 -> 96
-    ((512, 2048, 410, 32), (1, 96, 1)),
+    # the same for 32 columns of B: rows of 410 >= 256 on 512 rows -> 2 rows as well
+    ((512, 2048, 410, 32), (2, 160, 1)),
+    # ... but rows of 200 stay single: 512 panels of 200 -> 8 pieces -> ceil(5*200/32) = 32
+    ((512, 2048, 200, 32), (1, 32, 1)),
     # 4096 x 1024 at 50 %: 4 rows; 1024 panels of 2048 -> 8 pieces -> 320
     ((4096, 1024, 512, 128), (4, 320, 1)),
-    # narrow B, 2 M entries: below the size that pays for tall panels; 4096 whole rows -> 640
+    # narrow B, rows of 512 < 1024: single rows; 4096 whole rows -> 640
     ((4096, 1024, 512, 32), (1, 640, 1)),
     # 5 % kept: single rows whatever the hint; 4096 whole rows of 52 -> 65 -> 96
     ((4096, 1024, 52, 0), (1, 96, 1)),
@@ -137,12 +139,17 @@ SCHEDULE_CASES = [
     ((256, 256, 128, 128), (1, 32, 1)),
     # 32768 single rows: 4 panels share a wave, budget 5*8*4/4 = 40 -> 64
     ((32768, 1024, 8, 0), (1, 64, 4)),
-    # 8192 x 8192 at 50 %, narrow B: big and dense enough for 4 rows; 2048 panels -> 4 pieces, capped
+    # 8192 x 8192 at 50 %, narrow B: rows of 4096 >= 1024 -> 4 rows; 2048 panels -> 4 pieces, capped
     ((8192, 8192, 4096, 32), (4, 1024, 1)),
-    # 64 columns of B: rows of 512 entries are the least that get 4 rows
+    # ... medium and wide B: 8 rows; 1024 panels -> 8 pieces, capped
+    ((8192, 8192, 4096, 64), (8, 1024, 1)),
+    ((8192, 8192, 4096, 128), (8, 1024, 1)),
+    # 64 columns of B: 4 rows from 2048 rows on when rows hold 256 or more
     ((4096, 1024, 512, 64), (4, 320, 1)),
-    # ... rows of 410 stay single: 4096 whole rows, ceil(5*410/4) = 513 -> 544
-    ((4096, 4096, 410, 64), (1, 544, 1)),
+    # ... 1024 panels of 1640 -> 8 pieces -> ceil(5*1640/32) = 257 -> 288
+    ((4096, 4096, 410, 64), (4, 288, 1)),
+    # ... 1024 rows: 2 rows; 512 panels of 4096 -> 8 pieces -> 640
+    ((1024, 4096, 2048, 64), (2, 640, 1)),
     # wide B, a tenth kept but rows of 102 < 128: single rows; 1024 rows -> 8 pieces -> 16 -> 32
     ((1024, 1024, 102, 128), (1, 32, 1)),
 ]
@@ -180,7 +187,7 @@ def test_split_panels_have_power_of_two_piece_counts():
 
 @pytest.mark.parametrize("name", sorted(CASES))
 @pytest.mark.parametrize("group_nnz", [0, 32, 200])
-@pytest.mark.parametrize("force_ufi", [0, 1, 2, 4])
+@pytest.mark.parametrize("force_ufi", [0, 1, 2, 4, 8])
 def test_format_round_trip_is_bit_exact(name, group_nnz, force_ufi):
     csr = CASES[name]()
     plan = host_plan(csr, group_nnz=group_nnz, ufi=force_ufi)
@@ -193,10 +200,10 @@ def test_format_round_trip_is_bit_exact(name, group_nnz, force_ufi):
     assert np.array_equal(cc[order], want_cols)
     assert np.array_equal(bits[order], want_bits)
     info = plan.describe()
-    counts = (hdr[:info["n_chunks"]] >> 4) & 15
+    counts = (hdr[:info["n_chunks"]] >> 8) & 15
     assert int(counts.sum()) == info["n_enum"]
     assert len(hdr) >= info["n_chunks"] + 10 and not hdr[info["n_chunks"]:].any()
-    pc = np.array([bin(int(h) & 15).count("1") for h in hdr[:info["n_chunks"]]])
+    pc = np.array([bin(int(h) & 255).count("1") for h in hdr[:info["n_chunks"]]])
     assert len(stream) == info["stream_words"] >= (UFK + 1) * len(pc) + UFK * int(pc.sum())
 
 
@@ -218,7 +225,7 @@ def test_unsorted_and_duplicate_columns_are_canonicalised():
     for it in items.reshape(-1, 16):
         if not int(it[5]) & 2:
             for h, cols, _ in walk_chunks(it, hdr, stream, wins):
-                slots += [int(c) for c in cols[:(h >> 4) & 15]]
+                slots += [int(c) for c in cols[:(h >> 8) & 15]]
     assert slots.count(7) == 2 and slots.count(2) == 2
     # within a row, duplicates keep their stored order (3 after 1 for column 7 of row 0)
     B = np.eye(8, dtype=np.float32)
@@ -240,13 +247,13 @@ def test_every_pattern_of_a_four_row_panel_is_enumerated():
     for it in items.reshape(-1, 16):
         if not int(it[5]) & 2:
             for h, cols, _ in walk_chunks(it, hdr, stream, wins):
-                seen[h & 15] = int(cols[0])
+                seen[h & 255] = int(cols[0])
     assert sorted(seen) == list(range(1, 16)) and len(seen) == 2 ** 4 - 1
     assert all(col == p - 1 for p, col in seen.items())
     # three rows give 2^3 - 1 = 7 patterns (caption of the paper's Figure 4)
     plan3 = host_plan(gen.csr_from_dense(W[:3]), ufi=4)
     _, hdr3, _, _ = arrays(plan3)
-    pats3 = {int(h) & 15 for h in hdr3[:plan3.describe()["n_chunks"]]}
+    pats3 = {int(h) & 255 for h in hdr3[:plan3.describe()["n_chunks"]]}
     assert pats3 == set(range(1, 8))
 
 
@@ -264,8 +271,8 @@ def test_pattern_histogram_of_uniform_sparsity_matches_closed_form():
         info = plan.describe()
         items, hdr, stream, wins = arrays(plan)
         n = info["n_chunks"]
-        pat = hdr[:n] & 15
-        cnt = (hdr[:n] >> 4) & 15
+        pat = hdr[:n] & 255
+        cnt = (hdr[:n] >> 8) & 15
         hist = np.bincount(pat, weights=cnt, minlength=16)
         UFI = 4
         total_columns = (M // UFI) * K
@@ -280,7 +287,7 @@ def test_pattern_histogram_of_uniform_sparsity_matches_closed_form():
 
 @pytest.mark.parametrize("name", ["tiny", "ragged_rows", "heavy_tail", "all_empty", "single_row"])
 @pytest.mark.parametrize("group_nnz", [0, 32])
-@pytest.mark.parametrize("force_ufi", [0, 1, 2, 4])
+@pytest.mark.parametrize("force_ufi", [0, 1, 2, 4, 8])
 def test_chunk_arrays_evaluate_to_the_product(oracle, name, group_nnz, force_ufi):
     csr = CASES[name]()
     B = gen.dense_activations(csr.K, 5, 99)
