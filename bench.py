@@ -154,14 +154,16 @@ def measured_traffic(workload, N):
     return None
 
 
-def kernel_shape(N):
+def kernel_shape(N, ufi):
     """Template arguments of the instance spmm_execute launches for a tile of N columns
-    (N a multiple of 4, at most 128): slices per wave, floats per lane, pipeline depth."""
+    (N a multiple of 4, at most 128) of a plan with panels of `ufi` rows: slices per
+    wave, floats per lane, pipeline depth (the table of spmm_launch_chunks)."""
+    depth = {8: (2, 4, 8), 4: (3, 3, 4), 2: (3, 4, 6), 1: (3, 4, 8)}[ufi]
     if N > 64:
-        return "S=2,VW=4,D=3"
+        return "S=2,VW=4,D=%d" % depth[0]
     if N > 32:
-        return "S=4,VW=4,D=6"
-    return "S=8,VW=4,D=8"
+        return "S=4,VW=4,D=%d" % depth[1]
+    return "S=8,VW=4,D=%d" % depth[2]
 
 
 def run_sweep(args):
@@ -285,7 +287,7 @@ def main():
     kernel_tflops = 2.0 * nnz * Nd / (avg_ms * 1e-3) / 1e12
     roofline = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": measured_traffic(args.workload, Nd),
-                "kernel": "spmm_chunks_kernel<UFI=%d,%s> (bCols %d)" % (infos[Nd]["ufi"], kernel_shape(Nd), Nd),
+                "kernel": "spmm_chunks_kernel<UFI=%d,%s> (bCols %d)" % (infos[Nd]["ufi"], kernel_shape(Nd, infos[Nd]["ufi"]), Nd),
                 "avg_launch_us": round(avg_ms * 1e3, 3), "median_launch_us": round(med_ms * 1e3, 3),
                 "algorithmic_bytes": bmin, "kernel_tflops": round(kernel_tflops, 3),
                 "frac_of_fp32_valu_peak": round(kernel_tflops / FP32_VALU_PEAK_TFLOPS, 5)}

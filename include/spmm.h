@@ -39,7 +39,7 @@ typedef enum {
 /* Schedule constants and sizes of a plan (all read-only facts). */
 typedef struct {
     int64_t M, K, nnz;
-    int32_t ufi;           /* rows per panel: height of the register tile (the paper's UFi): 4, 2 or 1 */
+    int32_t ufi;           /* rows per panel: height of the register tile (the paper's UFi): 8, 4, 2 or 1 */
     int32_t ufk;           /* enumerated columns in flight per wave (the paper's UFk) */
     int32_t group_nnz;     /* nonzero budget of one row group (one wave's work item) */
     int32_t group_panels;  /* most panels a row group may hold */
@@ -58,7 +58,7 @@ typedef struct {
     int32_t group_panels;  /* override the panel cap per row group (>= 1) */
     int32_t host_only;     /* nonzero: build the plan in host memory only (no device needed;
                               such a plan can be described and exported but not executed) */
-    int32_t ufi;           /* force the rows per panel: 1, 2 or 4 (0 = choose) */
+    int32_t ufi;           /* force the rows per panel: 1, 2, 4 or 8 (0 = choose) */
     int32_t n_hint;        /* number of B columns the plan will mostly be executed with
                               (0 = unknown, >= 0).  Only the choice of the schedule
                               constants looks at it, as the paper's tuner does per bCols

@@ -8,7 +8,7 @@
 
 struct HostPlan {
     int64_t M = 0, K = 0, nnz = 0;
-    int32_t ufi = 0;           // rows per panel (4, 2 or 1)
+    int32_t ufi = 0;           // rows per panel (8, 4, 2 or 1)
     int32_t group_nnz = 0;     // nonzero budget per row group
     int32_t group_panels = 0;  // panel cap per row group
 
@@ -28,7 +28,7 @@ struct HostPlan {
 struct InspectorOptions {
     int32_t group_nnz = 0;     // 0 = choose
     int32_t group_panels = 0;  // 0 = choose
-    int32_t ufi = 0;           // 0 = choose; else 1, 2 or 4
+    int32_t ufi = 0;           // 0 = choose; else 1, 2, 4 or 8
     int32_t n_hint = 0;        // B columns the plan is meant for; 0 = unknown
 };
 
