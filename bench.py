@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path: fp32 CSR SpMM C = A x B on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conv|stress|ffn]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conv|stress|ffn|sweep|ablation|tune]
 
 A step is one pass of the whole hot path (spmm_execute, every kernel it
 launches) over the workload's column counts, with the plan and all operands
@@ -15,9 +15,15 @@ Prints ONE JSON line:
                 the kernel's average duration, measured with HIP events on the
                 launch stream inside the timed region, against 8 TB/s
   cpu_baseline  the CPU oracle timed on the host cores for the same products
-  baselines     rocSPARSE/hipSPARSE CSR SpMM (through torch.sparse) and dense
-                rocBLAS SGEMM (through torch.mm) on the same inputs, as effective
-                GFLOP/s with the same numerator
+  baselines     hipSPARSE CSR SpMM (fastest of its CSR algorithms) and rocBLAS
+                SGEMM on the densified matrix, same inputs, timed with HIP events
+                inside a small C shim (baselines/)
+
+Other workloads print one JSON line of their own: `sweep` (48 matrices x 3 column
+counts against the two libraries), `ablation` (the method's ingredients switched
+on one by one, the ladder of the paper's Figure 7) and `tune` (every panel height
+and three group budgets forced per matrix: what the closed schedule rule loses
+against the best candidate, and the plan's size against CSR and dense).
 """
 import argparse
 import json
@@ -227,6 +233,132 @@ def run_sweep(args):
     print(json.dumps(out))
 
 
+def _time_plan(torch, plan, B, C, N, reps=10, batch=20):
+    pb, pc = B.data_ptr(), C.data_ptr()
+    st = torch.cuda.current_stream().cuda_stream or None
+    fn = lambda: plan.execute_raw(pb, N, pc, st)
+    for _ in range(10):
+        fn()
+    torch.cuda.synchronize()
+    return time_kernel_events(torch, fn, reps, batch=batch)[1] * 1e3   # median, us
+
+
+def _geomean(xs):
+    import math
+    return math.exp(sum(math.log(x) for x in xs) / len(xs))
+
+
+def _ladder_matrices(gen):
+    """The sweep's matrices with at least 1024 rows and columns (24 of the 48)."""
+    return [e for e in gen.sweep_entries() if e["M"] >= 1024 and e["K"] >= 1024]
+
+
+def run_ablation(args):
+    """The ingredients of the method switched on one by one on 24 sweep matrices (paper
+    Section 4.3, Figure 7: baseline -> + enumeration -> + coarsening), as geometric-mean
+    GFLOP/s per column count:
+      rows        one wave per row, rows never cut (the paper's Figure 1a mapping with
+                  this kernel's chunked B loads)
+      +balance    nnz-balanced row groups: heavy rows cut into pieces that meet in LDS
+      +enumerate  panels of 2, 4 or 8 rows enumerated by nonzero pattern, height by the
+                  schedule rule (the full method)"""
+    import torch
+    import paper_2506_15174_amd as spmm
+    from workloads import generators as gen
+    torch.cuda.set_device(0)
+    cols = (32, 64, 128)
+    rungs = ("rows", "+balance", "+enumerate")
+    pts = []
+    t_start = time.perf_counter()
+    for entry in _ladder_matrices(gen):
+        csr = gen.sweep_matrix(entry)
+        nnz = int(csr.row_ptr[-1])
+        a = (csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals)
+        for N in cols:
+            B = torch.from_numpy(gen.activations_for(csr, N)).cuda()
+            C = torch.empty((csr.M, N), dtype=torch.float32, device="cuda")
+            plans = {"rows": spmm.plan_create(*a, ufi=1, group_nnz=1 << 30, group_panels=1),
+                     "+balance": spmm.plan_create(*a, ufi=1, n_hint=N),
+                     "+enumerate": spmm.plan_create(*a, n_hint=N)}
+            row = {"M": csr.M, "K": csr.K, "sparsity": entry["sparsity"], "N": N,
+                   "ufi": plans["+enumerate"].describe()["ufi"]}
+            for r in rungs:
+                us = _time_plan(torch, plans[r], B, C, N)
+                row[r + "_us"] = round(us, 3)
+                row[r + "_gflops"] = round(2.0 * nnz * N / us / 1e3, 1)
+                plans[r].destroy()
+            pts.append(row)
+            print(json.dumps(row), file=sys.stderr, flush=True)
+    summary = {}
+    for N in cols:
+        sel = [p for p in pts if p["N"] == N]
+        summary[str(N)] = {r: round(_geomean([p[r + "_gflops"] for p in sel]), 1) for r in rungs}
+        summary[str(N)]["speedup_full_over_rows"] = round(
+            _geomean([p["rows_us"] / p["+enumerate_us"] for p in sel]), 3)
+    full = [p["+enumerate_gflops"] for p in pts]
+    print(json.dumps({"metric": "fp32 CSR SpMM GFLOP/s (2*nnz*bCols), geomean per rung", "value": round(_geomean(full), 2),
+                      "unit": "GFLOP/s", "n_gpus": 1, "higher_is_better": True, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": "ablation ladder on 24 sweep matrices (M, K >= 1024) x bCols 32/64/128",
+                                 "wall_s": round(time.perf_counter() - t_start, 1)},
+                      "summary": summary, "points": pts}))
+
+
+def run_tune(args):
+    """Offline tuning run (paper Section 3.5): every panel height and three group budgets
+    forced on each of the 24 larger sweep matrices per column count; reports what the
+    inspector's closed rule loses against the best candidate, and the size of the plan
+    against CSR (8 nnz + 4 (M+1) bytes) and dense (4 M K bytes), the comparison of the
+    paper's Section 4.4."""
+    import torch
+    import paper_2506_15174_amd as spmm
+    from workloads import generators as gen
+    torch.cuda.set_device(0)
+    cols = (32, 64, 128)
+    pts = []
+    t_start = time.perf_counter()
+    for entry in _ladder_matrices(gen):
+        csr = gen.sweep_matrix(entry)
+        nnz = int(csr.row_ptr[-1])
+        a = (csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals)
+        for N in cols:
+            B = torch.from_numpy(gen.activations_for(csr, N)).cuda()
+            C = torch.empty((csr.M, N), dtype=torch.float32, device="cuda")
+            auto = spmm.plan_create(*a, n_hint=N)
+            ai = auto.describe()
+            _time_plan(torch, auto, B, C, N, reps=3)          # clocks up before the first figure
+            row = {"M": csr.M, "K": csr.K, "sparsity": entry["sparsity"], "N": N, "rule_ufi": ai["ufi"],
+                   "rule_group_nnz": ai["group_nnz"], "rule_us": round(_time_plan(torch, auto, B, C, N), 3),
+                   "plan_bytes_over_csr": round(ai["device_bytes"] / (8.0 * nnz + 4 * (csr.M + 1)), 3),
+                   "plan_bytes_over_dense": round(ai["device_bytes"] / (4.0 * csr.M * csr.K), 3)}
+            auto.destroy()
+            best = None
+            for ufi in (1, 2, 4, 8):
+                g0 = spmm.plan_create(*a, ufi=ufi, host_only=True).describe()["group_nnz"]
+                for g in sorted({max(32, g0 // 2), g0, min(1024, g0 * 2)}):
+                    plan = spmm.plan_create(*a, ufi=ufi, group_nnz=g)
+                    us = _time_plan(torch, plan, B, C, N, reps=5)
+                    plan.destroy()
+                    if best is None or us < best[0]:
+                        best = (us, ufi, g)
+            row.update(best_us=round(best[0], 3), best_ufi=best[1], best_group_nnz=best[2],
+                       rule_over_best=round(row["rule_us"] / best[0], 3))
+            pts.append(row)
+            print(json.dumps(row), file=sys.stderr, flush=True)
+    summary = {str(N): {"geomean_rule_over_best": round(_geomean([p["rule_over_best"] for p in pts if p["N"] == N]), 3),
+                        "worst": max(p["rule_over_best"] for p in pts if p["N"] == N)} for N in cols}
+    size = {}
+    for sp in sorted({p["sparsity"] for p in pts}):
+        sel = [p for p in pts if p["sparsity"] == sp and p["N"] == 128]
+        size[str(sp)] = {"plan_over_csr": round(_geomean([p["plan_bytes_over_csr"] for p in sel]), 3),
+                         "plan_over_dense": round(_geomean([p["plan_bytes_over_dense"] for p in sel]), 3)}
+    print(json.dumps({"metric": "time of the rule's plan / time of the best forced plan (geomean)",
+                      "value": round(_geomean([p["rule_over_best"] for p in pts]), 3), "unit": "ratio", "n_gpus": 1,
+                      "higher_is_better": False, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": "tuning run on 24 sweep matrices (M, K >= 1024) x bCols 32/64/128",
+                                 "wall_s": round(time.perf_counter() - t_start, 1)},
+                      "summary": summary, "plan_size_by_sparsity_bcols128": size, "points": pts}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -238,8 +370,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
-    if args.workload == "sweep" and args.gpus == 1:
-        return run_sweep(args)
+    if args.gpus == 1 and args.workload in ("sweep", "ablation", "tune"):
+        return {"sweep": run_sweep, "ablation": run_ablation, "tune": run_tune}[args.workload](args)
     if args.gpus != 1:
         raise SystemExit("this build runs on one GPU only: the path shards by rows of A "
                          "(see DESIGN.md) but no multi-GPU run exists; use --gpus 1")
