@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path: fp32 CSR SpMM C = A x B on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conv|stress|ffn|sweep|ablation|tune]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conv|stress|ffn|sweep|narrow|ablation|tune]
 
 A step is one pass of the whole hot path (spmm_execute, every kernel it
 launches) over the workload's column counts, with the plan and all operands
@@ -20,7 +20,7 @@ Prints ONE JSON line:
                 inside a small C shim (baselines/)
 
 Other workloads print one JSON line of their own: `sweep` (48 matrices x 3 column
-counts against the two libraries), `ablation` (the method's ingredients switched
+counts against the two libraries), `narrow` (the same for 4 / 8 / 16 columns), `ablation` (the method's ingredients switched
 on one by one, the ladder of the paper's Figure 7) and `tune` (every panel height
 and three group budgets forced per matrix: what the closed schedule rule loses
 against the best candidate, and the plan's size against CSR and dense).
@@ -172,20 +172,21 @@ def kernel_shape(N, ufi):
     return "S=8,VW=4,D=%d" % depth[2]
 
 
-def run_sweep(args):
+def run_sweep(args, cols=(32, 64, 128), narrow=False):
     """Configuration 4: 48 magnitude-pruned matrices x bCols 32/64/128 against
     hipSPARSE CSR SpMM and rocBLAS SGEMM; geometric means of the speedups and the
-    share of points where this library is faster (the shape of the paper's Table 1)."""
+    share of points where this library is faster (the shape of the paper's Table 1).
+    narrow: the same on the 30 matrices with M, K >= 1024 for bCols 4/8/16, the
+    widths below the kernel's narrowest tile (the paper's Figure 9 measures bCols 4)."""
     import math
     import numpy as np
     import torch
     import paper_2506_15174_amd as spmm
     from workloads import generators as gen
     torch.cuda.set_device(0)
-    cols = (32, 64, 128)
     rows_out = []
     t_start = time.perf_counter()
-    for entry in gen.sweep_entries():
+    for entry in (_ladder_matrices(gen) if narrow else gen.sweep_entries()):
         csr = gen.sweep_matrix(entry)
         nnz = int(csr.row_ptr[-1])
         # one plan per column count: the schedule constants are chosen per bCols
@@ -227,7 +228,8 @@ def run_sweep(args):
     out = {"metric": "fp32 CSR SpMM GFLOP/s (2*nnz*bCols)", "value": round(total_flops / total_s / 1e9, 2),
            "unit": "GFLOP/s", "n_gpus": 1, "steps": 1, "warmup": 10, "ms_per_step": round(total_s * 1e3, 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": "sweep: 48 magnitude-pruned matrices x bCols 32/64/128 (configs[4])",
+           "config": {"workload": ("narrow B: 30 magnitude-pruned matrices (M, K >= 1024) x bCols 4/8/16" if narrow else
+                                   "sweep: 48 magnitude-pruned matrices x bCols 32/64/128 (configs[4])"),
                       "wall_s": round(time.perf_counter() - t_start, 1)},
            "summary": summary, "points": rows_out}
     print(json.dumps(out))
@@ -249,12 +251,12 @@ def _geomean(xs):
 
 
 def _ladder_matrices(gen):
-    """The sweep's matrices with at least 1024 rows and columns (24 of the 48)."""
+    """The sweep's matrices with at least 1024 rows and columns (30 of the 48)."""
     return [e for e in gen.sweep_entries() if e["M"] >= 1024 and e["K"] >= 1024]
 
 
 def run_ablation(args):
-    """The ingredients of the method switched on one by one on 24 sweep matrices (paper
+    """The ingredients of the method switched on one by one on 30 sweep matrices (paper
     Section 4.3, Figure 7: baseline -> + enumeration -> + coarsening), as geometric-mean
     GFLOP/s per column count:
       rows        one wave per row, rows never cut (the paper's Figure 1a mapping with
@@ -298,14 +300,14 @@ def run_ablation(args):
     full = [p["+enumerate_gflops"] for p in pts]
     print(json.dumps({"metric": "fp32 CSR SpMM GFLOP/s (2*nnz*bCols), geomean per rung", "value": round(_geomean(full), 2),
                       "unit": "GFLOP/s", "n_gpus": 1, "higher_is_better": True, "dtype": "f32", "data": "synthetic",
-                      "config": {"workload": "ablation ladder on 24 sweep matrices (M, K >= 1024) x bCols 32/64/128",
+                      "config": {"workload": "ablation ladder on 30 sweep matrices (M, K >= 1024) x bCols 32/64/128",
                                  "wall_s": round(time.perf_counter() - t_start, 1)},
                       "summary": summary, "points": pts}))
 
 
 def run_tune(args):
     """Offline tuning run (paper Section 3.5): every panel height and three group budgets
-    forced on each of the 24 larger sweep matrices per column count; reports what the
+    forced on each of the 30 larger sweep matrices per column count; reports what the
     inspector's closed rule loses against the best candidate, and the size of the plan
     against CSR (8 nnz + 4 (M+1) bytes) and dense (4 M K bytes), the comparison of the
     paper's Section 4.4."""
@@ -354,7 +356,7 @@ def run_tune(args):
     print(json.dumps({"metric": "time of the rule's plan / time of the best forced plan (geomean)",
                       "value": round(_geomean([p["rule_over_best"] for p in pts]), 3), "unit": "ratio", "n_gpus": 1,
                       "higher_is_better": False, "dtype": "f32", "data": "synthetic",
-                      "config": {"workload": "tuning run on 24 sweep matrices (M, K >= 1024) x bCols 32/64/128",
+                      "config": {"workload": "tuning run on 30 sweep matrices (M, K >= 1024) x bCols 32/64/128",
                                  "wall_s": round(time.perf_counter() - t_start, 1)},
                       "summary": summary, "plan_size_by_sparsity_bcols128": size, "points": pts}))
 
@@ -370,6 +372,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
+    if args.gpus == 1 and args.workload == "narrow":
+        return run_sweep(args, cols=(4, 8, 16), narrow=True)
     if args.gpus == 1 and args.workload in ("sweep", "ablation", "tune"):
         return {"sweep": run_sweep, "ablation": run_ablation, "tune": run_tune}[args.workload](args)
     if args.gpus != 1:

@@ -91,7 +91,7 @@ def test_ffn_config(torch_gpu, oracle, shape_index, sparsity_index, N):
     check(oracle, csr, B, C)
 
 
-@pytest.mark.parametrize("N", [1, 2, 31, 33, 63, 65, 96, 127, 130, 200, 256, 257])
+@pytest.mark.parametrize("N", [1, 2, 4, 8, 12, 16, 20, 31, 33, 63, 65, 96, 127, 130, 144, 200, 256, 257])
 def test_any_column_count_with_ragged_rows_and_split_panels(torch_gpu, oracle, N):
     csr = heavy_tail(39, 1500, 40 + N)   # M % 8 != 0, dense rows, empty rows
     B = gen.dense_activations(csr.K, N, 50 + N)
@@ -110,7 +110,7 @@ def test_group_budget_does_not_change_the_result_class(torch_gpu, oracle, group_
 
 
 @pytest.mark.parametrize("ufi", [0, 1, 2, 4, 8])
-@pytest.mark.parametrize("N", [32, 64, 128, 100])
+@pytest.mark.parametrize("N", [4, 8, 16, 32, 64, 128, 100])
 def test_small_integer_data_is_bit_exact(torch_gpu, oracle, N, ufi):
     rng = np.random.default_rng(70 + N)
     M, K = 203, 900
