@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path: fp32 CSR SpMM C = A x B on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conv|stress|ffn|sweep|narrow|ablation|tune]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conv|stress|ffn|matrix|sweep|narrow|ablation|tune]
 
 A step is one pass of the whole hot path (spmm_execute, every kernel it
 launches) over the workload's column counts, with the plan and all operands
@@ -44,8 +44,14 @@ def bytes_min(M, K, nnz, N):
     return 4 * (M + 1) + 8 * nnz + 4 * K * N + 4 * M * N
 
 
-def build_workload(name):
+def build_workload(name, args=None):
     from workloads import generators as gen
+    if name == "matrix":
+        # one matrix of the sweep's recipe, for counter runs: --shape MxK --sparsity s --bcols N
+        M, K = (int(x) for x in args.shape.lower().split("x"))
+        return ("magnitude-pruned N(0,1) %dx%d @%g%% (sweep recipe, seed %d), bCols %d"
+                % (M, K, 100 * args.sparsity, args.seed, args.bcols),
+                gen.magnitude_pruned(M, K, args.sparsity, args.seed), (args.bcols,))
     if name == "conv":
         return ("conv1x1 512x2048 @80% magnitude-pruned N(0,1), bCols 32/64/128 (configs[1])",
                 gen.conv_layer(), (32, 64, 128))
@@ -367,6 +373,10 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="conv")
+    ap.add_argument("--shape", default="4096x4096", help="--workload matrix: rows x columns of A")
+    ap.add_argument("--sparsity", type=float, default=0.5, help="--workload matrix: pruned share")
+    ap.add_argument("--bcols", type=int, default=128, help="--workload matrix: columns of B")
+    ap.add_argument("--seed", type=int, default=11, help="--workload matrix: generator seed")
     ap.add_argument("--no-baselines", action="store_true")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -387,7 +397,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
-    label, csr, cols = build_workload(args.workload)
+    label, csr, cols = build_workload(args.workload, args)
     nnz = int(csr.row_ptr[-1])
     t0 = time.perf_counter()
     # one plan per column count: the schedule constants are chosen per bCols, as the

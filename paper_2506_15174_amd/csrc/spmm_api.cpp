@@ -149,6 +149,7 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
     a.items = plan->d_items;
     a.n_blocks = (int32_t)h.n_blocks;
     a.ldn = N;
+    a.col_mask = h.K <= ((int64_t)1 << spmm_fmt::COL_PATTERN_SHIFT) ? spmm_fmt::COL_INDEX_MASK : 0xFFFFFFFFu;
     // Column tiles run one after another on the stream.
     int32_t j0 = 0;
     while (j0 < N) {

@@ -33,11 +33,16 @@ constexpr int UFK = 8;
 //                                     single chunk of a panel without nonzeros
 //                         bits 8..11  count of real columns, 0..UFK
 //                         bit  12     last chunk of its panel (write the tile)
-//   columns    UFK column indices (slots >= count repeat a valid column of the
-//              chunk, or 0, and carry zero values)
+//   columns    UFK column words (slots >= count repeat a valid column of the chunk,
+//              or 0, and carry zero values).  Bits 0..23 hold the column index.  The
+//              leftovers of several patterns may share a chunk; its header then holds
+//              the union of their patterns and a slot whose own pattern is smaller
+//              keeps it in bits 24..31 (0 = the slot has the chunk's pattern).  Plans
+//              of matrices with more than 2^24 columns never share chunks and use all
+//              32 bits for the index.
 //   values     for every set row of the pattern in ascending row order UFK value
 //              words (float bits, value of that row in column slot u; zero in
-//              unused slots)
+//              unused slots and in slots whose own pattern lacks the row)
 //
 // The chunks of a row group are cut into *windows*, the unit a wave stages through
 // LDS: as many consecutive chunks as fit WIN_WORDS words.  `stream` holds the
@@ -53,6 +58,8 @@ constexpr uint32_t HDR_PATTERN_MASK = 0xFFu;
 constexpr int HDR_COUNT_SHIFT = 8;
 constexpr uint32_t HDR_COUNT_MASK = 0xFu;
 constexpr uint32_t HDR_END_PANEL = 1u << 12;
+constexpr int COL_PATTERN_SHIFT = 24;
+constexpr uint32_t COL_INDEX_MASK = (1u << COL_PATTERN_SHIFT) - 1u;
 
 // Words of LDS one wave owns (its window; later its partial tile).
 constexpr int WIN_WORDS = 1024;

@@ -15,6 +15,7 @@ struct spmm_launch_args {
     float *C;               // DEVICE first column of the column tile
     int32_t ldn;            // leading dimension of B and C (= N)
     int32_t width;          // columns in this tile
+    uint32_t col_mask;      // bits of a column word that hold the column index
 };
 
 // Enqueues one column tile.  ufi = rows per panel of the plan (1, 2, 4).  slices = 2 / 4 / 8: four columns per lane, tile of up

@@ -204,7 +204,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_WG, (waves_per_simd(S, UFI))) void
 spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                    const uint32_t *__restrict__ wins_g, const uint32_t *__restrict__ items_g,
                    const float *__restrict__ B, uint32_t b_bytes, float *__restrict__ C, int32_t ldn,
-                   int32_t width)
+                   int32_t width, uint32_t col_mask)
 {
     typedef typename Vec<VW>::type vec_t;
     typedef typename BSource<WIDE>::off_t off_t;
@@ -223,6 +223,10 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
     const uint32_t flags = it[IT_FLAGS];
     const uint32_t n_wins = it[IT_NWINS];
     uint32_t *win = lds[wave];
+
+    // Column index of a column word.  The top byte may hold a slot pattern (shared
+    // leftover chunks); the 24-bit multiply of the narrow path ignores it anyway.
+    auto col_index = [&](uint32_t word) -> uint32_t { return WIDE ? (word & col_mask) : word; };
 
     // Lanes beyond the tile width compute on the tile's first columns and store
     // nothing: no divergent control flow in the hot loop, no out-of-range access.
@@ -268,14 +272,14 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                 lds_read<Q>(cv, win, cols_base + (uint32_t)(j * UFK));
                 const uint32_t ld_eff = (uint32_t)j < wc ? ld_bytes : 0u;
 #pragma unroll
-                for (int q = 0; q < Q; ++q) src.load(b[j][q], BSource<WIDE>::offset(cv[q], ld_eff, lane_off));
+                for (int q = 0; q < Q; ++q) src.load(b[j][q], BSource<WIDE>::offset(col_index(cv[q]), ld_eff, lane_off));
             }
             {
                 uint32_t cv[Q];
                 lds_read<Q>(cv, win, cols_base + (uint32_t)((D - 1) * UFK));
                 const uint32_t ld_eff = (uint32_t)(D - 1) < wc ? ld_bytes : 0u;
 #pragma unroll
-                for (int q = 0; q < Q; ++q) voff[q] = BSource<WIDE>::offset(cv[q], ld_eff, lane_off);
+                for (int q = 0; q < Q; ++q) voff[q] = BSource<WIDE>::offset(col_index(cv[q]), ld_eff, lane_off);
             }
             // last word a slice may start a value read at (blocks are requested for
             // every row of the tile; those of rows outside the pattern are clamped
@@ -334,7 +338,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                     }
 
 #pragma unroll
-                    for (int q = 0; q < Q; ++q) voff[q] = BSource<WIDE>::offset(cv[q], ld_next, lane_off);
+                    for (int q = 0; q < Q; ++q) voff[q] = BSource<WIDE>::offset(col_index(cv[q]), ld_next, lane_off);
 
                     if (__builtin_expect((h_now & HDR_END_PANEL) != 0, 0)) {
                         // add the slices' partial tiles across lanes
@@ -403,7 +407,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
 #define SPMM_LAUNCH(U, S, VW, D, WIDE)                                                                \
     hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE>), dim3((unsigned)a.n_blocks),           \
                        dim3(64 * WAVES_PER_WG), 0, (hipStream_t)stream, a.stream, a.wins, a.items,    \
-                       a.B, a.b_bytes, a.C, a.ldn, a.width)
+                       a.B, a.b_bytes, a.C, a.ldn, a.width, a.col_mask)
 
 // Pipeline depths: as deep as the 128 VGPRs of a wave allow.  The eight-row tile
 // holds 32 accumulators, which leaves room for fewer B rows in flight.

@@ -44,43 +44,46 @@ struct Entry {
 // columns by timing candidates (Section 3.5 "Scheduler & Tuner").  The closed rule
 // below is the outcome of that exercise on MI355X, fitted to timings of pruned-layer
 // shapes (256 .. 8192 rows and columns, 50 .. 98 % pruned) with forced heights.
-// `row` is the mean number of entries per row; "dense" means that at least a
-// twelfth of the entries is kept.
+// `row` is the mean number of entries per row.
 //
+//   * whatever the width: single rows when the rows of B a column tile touches
+//     (K rows of 128 / 256 / 512 bytes for narrow / medium / wide B) exceed the
+//     4 MiB of one L2: every wave then sweeps B in ascending row order and waves
+//     that run together stay close together in B, which tall panels (pattern by
+//     pattern) give up;
 //   * narrow B (hint <= 32 columns): one wave load already covers eight enumerated
 //     columns, so tall panels save few loads and pay with a longer dependent chain
 //     per chunk: four rows only from 4096 rows on with row >= 1024; two rows for
 //     512 .. 4095 rows with row >= 256; else single rows;
-//   * medium B (hint 33 .. 64), dense and row >= 256: eight rows from 4096 rows on
-//     with row >= 2048, four rows from 2048 rows on, two from 512 on; else single
-//     rows;
-//   * wide or unknown B, dense and row >= 128: eight rows from 4096 rows on with
-//     row >= 1024, four rows from 1024 rows on, two from 512 on; else single rows.
+//   * medium B (hint 33 .. 64): eight rows from 4096 rows on with row >= 256; two
+//     rows for 512 .. 4095 rows with row >= 64; else single rows;
+//   * wide or unknown B: eight rows from 4096 rows on with row >= 192; for 1024 ..
+//     4095 rows four rows with row >= 128 and two with row >= 64; two rows for
+//     512 .. 1023 rows with row >= 128; else single rows.
 //
-// Sparser or shorter rows leave most patterns with one row set, and the partly
-// filled chunks of many patterns cost more than the shared B rows save; few rows
-// cannot fill the chip with tall panels (a split panel of eight rows owns a whole
-// workgroup).
+// Short rows leave most patterns with one row set, so tall panels share nothing;
+// few rows cannot fill the chip with tall panels (a split panel of eight rows owns
+// a whole workgroup: 1024 rows give 128 workgroups).
 int choose_ufi(int64_t M, int64_t K, int64_t nnz, int32_t n_hint)
 {
     const int64_t row = M > 0 ? nnz / M : 0;
-    if (n_hint > 0 && n_hint <= 32) {
+    const bool narrow = n_hint > 0 && n_hint <= 32;
+    const bool medium = n_hint > 32 && n_hint <= 64;
+    const int64_t tile_row_bytes = narrow ? 128 : medium ? 256 : 512;
+    if (K * tile_row_bytes > ((int64_t)4 << 20)) return 1;
+    if (narrow) {
         if (M >= 4096) return row >= 1024 ? 4 : 1;
         if (M >= 512) return row >= 256 ? 2 : 1;
         return 1;
     }
-    const bool dense = nnz * 12 >= M * K;
-    if (n_hint > 0 && n_hint <= 64) {
-        if (!dense || row < 256) return 1;
-        if (M >= 4096 && row >= 2048) return 8;
-        if (M >= 2048) return 4;
-        if (M >= 512) return 2;
+    if (medium) {
+        if (M >= 4096) return row >= 256 ? 8 : 1;
+        if (M >= 512) return row >= 64 ? 2 : 1;
         return 1;
     }
-    if (!dense || row < 128) return 1;
-    if (M >= 4096 && row >= 1024) return 8;
-    if (M >= 1024) return 4;
-    if (M >= 512) return 2;
+    if (M >= 4096) return row >= 192 ? 8 : 1;
+    if (M >= 1024) return row >= 128 ? 4 : row >= 64 ? 2 : 1;
+    if (M >= 512) return row >= 128 ? 2 : 1;
     return 1;
 }
 
@@ -112,23 +115,33 @@ struct Emitter {
     std::vector<uint32_t> hdr, cols, vals;
     int64_t n_enum = 0;
     int ufi = MAX_UFI;
+    bool merge = true;            // leftovers of different patterns may share a chunk
+    std::vector<Entry> leftovers; // scratch of panel()
 
-    // Emits one chunk of `count` entries (all of pattern `pattern`).
-    void chunk(const Entry *e, int count, uint32_t pattern, bool end_panel)
+    // Emits one chunk of `count` entries.  Its pattern is the union of the entries'
+    // patterns; an entry whose own pattern is smaller keeps it in the top byte of
+    // its column word and has zeros in the value blocks of the rows it lacks.
+    void chunk(const Entry *e, int count, bool end_panel)
     {
+        uint32_t pattern = 0;
+        for (int u = 0; u < count; ++u) pattern |= e[u].pattern;
         uint32_t h = pattern | ((uint32_t)count << HDR_COUNT_SHIFT);
         if (end_panel) h |= HDR_END_PANEL;
         hdr.push_back(h);
         for (int u = 0; u < UFK; ++u) {
-            int32_t c = 0;
-            if (count > 0) c = e[u < count ? u : count - 1].col;
-            cols.push_back((uint32_t)c);
+            uint32_t c = 0;
+            if (count > 0) {
+                const Entry &s = e[u < count ? u : count - 1];
+                c = (uint32_t)s.col;
+                if (u < count && s.pattern != pattern) c |= s.pattern << COL_PATTERN_SHIFT;
+            }
+            cols.push_back(c);
         }
         for (int r = 0; r < ufi; ++r) {
             if (!(pattern & (1u << r))) continue;
             for (int u = 0; u < UFK; ++u) {
                 uint32_t bits = 0;
-                if (u < count) std::memcpy(&bits, &e[u].v[r], 4);
+                if (u < count && (e[u].pattern & (1u << r))) std::memcpy(&bits, &e[u].v[r], 4);
                 vals.push_back(bits);
             }
         }
@@ -136,20 +149,47 @@ struct Emitter {
     }
 
     // Emits the chunks of one panel (or one piece of a panel) whose entries are
-    // ordered so that equal patterns are adjacent.
+    // ordered so that equal patterns are adjacent: first the full chunks of every
+    // pattern, then the leftovers (fewer than UFK entries per pattern), packed UFK
+    // at a time in pattern order.  A leftover chunk costs one step of the kernel
+    // whatever it holds, so sharing it between patterns saves both B loads and
+    // multiply slots: the paper's compaction of rarely used enumerated blocks
+    // (Section 3.2.2), done in the data instead of the code.
     void panel(const std::vector<Entry> &ents)
     {
         if (ents.empty()) {
-            chunk(nullptr, 0, 0, true);
+            chunk(nullptr, 0, true);
             return;
         }
-        size_t i = 0;
         const size_t n = ents.size();
-        while (i < n) {
+        leftovers.clear();
+        size_t n_full = 0;
+        for (size_t i = 0; i < n;) {
             size_t j = i + 1;
-            while (j < n && j - i < (size_t)UFK && ents[j].pattern == ents[i].pattern) ++j;
-            chunk(&ents[i], (int)(j - i), ents[i].pattern, j == n);
+            while (j < n && ents[j].pattern == ents[i].pattern) ++j;
+            const size_t full = (j - i) / (size_t)UFK;
+            n_full += full;
+            const size_t rest0 = merge ? i + full * (size_t)UFK : j;
+            for (size_t q = rest0; q < j; ++q) leftovers.push_back(ents[q]);
+            if (!merge) n_full += (j - i) % (size_t)UFK ? 1 : 0;
             i = j;
+        }
+        // pass 2: emit
+        size_t emitted = 0;
+        for (size_t i = 0; i < n;) {
+            size_t j = i + 1;
+            while (j < n && ents[j].pattern == ents[i].pattern) ++j;
+            const size_t stop = merge ? i + (j - i) / (size_t)UFK * (size_t)UFK : j;
+            for (size_t q = i; q < stop; q += (size_t)UFK) {
+                const int count = (int)std::min<size_t>((size_t)UFK, stop - q);
+                emitted += 1;
+                chunk(&ents[q], count, emitted == n_full && leftovers.empty());
+            }
+            i = j;
+        }
+        for (size_t q = 0; q < leftovers.size(); q += (size_t)UFK) {
+            const int count = (int)std::min<size_t>((size_t)UFK, leftovers.size() - q);
+            chunk(&leftovers[q], count, q + (size_t)UFK >= leftovers.size());
         }
     }
 };
@@ -253,6 +293,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         // ---- 2. enumeration and emission, panel by panel ----------------------
         Emitter em;
         em.ufi = UFI;
+        em.merge = K <= ((int64_t)1 << COL_PATTERN_SHIFT);  // the top byte of a column word must be free
         em.hdr.reserve((size_t)(nnz / 4 + P + 16));
         em.cols.reserve((size_t)(nnz / 4 + P + 16) * UFK);
         em.vals.reserve((size_t)(nnz + nnz / 2 + 64));

@@ -11,6 +11,8 @@ MAX_UFI = 8
 UFK = 8
 ITEM_WORDS = 16
 WIN_WORDS = 1024
+COL_PATTERN_SHIFT = 24
+COL_INDEX_MASK = (1 << COL_PATTERN_SHIFT) - 1
 
 
 WAVES_PER_WG = 8
@@ -70,24 +72,22 @@ def choose_ufi(M, K, nnz, n_hint=0):
     """The inspector's panel height as a function of the shape, the number of
     entries and the number of B columns the plan is meant for (0 = unknown)."""
     row = nnz // M if M else 0
-    if 0 < n_hint <= 32:
+    narrow, medium = 0 < n_hint <= 32, 32 < n_hint <= 64
+    if K * (128 if narrow else 256 if medium else 512) > 4 << 20:
+        return 1
+    if narrow:
         if M >= 4096:
             return 4 if row >= 1024 else 1
-        if M >= 512:
-            return 2 if row >= 256 else 1
-        return 1
-    dense = nnz * 12 >= M * K
-    if 0 < n_hint <= 64:
-        if not dense or row < 256:
-            return 1
-        if M >= 4096 and row >= 2048:
-            return 8
-        return 4 if M >= 2048 else 2 if M >= 512 else 1
-    if not dense or row < 128:
-        return 1
-    if M >= 4096 and row >= 1024:
-        return 8
-    return 4 if M >= 1024 else 2 if M >= 512 else 1
+        return 2 if (M >= 512 and row >= 256) else 1
+    if medium:
+        if M >= 4096:
+            return 8 if row >= 256 else 1
+        return 2 if (M >= 512 and row >= 64) else 1
+    if M >= 4096:
+        return 8 if row >= 192 else 1
+    if M >= 1024:
+        return 4 if row >= 128 else 2 if row >= 64 else 1
+    return 2 if (M >= 512 and row >= 128) else 1
 
 
 def choose_group_budget(M, nnz, ufi):
@@ -208,8 +208,17 @@ def decode_plan(items, hdr, stream, wins, ufi):
             assert rows_left > 0, "chunks after the last panel of the group"
             rows_here = min(ufi, rows_left)
             assert pattern < (1 << rows_here), "pattern names a row beyond the panel"
+            # a slot's own pattern: the top byte of its column word, or the chunk's
+            own = [(int(cc[u]) >> COL_PATTERN_SHIFT) or pattern for u in range(count)]
+            union = 0
+            for u in range(count):
+                assert own[u] & ~pattern == 0 and own[u] != 0, "a slot's pattern lies inside the chunk's"
+                assert (int(cc[u]) >> COL_PATTERN_SHIFT) != pattern, "a full slot pattern is stored as 0"
+                union |= own[u]
+            assert union == pattern, "the chunk's pattern is the union of its slots'"
             if count:
-                assert np.all(cc[count:] == cc[count - 1]), "unused slots repeat the last real column"
+                assert np.all((cc[count:] & COL_INDEX_MASK) == (cc[count - 1] & COL_INDEX_MASK)), \
+                    "unused slots repeat the last real column"
             t = 0
             for r in range(ufi):
                 if not (pattern >> r) & 1:
@@ -218,9 +227,12 @@ def decode_plan(items, hdr, stream, wins, ufi):
                 t += 1
                 assert not block[count:].any(), "unused value slots must be zero"
                 for u in range(count):
-                    out_rows.append(row + r)
-                    out_cols.append(int(cc[u]))
-                    out_bits.append(int(block[u]))
+                    if (own[u] >> r) & 1:
+                        out_rows.append(row + r)
+                        out_cols.append(int(cc[u]) & COL_INDEX_MASK)
+                        out_bits.append(int(block[u]))
+                    else:
+                        assert block[u] == 0, "a slot without the row holds a zero there"
             if end:
                 row += rows_here
                 rows_left -= rows_here
@@ -259,7 +271,7 @@ def interpret_plan(items, hdr, stream, wins, B, M, ufi):
                     for u in range(UFK):
                         a = np.float64(fv[u])
                         # fused multiply-add: exact product and sum in double, one rounding
-                        acc[r] = (a * B64[cc[u]] + acc[r].astype(np.float64)).astype(np.float32)
+                        acc[r] = (a * B64[cc[u] & COL_INDEX_MASK] + acc[r].astype(np.float64)).astype(np.float32)
                 if end:
                     rows_here = min(ufi, rows_left)
                     if flags & FLAG_SPLIT:

@@ -129,11 +129,11 @@ SCHEDULE_CASES = [
     ((512, 2048, 410, 32), (2, 160, 1)),
     # ... but rows of 200 stay single: 512 panels of 200 -> 8 pieces -> ceil(5*200/32) = 32
     ((512, 2048, 200, 32), (1, 32, 1)),
-    # 4096 x 1024 at 50 %: 4 rows; 1024 panels of 2048 -> 8 pieces -> 320
-    ((4096, 1024, 512, 128), (4, 320, 1)),
+    # 4096 x 1024 at 50 %, wide B: 8 rows; 512 panels of 4096 -> 8 pieces -> 640
+    ((4096, 1024, 512, 128), (8, 640, 1)),
     # narrow B, rows of 512 < 1024: single rows; 4096 whole rows -> 640
     ((4096, 1024, 512, 32), (1, 640, 1)),
-    # 5 % kept: single rows whatever the hint; 4096 whole rows of 52 -> 65 -> 96
+    # rows of 52 < 192: single rows; 4096 whole rows of 52 -> 65 -> 96
     ((4096, 1024, 52, 0), (1, 96, 1)),
     # 256 rows: too few panels for tall ones; 256 rows of 128 -> 8 pieces -> 20 -> 32
     ((256, 256, 128, 128), (1, 32, 1)),
@@ -144,14 +144,16 @@ SCHEDULE_CASES = [
     # ... medium and wide B: 8 rows; 1024 panels -> 8 pieces, capped
     ((8192, 8192, 4096, 64), (8, 1024, 1)),
     ((8192, 8192, 4096, 128), (8, 1024, 1)),
-    # 64 columns of B: 4 rows from 2048 rows on when rows hold 256 or more
-    ((4096, 1024, 512, 64), (4, 320, 1)),
-    # ... 1024 panels of 1640 -> 8 pieces -> ceil(5*1640/32) = 257 -> 288
-    ((4096, 4096, 410, 64), (4, 288, 1)),
+    # 64 columns of B: 8 rows from 4096 rows on when rows hold 256 or more
+    ((4096, 1024, 512, 64), (8, 640, 1)),
+    # ... 512 panels of 3280 -> 8 pieces -> ceil(5*3280/32) = 513 -> 544
+    ((4096, 4096, 410, 64), (8, 544, 1)),
     # ... 1024 rows: 2 rows; 512 panels of 4096 -> 8 pieces -> 640
     ((1024, 4096, 2048, 64), (2, 640, 1)),
-    # wide B, a tenth kept but rows of 102 < 128: single rows; 1024 rows -> 8 pieces -> 16 -> 32
-    ((1024, 1024, 102, 128), (1, 32, 1)),
+    # wide B, 1024 rows of 102 (64 <= 102 < 128): 2 rows; 512 panels of 204 -> ceil(1020/32) = 32
+    ((1024, 1024, 102, 128), (2, 32, 1)),
+    # 16384 rows of B of 512 bytes do not fit one L2: single rows; 2 panels per wave, capped budget
+    ((16384, 16384, 800, 128), (1, 1024, 2)),
 ]
 
 
@@ -207,6 +209,39 @@ def test_format_round_trip_is_bit_exact(name, group_nnz, force_ufi):
     assert len(stream) == info["stream_words"] >= (UFK + 1) * len(pc) + UFK * int(pc.sum())
 
 
+def slot_patterns(h, cols):
+    """(own pattern, column index) of the real slots of a chunk: a slot's pattern is
+    the top byte of its column word, or the chunk's when that byte is 0."""
+    return [((int(c) >> 24) or (int(h) & 255), int(c) & 0xFFFFFF) for c in cols[:(int(h) >> 8) & 15]]
+
+
+def test_leftovers_of_different_patterns_share_chunks():
+    # 4-row panel, K = 64: columns 0..9 have pattern 0b0001, 10..12 pattern 0b0110,
+    # 13..14 pattern 0b1000: one full chunk of pattern 1, then 2 + 3 + 2 leftovers
+    # in one chunk whose header holds the union 0b1111
+    W = np.zeros((4, 64), dtype=np.float32)
+    W[0, 0:10] = np.arange(1, 11)
+    W[1, 10:13] = 20 + np.arange(3)
+    W[2, 10:13] = 30 + np.arange(3)
+    W[3, 13:15] = 40 + np.arange(2)
+    plan = host_plan(gen.csr_from_dense(W), ufi=4)
+    items, hdr, stream, wins = arrays(plan)
+    info = plan.describe()
+    assert info["n_chunks"] == 2 and info["n_enum"] == 15
+    chunks = [c for it in items.reshape(-1, 16) if not int(it[5]) & 2 for c in walk_chunks(it, hdr, stream, wins)]
+    (h0, c0, v0), (h1, c1, v1) = chunks
+    assert h0 & 255 == 0b0001 and (h0 >> 8) & 15 == 8 and not (h0 >> 12) & 1
+    assert [x for _, x in slot_patterns(h0, c0)] == list(range(8)) and all(int(c) >> 24 == 0 for c in c0)
+    assert h1 & 255 == 0b1111 and (h1 >> 8) & 15 == 7 and (h1 >> 12) & 1
+    assert slot_patterns(h1, c1) == [(1, 8), (1, 9), (6, 10), (6, 11), (6, 12), (8, 13), (8, 14)]
+    # four value blocks (rows 0..3); a slot holds zeros in the rows it lacks
+    f = [b.view(np.float32) for b in v1]
+    assert f[0].tolist() == [9, 10, 0, 0, 0, 0, 0, 0]
+    assert f[1].tolist() == [0, 0, 20, 21, 22, 0, 0, 0]
+    assert f[2].tolist() == [0, 0, 30, 31, 32, 0, 0, 0]
+    assert f[3].tolist() == [0, 0, 0, 0, 0, 40, 41, 0]
+
+
 def test_unsorted_and_duplicate_columns_are_canonicalised():
     row_ptr = np.array([0, 5, 5, 8, 9], dtype=np.int32)
     col_idx = np.array([7, 2, 7, 0, 2, 2, 7, 1, 7], dtype=np.int32)
@@ -225,7 +260,7 @@ def test_unsorted_and_duplicate_columns_are_canonicalised():
     for it in items.reshape(-1, 16):
         if not int(it[5]) & 2:
             for h, cols, _ in walk_chunks(it, hdr, stream, wins):
-                slots += [int(c) for c in cols[:(h >> 8) & 15]]
+                slots += [int(c) & 0xFFFFFF for c in cols[:(h >> 8) & 15]]
     assert slots.count(7) == 2 and slots.count(2) == 2
     # within a row, duplicates keep their stored order (3 after 1 for column 7 of row 0)
     B = np.eye(8, dtype=np.float32)
@@ -247,13 +282,20 @@ def test_every_pattern_of_a_four_row_panel_is_enumerated():
     for it in items.reshape(-1, 16):
         if not int(it[5]) & 2:
             for h, cols, _ in walk_chunks(it, hdr, stream, wins):
-                seen[h & 255] = int(cols[0])
+                for own, col in slot_patterns(h, cols):
+                    seen[own] = col
     assert sorted(seen) == list(range(1, 16)) and len(seen) == 2 ** 4 - 1
     assert all(col == p - 1 for p, col in seen.items())
+    # one column per pattern: all fifteen are leftovers and share two chunks
+    assert plan.describe()["n_chunks"] == 2
     # three rows give 2^3 - 1 = 7 patterns (caption of the paper's Figure 4)
     plan3 = host_plan(gen.csr_from_dense(W[:3]), ufi=4)
-    _, hdr3, _, _ = arrays(plan3)
-    pats3 = {int(h) & 255 for h in hdr3[:plan3.describe()["n_chunks"]]}
+    items3, hdr3, stream3, wins3 = arrays(plan3)
+    pats3 = set()
+    for it in items3.reshape(-1, 16):
+        if not int(it[5]) & 2:
+            for h, cols, _ in walk_chunks(it, hdr3, stream3, wins3):
+                pats3 |= {own for own, _ in slot_patterns(h, cols)}
     assert pats3 == set(range(1, 8))
 
 
@@ -270,10 +312,12 @@ def test_pattern_histogram_of_uniform_sparsity_matches_closed_form():
         plan = host_plan(csr, group_nnz=1 << 20, group_panels=1 << 20, ufi=4)
         info = plan.describe()
         items, hdr, stream, wins = arrays(plan)
-        n = info["n_chunks"]
-        pat = hdr[:n] & 255
-        cnt = (hdr[:n] >> 8) & 15
-        hist = np.bincount(pat, weights=cnt, minlength=16)
+        hist = np.zeros(16)
+        for it in items.reshape(-1, 16):
+            if not int(it[5]) & 2:
+                for h, cols, _ in walk_chunks(it, hdr, stream, wins):
+                    for own, _ in slot_patterns(h, cols):
+                        hist[own] += 1
         UFI = 4
         total_columns = (M // UFI) * K
         for p in range(1, 16):
