@@ -69,9 +69,11 @@ typedef struct {
  * Inspector (paper Section 3.2 "Enumeration", Section 3.3 "Data
  * transformation", Section 3.4 "Data transformer"; here from CSR in O(nnz log)
  * rather than from dense A).  Validates the CSR, orders the columns of every
- * row, enumerates nnz-balanced row groups, merges the columns of each panel of
- * `ufi` rows into enumerated columns tagged with their nonzero pattern,
- * re-stores the values in schedule order and uploads the result.
+ * row, picks the panel height `ufi` and the group budget from the shape, the
+ * number of nonzeros and the B-column hint, enumerates nnz-balanced row groups,
+ * merges the columns of each panel of `ufi` rows into enumerated columns tagged
+ * with their nonzero pattern, re-stores the values in schedule order and
+ * uploads the result.
  *
  *   plan     HOST  out; set to NULL on failure
  *   M, K     rows / columns of A; 0 is legal
@@ -108,7 +110,9 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
  * execution (pieces of a split panel meet in on-chip memory, not in the plan),
  * so any number of executes of one plan may be in flight on any streams.
  * Results are bit-identical from run to run.  B and C must be 4-byte aligned;
- * 8-byte alignment with even N enables the two-columns-per-lane kernels.
+ * 16-byte alignment of both with N a multiple of 4 enables the kernels that
+ * handle four columns per lane (all the tuned ones); anything else runs on the
+ * one-column-per-lane kernel.
  */
 spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N,
                            float *C, void *stream);

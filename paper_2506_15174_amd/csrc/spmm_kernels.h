@@ -18,7 +18,7 @@ struct spmm_launch_args {
     uint32_t col_mask;      // bits of a column word that hold the column index
 };
 
-// Enqueues one column tile.  ufi = rows per panel of the plan (1, 2, 4).  slices = 2 / 4 / 8: four columns per lane, tile of up
+// Enqueues one column tile.  ufi = rows per panel of the plan (1, 2, 4, 8).  slices = 2 / 4 / 8: four columns per lane, tile of up
 // to 128 / 64 / 32 columns (width a multiple of 4, B and C 16-byte aligned);
 // slices = 1: one column per lane, tile of up to 64 columns, any alignment.
 // wide = 64-bit addressing of B.  Returns the hipError_t of the launch as int.

@@ -2,8 +2,9 @@
 // the inspector (paper Section 3.3 "Sparse Coarsen", Listings 5-7, re-derived
 // for wave64 and for the memory paths of a CDNA4 compute unit).
 //
-// One wave executes one row group; up to 8 waves form a workgroup, and the
-// register budget (at most 128 VGPRs) lets two workgroups share a compute unit.
+// One wave executes one row group; 8 waves form a workgroup, and the register
+// budget of an instance (128 / 80 / 64 VGPRs for 2 / 4 / 8 slices) lets two to
+// four workgroups share a compute unit.
 //
 //   * Lanes run along j, the columns of B and C (the paper's map(j, .),
 //     Listing 5).  A vector load costs the compute unit's address path the same
@@ -15,7 +16,9 @@
 //     when a panel ends (the warp-level reduction of Section 3.3.2).
 //   * The UFI x 4 accumulators of a panel stay in VGPRs across all chunks of the
 //     panel (the paper's register tile, Listing 6).
-//   * A chunk is UFK = 8 enumerated columns of one nonzero pattern.  Its column
+//   * A chunk is UFK = 8 enumerated columns of one nonzero pattern (or leftovers
+//     of several patterns under the union of their patterns, with zeros where a
+//     column lacks a row).  Its column
 //     indices and values are staged through LDS, a window of the group's stream
 //     at a time, with coalesced 16-byte loads (the scalar data path tops out far
 //     below what the stream needs); a slice reads its own slots back with one
