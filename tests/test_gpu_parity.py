@@ -134,6 +134,14 @@ def test_identity_and_empty_matrices(torch_gpu, oracle):
     empty = gen.csr_from_dense(np.zeros((11, n), dtype=np.float32))
     C0, _ = gpu_product(torch_gpu, empty, B)
     assert C0.shape == (11, 64) and not C0.any() and not np.signbit(C0).any()
+    # no columns: every product is an empty sum; B holds no bytes and the kernels'
+    # look-ahead loads go through a zero-length buffer range
+    nocols = spmm.plan_create(5, 0, np.zeros(6, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
+    for ncol in (8, 7):
+        out0 = nocols.execute(torch_gpu.empty((0, ncol), dtype=torch_gpu.float32, device="cuda"),
+                              torch_gpu.full((5, ncol), 3.0, dtype=torch_gpu.float32, device="cuda"))
+        torch_gpu.cuda.synchronize()
+        assert tuple(out0.shape) == (5, ncol) and not out0.cpu().numpy().any()
     # no rows at all: nothing to launch, nothing written
     none = spmm.plan_create(0, n, np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
     dB = torch_gpu.from_numpy(B).cuda()
