@@ -90,7 +90,13 @@ spmm_status_t spmm_plan_create(spmm_plan_t **plan, int64_t M, int64_t K,
                                const int32_t *row_ptr, const int32_t *col_idx,
                                const float *vals);
 
-/* Same, with explicit settings (opts may be NULL). */
+/*
+ * Same, with explicit settings (opts may be NULL).  For experiments the
+ * environment variables SPMM_UFI, SPMM_GROUP_NNZ and SPMM_GROUP_PANELS set the
+ * corresponding field wherever the caller left it 0 (this is how bench.py forces
+ * a panel height for counter runs), and SPMM_FORCE_WIDE=1 makes spmm_execute use
+ * the 64-bit addressing kernels on inputs that do not need them.
+ */
 spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
                                   const int32_t *row_ptr, const int32_t *col_idx,
                                   const float *vals, const spmm_options_t *opts);
@@ -137,18 +143,24 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
 spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_t cap);
 
 /*
- * Raw copies of the plan's schedule-ordered arrays (host mirror), for format
- * round-trip tests and byte accounting.  Layouts are those the kernels read:
- *   SPMM_ARRAY_HDR     one word per chunk, launch order (host-side copy): bits 0-3
- *                      pattern (panel rows present in every column of the chunk),
- *                      bits 4-7 number of real columns, bit 8 last chunk of its panel
+ * Raw copies of the plan's schedule-ordered arrays, for format round-trip tests
+ * and byte accounting.  Only a host-only plan keeps them (a plan on a device
+ * holds them in device memory and drops the host mirror): on any other plan the
+ * call returns SPMM_ERR_INVALID_ARG.  Layouts are those the kernels read:
+ *   SPMM_ARRAY_HDR     one word per chunk, launch order (host-side copy): bits 0-7
+ *                      pattern (panel rows that own a value in some column of the
+ *                      chunk), bits 8-11 number of real columns, bit 12 last chunk
+ *                      of its panel
  *   SPMM_ARRAY_WINS    one word per LDS staging window of a group: bits 0-15 chunks,
  *                      bits 16-31 words (at most 1024)
  *   SPMM_ARRAY_STREAM  the windows back to back, each as: the headers of its chunks
- *                      (zero-padded to a multiple of 8 words); ufk column indices per
- *                      chunk (unused slots repeat a real column); per chunk one block
- *                      of ufk float bit patterns per set pattern row in ascending row
- *                      order (zeros in unused slots)
+ *                      (zero-padded to a multiple of 8 words); ufk column words per
+ *                      chunk (bits 0-23 the column index, unused slots repeat a real
+ *                      column; bits 24-31 the slot's own pattern where leftovers of
+ *                      several patterns share a chunk and the slot's pattern is
+ *                      smaller than the chunk's, else 0); per chunk one block of ufk
+ *                      float bit patterns per set pattern row in ascending row order
+ *                      (zeros in unused slots and where a slot lacks the row)
  *   SPMM_ARRAY_ITEMS   16 words per wave slot, 8 slots per workgroup, launch order:
  *                      first row, rows, first chunk, chunks, first record word, flags
  *                      (1 piece of a split panel, 2 idle slot, 4 workgroup with split

@@ -128,6 +128,7 @@ class Plan:
         return out
 
     def get_array(self, which):
+        """spmm_plan_get_array: one of the plan's arrays (ARRAY_*) as uint32; host-only plans only."""
         n = ctypes.c_int64(0)
         _check(load().spmm_plan_get_array(self._h, which, None, 0, ctypes.byref(n)),
                "spmm_plan_get_array")

@@ -7,6 +7,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "spmm_format.h"
 #include "spmm_kernels.h"
@@ -20,6 +21,7 @@ struct spmm_plan {
     int device = -1;
     uint32_t *d_stream = nullptr, *d_wins = nullptr, *d_items = nullptr;
     int64_t device_bytes = 0;
+    int64_t stream_words = 0;  // length of host.stream at creation (a device plan drops its host mirror)
     bool force_wide = false;  // test hook: exercise the 64-bit addressing kernels on small inputs
 };
 
@@ -117,6 +119,14 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
         }
         p->on_device = true;
     }
+    p->stream_words = (int64_t)p->host.stream.size();
+    if (p->on_device) {
+        // the arrays live on the device now: keep the descriptors (row groups, sizes), not the mirror
+        std::vector<uint32_t>().swap(p->host.stream);
+        std::vector<uint32_t>().swap(p->host.hdr);
+        std::vector<uint32_t>().swap(p->host.wins);
+        std::vector<uint32_t>().swap(p->host.items);
+    }
     *plan = p;
     return SPMM_OK;
 }
@@ -199,7 +209,7 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
     out->n_split = h.n_split;
     out->n_enum = h.n_enum;
     out->n_chunks = h.n_chunks;
-    out->stream_words = (int64_t)h.stream.size();
+    out->stream_words = plan->stream_words;
     out->device_bytes = plan->device_bytes;
     return SPMM_OK;
 }
@@ -218,6 +228,7 @@ spmm_status_t spmm_plan_get_array(const spmm_plan_t *plan, int32_t which, uint32
                                   int64_t *n_words)
 {
     if (!plan) return SPMM_ERR_INVALID_ARG;
+    if (plan->on_device) return SPMM_ERR_INVALID_ARG;  // only host-only plans keep the mirror
     const HostPlan &h = plan->host;
     const std::vector<uint32_t> *v = nullptr;
     switch (which) {

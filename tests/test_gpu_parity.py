@@ -221,7 +221,13 @@ def test_execute_rejects_bad_arguments(torch_gpu):
     assert lib.spmm_execute(plan.handle, None, 32, dC.data_ptr(), None) == spmm.SPMM_ERR_INVALID_ARG
     assert lib.spmm_execute(plan.handle, dB.data_ptr(), 32, None, None) == spmm.SPMM_ERR_INVALID_ARG
     assert lib.spmm_execute(plan.handle, dB.data_ptr() + 2, 32, dC.data_ptr(), None) == spmm.SPMM_ERR_INVALID_ARG
-    assert plan.describe()["device_bytes"] > 0
+    info = plan.describe()
+    assert info["device_bytes"] > 0 and info["stream_words"] * 4 <= info["device_bytes"]
+    # a plan on the device keeps its row groups but not the host mirror of its arrays
+    assert len(plan.get_groups()) == info["n_groups"]
+    with pytest.raises(spmm.SpmmError) as err:
+        plan.get_array(spmm.ARRAY_STREAM)
+    assert err.value.status == spmm.SPMM_ERR_INVALID_ARG
 
 
 def test_stress_config_sampled_rows_at_full_size(torch_gpu, oracle):
