@@ -65,18 +65,22 @@ def heavy_tail(M, K, seed):
     return gen.csr_from_dense(W)
 
 
-def test_tiny_config(torch_gpu, oracle):
+# The configurations of the benchmark run as bench.py runs them: one plan per column
+# count, created with that count as hint (hinted), and also with the hint left out.
+@pytest.mark.parametrize("hinted", [True, False])
+def test_tiny_config(torch_gpu, oracle, hinted):
     csr = gen.tiny()
     B = gen.activations_for(csr, 32)
-    C, _ = gpu_product(torch_gpu, csr, B, guard_rows=8)
+    C, _ = gpu_product(torch_gpu, csr, B, guard_rows=8, n_hint=32 if hinted else 0)
     check(oracle, csr, B, C)
 
 
+@pytest.mark.parametrize("hinted", [True, False])
 @pytest.mark.parametrize("N", [32, 64, 128])
-def test_conv_config(torch_gpu, oracle, N):
+def test_conv_config(torch_gpu, oracle, N, hinted):
     csr = gen.conv_layer()
     B = gen.activations_for(csr, N)
-    C, plan = gpu_product(torch_gpu, csr, B, guard_rows=4)
+    C, plan = gpu_product(torch_gpu, csr, B, guard_rows=4, n_hint=N if hinted else 0)
     check(oracle, csr, B, C)
     assert plan.describe()["n_split"] > 0  # 410 nonzeros per row: every panel is split
     assert plan.describe()["ufi"] < 4      # 512 rows: shorter panels give the chip enough workgroups
@@ -87,8 +91,9 @@ def test_conv_config(torch_gpu, oracle, N):
 def test_ffn_config(torch_gpu, oracle, shape_index, sparsity_index, N):
     csr = gen.ffn(shape_index, sparsity_index)
     B = gen.activations_for(csr, N)
-    C, _ = gpu_product(torch_gpu, csr, B)
-    check(oracle, csr, B, C)
+    for hint in (N, 0):
+        C, _ = gpu_product(torch_gpu, csr, B, n_hint=hint)
+        check(oracle, csr, B, C)
 
 
 @pytest.mark.parametrize("N", [1, 2, 4, 8, 12, 16, 20, 31, 33, 63, 65, 96, 127, 130, 144, 200, 256, 257])
@@ -230,13 +235,26 @@ def test_execute_rejects_bad_arguments(torch_gpu):
     assert err.value.status == spmm.SPMM_ERR_INVALID_ARG
 
 
+def check_sampled_rows(oracle, csr, B, C, rows):
+    """Oracle parity on the given rows of a product too large to check whole."""
+    lens = np.diff(csr.row_ptr)
+    rows = np.array(sorted(set(int(r) for r in rows)))
+    sub_ptr = np.zeros(len(rows) + 1, dtype=np.int32)
+    np.cumsum(lens[rows], out=sub_ptr[1:])
+    idx = np.concatenate([np.arange(csr.row_ptr[r], csr.row_ptr[r + 1]) for r in rows])
+    sub = gen.Csr(len(rows), csr.K, sub_ptr, csr.col_idx[idx], csr.vals[idx])
+    C_ref, S = oracle.spmm(sub.row_ptr, sub.col_idx, sub.vals, B)
+    err, bad_zero = oracle.parity_error(C[rows], C_ref, S)
+    assert bad_zero == 0 and err <= TOL, "max relative error %.3e" % err
+
+
 def test_stress_config_sampled_rows_at_full_size(torch_gpu, oracle):
     """Full 16384 x 16384 Zipf matrix at N = 128 in the launch configuration the
     benchmark times; the oracle checks a sample of rows one by one (all rows of
     256 sampled panels plus every dense and every empty row among them)."""
     csr = gen.stress()
     B = gen.activations_for(csr, 128)
-    C, plan = gpu_product(torch_gpu, csr, B)
+    C, plan = gpu_product(torch_gpu, csr, B, n_hint=128)
     assert np.isfinite(C).all()
     rng = np.random.default_rng(123)
     lens = np.diff(csr.row_ptr)
@@ -245,14 +263,24 @@ def test_stress_config_sampled_rows_at_full_size(torch_gpu, oracle):
         sample.update(range(4 * p, 4 * p + 4))
     sample.update(np.flatnonzero(lens == lens.max())[:16].tolist())
     sample.update(np.flatnonzero(lens == 0)[:64].tolist())
-    rows = np.array(sorted(sample))
-    counts = lens[rows]
-    sub_ptr = np.zeros(len(rows) + 1, dtype=np.int32)
-    np.cumsum(counts, out=sub_ptr[1:])
-    idx = np.concatenate([np.arange(csr.row_ptr[r], csr.row_ptr[r + 1]) for r in rows])
-    sub = gen.Csr(len(rows), csr.K, sub_ptr, csr.col_idx[idx], csr.vals[idx])
-    C_ref, S = oracle.spmm(sub.row_ptr, sub.col_idx, sub.vals, B)
-    err, bad_zero = oracle.parity_error(C[rows], C_ref, S)
-    assert bad_zero == 0 and err <= TOL, "max relative error %.3e" % err
+    check_sampled_rows(oracle, csr, B, C, sample)
     # every empty row of the full matrix is exactly zero
     assert not C[lens == 0].any()
+
+
+@pytest.mark.parametrize("N,want_ufi", [(128, 8), (64, 8), (32, 4)])
+def test_largest_sweep_entry_sampled_rows_at_full_size(torch_gpu, oracle, N, want_ufi):
+    """The largest matrix of the sweep (8192 x 8192, half of the entries kept) in the
+    launch configuration the benchmark times: eight-row panels for 64 and 128 columns,
+    four-row panels for 32; the oracle checks 64 sampled panels of eight rows."""
+    entry = [e for e in gen.sweep_entries() if e["M"] == 8192 and e["sparsity"] == 0.5][0]
+    csr = gen.sweep_matrix(entry)
+    B = gen.activations_for(csr, N)
+    C, plan = gpu_product(torch_gpu, csr, B, n_hint=N)
+    assert plan.describe()["ufi"] == want_ufi and np.isfinite(C).all()
+    rng = np.random.default_rng(321 + N)
+    sample = set()
+    for p in rng.choice(csr.M // 8, size=64, replace=False):
+        sample.update(range(8 * p, 8 * p + 8))
+    sample.update((0, csr.M - 1))
+    check_sampled_rows(oracle, csr, B, C, sample)
