@@ -170,7 +170,7 @@ def kernel_shape(N, ufi):
     """Template arguments of the instance spmm_execute launches for a tile of N columns
     (N a multiple of 4, at most 128) of a plan with panels of `ufi` rows: slices per
     wave, floats per lane, pipeline depth (the table of spmm_launch_chunks)."""
-    depth = {8: (2, 4, 8), 4: (3, 3, 4), 2: (3, 4, 6), 1: (3, 4, 8)}[ufi]
+    depth = {8: (2, 4, 4), 4: (3, 3, 4), 2: (3, 4, 6), 1: (3, 4, 8)}[ufi]
     if N > 64:
         return "S=2,VW=4,D=%d" % depth[0]
     if N > 32:

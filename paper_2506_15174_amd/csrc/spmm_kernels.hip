@@ -199,8 +199,9 @@ __device__ __forceinline__ uint32_t value_block(uint32_t at, uint32_t pattern, i
 // keep few B rows in flight per wave and walk a long dependent chain per chunk
 // (header, row branches, LDS reads), so they need more resident waves to cover
 // it: 8 (64 VGPRs) with eight slices, 6 (80 VGPRs) with four, 4 (128 VGPRs)
-// otherwise.
-constexpr int waves_per_simd(int S, int UFI) { return UFI > 4 ? 4 : S >= 8 ? 8 : S >= 4 ? 6 : 4; }
+// with two.  The eight-row tile alone is 32 registers: 6 waves with eight slices,
+// else 4.
+constexpr int waves_per_simd(int S, int UFI) { return UFI > 4 ? (S >= 8 ? 6 : 4) : S >= 8 ? 8 : S >= 4 ? 6 : 4; }
 
 template <int UFI, int S, int VW, int D, bool WIDE>
 __global__ __launch_bounds__(64 * WAVES_PER_WG, (waves_per_simd(S, UFI))) void
@@ -426,7 +427,7 @@ int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int slices, bool wide
 {
     if (a.n_blocks <= 0) return 0;
     switch (ufi) {
-    case 8: SPMM_LAUNCH_SLICES(8, 2, 4, 8) break;
+    case 8: SPMM_LAUNCH_SLICES(8, 2, 4, 4) break;
     case 4: SPMM_LAUNCH_SLICES(4, 3, 3, 4) break;
     case 2: SPMM_LAUNCH_SLICES(2, 3, 4, 6) break;
     case 1: SPMM_LAUNCH_SLICES(1, 3, 4, 8) break;
