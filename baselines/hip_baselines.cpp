@@ -12,8 +12,9 @@
 
 namespace {
 
-// median over `samples` of (time of `inner` back-to-back calls) / inner, in ms
-template <typename F> float time_ms(F &&call, int samples, int inner)
+// median over `samples` of (time of `inner` back-to-back calls) / inner, in ms;
+// *mean_out (may be null) receives the mean over the samples
+template <typename F> float time_ms(F &&call, int samples, int inner, float *mean_out = nullptr)
 {
     hipEvent_t a, b;
     if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -1.f;
@@ -32,6 +33,11 @@ template <typename F> float time_ms(F &&call, int samples, int inner)
     (void)hipEventDestroy(a);
     (void)hipEventDestroy(b);
     std::sort(t.begin(), t.end());
+    if (mean_out) {
+        double sum = 0;
+        for (float x : t) sum += x;
+        *mean_out = (float)(sum / (double)t.size());
+    }
     return t[t.size() / 2];
 }
 
@@ -104,6 +110,22 @@ int baseline_rocblas_sgemm(int M, int K, int N, const float *A, const float *B, 
     };
     *ms_out = time_ms(call, samples, inner);
     (void)rocblas_destroy_handle(h);
+    return ok ? 0 : 2;
+}
+
+// The library under test timed the same way as the two comparison systems: `fn` is
+// its spmm_execute (signature of include/spmm.h, status 0 = ok), called on the default
+// stream from this C loop so that no interpreter sits between two launches.
+// ms_out: HOST, 2 floats (median, mean).
+typedef int (*spmm_execute_fn)(const void *plan, const float *B, int N, float *C, void *stream);
+int baseline_time_spmm_execute(spmm_execute_fn fn, const void *plan, const float *B, int N, float *C,
+                               int samples, int inner, float *ms_out)
+{
+    bool ok = true;
+    auto call = [&]() {
+        if (fn(plan, B, N, C, nullptr) != 0) ok = false;
+    };
+    ms_out[0] = time_ms(call, samples, inner, &ms_out[1]);
     return ok ? 0 : 2;
 }
 

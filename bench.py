@@ -64,24 +64,12 @@ def build_workload(name, args=None):
     raise SystemExit("unknown workload %r" % name)
 
 
-def time_kernel_events(torch, fn, reps, batch=20):
-    """Average and median duration (ms) of one fn() launch: `reps` samples, each
-    `batch` back-to-back launches between two HIP events recorded on the current
-    stream (the stream spmm_execute launches on).  Microsecond kernels cannot be
-    timed one launch per event pair: the pair itself costs several microseconds."""
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
-    ends = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
-    for i in range(reps):
-        starts[i].record()
-        for _ in range(batch):
-            fn()
-        ends[i].record()
-    torch.cuda.synchronize()
-    ts = sorted(s.elapsed_time(e) / batch for s, e in zip(starts, ends))
-    return sum(ts) / len(ts), ts[len(ts) // 2]
-
-
 _BASE = None
+# Every per-launch figure (this library, hipSPARSE, rocBLAS) is the median over SAMPLES
+# HIP-event intervals of INNER back-to-back calls issued from one C loop on the default
+# stream (baselines/hip_baselines.cpp): at 4-7 us per kernel an interpreter between two
+# launches (3.4 us per ctypes call) would pace them.
+SAMPLES, INNER = 10, 20
 
 
 def _baseline_lib():
@@ -98,6 +86,7 @@ def _baseline_lib():
         vp, ci = ctypes.c_void_p, ctypes.c_int
         lib.baseline_hipsparse_spmm.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, vp, ci, ci, vp]
         lib.baseline_rocblas_sgemm.argtypes = [ci, ci, ci, vp, vp, vp, ci, ci, vp]
+        lib.baseline_time_spmm_execute.argtypes = [vp, vp, vp, ci, vp, ci, ci, vp]
         _BASE = lib
     return _BASE
 
@@ -127,7 +116,7 @@ def measure_baselines(torch, np, csr, cols, Bs, dense_limit=1 << 28):
             entry = {}
             if nnz > 0:
                 rc = lib.baseline_hipsparse_spmm(csr.M, csr.K, N, nnz, d_rp.data_ptr(), d_ci.data_ptr(),
-                                                 d_v.data_ptr(), Bs[N].data_ptr(), C.data_ptr(), 7, 5, ms)
+                                                 d_v.data_ptr(), Bs[N].data_ptr(), C.data_ptr(), SAMPLES, INNER, ms)
                 good = [m for m in ms if m > 0]
                 if rc == 0 and good:
                     best = min(good)
@@ -137,7 +126,7 @@ def measure_baselines(torch, np, csr, cols, Bs, dense_limit=1 << 28):
             if A_dn is not None:
                 one = ctypes.c_float(-1)
                 rc = lib.baseline_rocblas_sgemm(csr.M, csr.K, N, A_dn.data_ptr(), Bs[N].data_ptr(), C.data_ptr(),
-                                                7, 5, ctypes.byref(one))
+                                                SAMPLES, INNER, ctypes.byref(one))
                 if rc == 0 and one.value > 0:
                     entry["rocblas_sgemm_us"] = round(one.value * 1e3, 3)
                     entry["rocblas_effective_gflops"] = round(2.0 * nnz * N / (one.value * 1e-3) / 1e9, 1)
@@ -202,13 +191,7 @@ def run_sweep(args, cols=(32, 64, 128), narrow=False):
         base = measure_baselines(torch, np, csr, cols, Bs)
         for N in cols:
             plan, info = plans[N], plans[N].describe()
-            pb, pc = Bs[N].data_ptr(), Cs[N].data_ptr()
-            st = torch.cuda.current_stream().cuda_stream or None
-            fn = lambda: plan.execute_raw(pb, N, pc, st)
-            for _ in range(10):
-                fn()
-            torch.cuda.synchronize()
-            _, med = time_kernel_events(torch, fn, 10, batch=20)
+            _, med = time_execute(torch, plan, Bs[N], Cs[N], N)
             b = base.get(str(N), {})
             rows_out.append({"index": entry["index"], "M": csr.M, "K": csr.K, "sparsity": entry["sparsity"],
                              "nnz": nnz, "N": N, "ufi": info["ufi"], "group_nnz": info["group_nnz"],
@@ -241,14 +224,25 @@ def run_sweep(args, cols=(32, 64, 128), narrow=False):
     print(json.dumps(out))
 
 
-def _time_plan(torch, plan, B, C, N, reps=10, batch=20):
-    pb, pc = B.data_ptr(), C.data_ptr()
-    st = torch.cuda.current_stream().cuda_stream or None
-    fn = lambda: plan.execute_raw(pb, N, pc, st)
-    for _ in range(10):
-        fn()
+def time_execute(torch, plan, B, C, N, samples=SAMPLES, inner=INNER):
+    """(mean, median) duration in ms of one spmm_execute launch on the default stream,
+    timed by the C loop of the shim with HIP events around `inner` back-to-back calls."""
+    import ctypes
+    import paper_2506_15174_amd as spmm
+    assert (torch.cuda.current_stream().cuda_stream or 0) == 0, "the C timing loop launches on the default stream"
+    lib = _baseline_lib()
+    fn = ctypes.cast(spmm.load().spmm_execute, ctypes.c_void_p)
+    ms = (ctypes.c_float * 2)(-1, -1)
     torch.cuda.synchronize()
-    return time_kernel_events(torch, fn, reps, batch=batch)[1] * 1e3   # median, us
+    rc = lib.baseline_time_spmm_execute(fn, plan.handle, B.data_ptr() or None, N, C.data_ptr() or None,
+                                        samples, inner, ms)
+    if rc != 0 or ms[0] <= 0:
+        raise RuntimeError("timing loop failed (status %d)" % rc)
+    return ms[1], ms[0]
+
+
+def _time_plan(torch, plan, B, C, N, reps=SAMPLES, batch=INNER):
+    return time_execute(torch, plan, B, C, N, reps, batch)[1] * 1e3   # median, us
 
 
 def _geomean(xs):
@@ -409,9 +403,18 @@ def main():
     Bs = {N: torch.from_numpy(gen.activations_for(csr, N)).cuda() for N in cols}
     Cs = {N: torch.empty((csr.M, N), dtype=torch.float32, device="cuda") for N in cols}
 
+    # spmm_execute through the binding's raw entry (device addresses marshalled once:
+    # at these kernel lengths the tensor checks of Plan.execute would pace the launches)
+    st = torch.cuda.current_stream().cuda_stream or None
+    calls = {N: (plans[N], Bs[N].data_ptr(), N, Cs[N].data_ptr()) for N in cols}
+
+    def run(N):
+        plan, pb, n, pc = calls[N]
+        plan.execute_raw(pb, n, pc, st)
+
     def step():
         for N in cols:
-            plans[N].execute(Bs[N], Cs[N])
+            run(N)
 
     for _ in range(args.warmup):
         step()
@@ -427,7 +430,7 @@ def main():
 
     # dominant kernel: the widest column count; one launch per execute there
     Nd = max(cols)
-    avg_ms, med_ms = time_kernel_events(torch, lambda: plans[Nd].execute(Bs[Nd], Cs[Nd]), 20)
+    avg_ms, med_ms = time_execute(torch, plans[Nd], Bs[Nd], Cs[Nd], Nd, samples=20)
     bmin = bytes_min(csr.M, csr.K, nnz, Nd)
     achieved = bmin / (avg_ms * 1e-3) / 1e9
     kernel_tflops = 2.0 * nnz * Nd / (avg_ms * 1e-3) / 1e12
@@ -440,7 +443,7 @@ def main():
 
     per_cols = {}
     for N in cols:
-        a, m = time_kernel_events(torch, lambda N=N: plans[N].execute(Bs[N], Cs[N]), 20)
+        a, m = time_execute(torch, plans[N], Bs[N], Cs[N], N, samples=20)
         per_cols[str(N)] = {"us": round(m * 1e3, 3), "gflops": round(2.0 * nnz * N / (m * 1e-3) / 1e9, 1),
                             "hbm_model_gbs": round(bytes_min(csr.M, csr.K, nnz, N) / (m * 1e-3) / 1e9, 1)}
 
