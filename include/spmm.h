@@ -111,6 +111,8 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
  *           overwritten (rows of A without nonzeros become +0.0); must not alias B
  *   stream  hipStream_t passed as void* (NULL = the default stream)
  *
+ * The device that was current at plan creation must be current again (else
+ * SPMM_ERR_INVALID_ARG), and `stream`, B and C must belong to it.
  * Asynchronous: kernels are enqueued on `stream` and the call returns.  It
  * allocates nothing and does not synchronise.  The plan is read-only during
  * execution (pieces of a split panel meet in on-chip memory, not in the plan),

@@ -146,6 +146,10 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
     if (!C) return SPMM_ERR_INVALID_ARG;
     if (h.K > 0 && !B) return SPMM_ERR_INVALID_ARG;
     if (((uintptr_t)B & 3u) || ((uintptr_t)C & 3u)) return SPMM_ERR_INVALID_ARG;
+    // the plan's arrays live on the device that was current when it was created
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return hip_fail();
+    if (dev != plan->device) return SPMM_ERR_INVALID_ARG;
 
     const uint64_t b_total = (uint64_t)h.K * (uint64_t)N * 4u;
     // Narrow addressing: 32-bit byte offsets into B formed by a 24 x 24-bit multiply.
