@@ -63,6 +63,9 @@ constexpr uint32_t COL_INDEX_MASK = (1u << COL_PATTERN_SHIFT) - 1u;
 
 // Words of LDS one wave owns (its window; later its partial tile).
 constexpr int WIN_WORDS = 1024;
+// Deepest software pipeline of any kernel instance: column slots of up to this
+// many chunks past a window's last chunk are read (and never used).
+constexpr int LOOKAHEAD = 8;
 
 // Headers (all zero) appended after the last real chunk so that the kernels'
 // look-ahead never leaves the array.

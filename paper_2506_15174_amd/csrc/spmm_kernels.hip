@@ -215,6 +215,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
     constexpr int L = 64 / S;    // lanes per slice
     constexpr int Q = UFK / S;   // column slots per slice and chunk
     static_assert(UFK % S == 0 && VW * L * UFI * 4 <= WIN_WORDS * 4, "tile must fit the wave's window");
+    static_assert(D <= LOOKAHEAD, "the inspector keeps LOOKAHEAD chunks of column slots inside every window");
 
     // Per wave: the staged window of its stream; later the partial tile of a split panel.
     __shared__ __attribute__((aligned(16))) uint32_t lds[WAVES_PER_WG][WIN_WORDS];

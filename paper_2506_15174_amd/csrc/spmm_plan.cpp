@@ -481,8 +481,11 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                 while (c + wc < g.n_chunks) {
                     const uint32_t pattern = em.hdr[(size_t)(g.chunk0 + c + wc)] & HDR_PATTERN_MASK;
                     const int64_t add = (int64_t)UFK * __builtin_popcount(pattern);
-                    const int64_t words = ((wc + 1 + 7) / 8) * 8 + (wc + 1) * UFK + vw + add;
-                    if (words > WIN_WORDS) break;
+                    const int64_t hdr_w = ((wc + 1 + 7) / 8) * 8;
+                    const int64_t words = hdr_w + (wc + 1) * UFK + vw + add;
+                    // the kernels read column slots up to LOOKAHEAD chunks past the last
+                    // one (values never used): those reads must stay inside the window
+                    if (words > WIN_WORDS || hdr_w + (wc + 1 + LOOKAHEAD) * UFK > WIN_WORDS) break;
                     wc += 1;
                     vw += add;
                 }

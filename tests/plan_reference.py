@@ -11,6 +11,7 @@ MAX_UFI = 8
 UFK = 8
 ITEM_WORDS = 16
 WIN_WORDS = 1024
+LOOKAHEAD = 8
 COL_PATTERN_SHIFT = 24
 COL_INDEX_MASK = (1 << COL_PATTERN_SHIFT) - 1
 
@@ -167,6 +168,7 @@ def walk_chunks(it, hdr, stream, wins):
     for w in range(win0, win0 + nwins):
         wc, ww = int(wins[w]) & 0xFFFF, int(wins[w]) >> 16
         assert 1 <= wc and ww <= WIN_WORDS and ww % UFK == 0
+        assert -(-wc // 8) * 8 + (wc + LOOKAHEAD) * UFK <= WIN_WORDS, "look-ahead column reads leave the window"
         hdr_words = -(-wc // 8) * 8
         assert not stream[at + wc:at + hdr_words].any()
         cols_at = at + hdr_words

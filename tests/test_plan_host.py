@@ -342,6 +342,23 @@ def test_chunk_arrays_evaluate_to_the_product(oracle, name, group_nnz, force_ufi
     assert err <= 1e-5 and bad_zero == 0
 
 
+def test_many_empty_panels_in_one_group_keep_windows_short():
+    # 400 empty rows packed into one group: 400 chunks without values; a window may
+    # hold only as many as leave the kernels' look-ahead column reads inside it
+    M = 400
+    plan = spmm.plan_create(M, 16, np.zeros(M + 1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32),
+                            host_only=True, ufi=1, group_panels=1000)
+    info = plan.describe()
+    assert info["n_groups"] == 1 and info["n_chunks"] == M
+    items, hdr, stream, wins = arrays(plan)
+    rows, _, _ = decode_plan(items, hdr, stream, wins, 1)      # walks and checks every window
+    assert len(rows) == 0
+    counts = [int(w) & 0xFFFF for w in wins[:-1]]
+    assert sum(counts) == M and len(counts) >= 4
+    # without the bound a window of 1024 words would take 113 such chunks (9 words each)
+    assert all(-(-wc // 8) * 8 + (wc + 8) * 8 <= 1024 for wc in counts) and max(counts) == 106
+
+
 def test_plan_bytes_against_csr_bytes_trend():
     # Paper Section 4.4: the transformed format is smaller than CSR at moderate
     # sparsity (one index per merged column instead of one per nonzero) and larger
