@@ -17,5 +17,18 @@ def build():
     return LIB
 
 
+MICROBENCH = os.path.join(HERE, "microbench_paths")
+
+
+def build_microbench():
+    """Compile the memory-path microbenchmark (a gfx950 executable; run it on the GPU machine)."""
+    cmd = [os.path.join(ROCM, "bin", "hipcc"), "--offload-arch=gfx950", "-O3",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           os.path.join(HERE, "microbench_paths.hip"), "-o", MICROBENCH]
+    subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+    return MICROBENCH
+
+
 if __name__ == "__main__":
     print(build())
+    print(build_microbench())
