@@ -381,8 +381,9 @@ def main():
     if args.gpus == 1 and args.workload in ("sweep", "ablation", "tune"):
         return {"sweep": run_sweep, "ablation": run_ablation, "tune": run_tune}[args.workload](args)
     if args.gpus != 1:
-        raise SystemExit("this build runs on one GPU only: the path shards by rows of A "
-                         "(see DESIGN.md) but no multi-GPU run exists; use --gpus 1")
+        raise SystemExit("this build runs on one GPU only: the path would shard by rows of A (each GPU "
+                         "plans and multiplies its own row range, B replicated), but no multi-GPU run "
+                         "exists; use --gpus 1")
 
     import numpy as np
     import torch
