@@ -284,3 +284,37 @@ def test_largest_sweep_entry_sampled_rows_at_full_size(torch_gpu, oracle, N, wan
         sample.update(range(8 * p, 8 * p + 8))
     sample.update((0, csr.M - 1))
     check_sampled_rows(oracle, csr, B, C, sample)
+
+
+def test_execute_can_be_captured_in_a_graph_and_replayed(torch_gpu, oracle):
+    """spmm_execute allocates nothing, clears nothing and never synchronises, so it can
+    sit in a captured graph: every replay (with eager work in between) reproduces the
+    eager result bit for bit, also for split panels and for a second set of B values."""
+    torch = torch_gpu
+    csr = heavy_tail(64, 2000, 95)
+    N = 128
+    plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, group_nnz=64)
+    assert plan.describe()["n_split"] > 0
+    B = torch.from_numpy(gen.dense_activations(csr.K, N, 96)).cuda()
+    C = torch.full((csr.M, N), float("nan"), dtype=torch.float32, device="cuda")
+    eager = plan.execute(B).clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        plan.execute(B, C)            # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.execute(B, C)
+    for replay in range(4):
+        C.fill_(float("nan"))
+        if replay == 2:               # new inputs in the captured buffers
+            B.copy_(torch.from_numpy(gen.dense_activations(csr.K, N, 97)).cuda())
+            eager = plan.execute(B).clone()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(C, eager), "replay %d differs from the eager result" % replay
+        plan.execute(B)               # eager work between replays
+        torch.cuda.synchronize()
+    check(oracle, csr, B.cpu().numpy(), C.cpu().numpy())
