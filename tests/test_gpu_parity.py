@@ -318,3 +318,32 @@ def test_execute_can_be_captured_in_a_graph_and_replayed(torch_gpu, oracle):
         plan.execute(B)               # eager work between replays
         torch.cuda.synchronize()
     check(oracle, csr, B.cpu().numpy(), C.cpu().numpy())
+
+
+def test_b_beyond_four_gib_is_addressed_with_64_bits(torch_gpu, oracle):
+    """K * N * 4 just above 2^32: the executor must take the 64-bit addressing kernels by
+    itself.  A has 16 rows whose columns include the last row of B and rows on both sides of
+    the 4 GiB boundary; the oracle works on the rows of B that A touches."""
+    torch = torch_gpu
+    N = 128
+    K = (1 << 23) + 4096                      # K * 512 bytes = 4 GiB + 2 MiB
+    M = 16
+    rng = np.random.default_rng(2024)
+    rows = []
+    for i in range(M):
+        c = set(rng.integers(0, K, size=60).tolist())
+        c.update((K - 1 - i, (1 << 23) - 1 - i, (1 << 23) + i))
+        rows.append(np.array(sorted(c), dtype=np.int32))
+    row_ptr = np.concatenate(([0], np.cumsum([len(r) for r in rows]))).astype(np.int32)
+    col_idx = np.concatenate(rows)
+    vals = rng.standard_normal(len(col_idx)).astype(np.float32)
+    dB = torch.empty((K, N), dtype=torch.float32, device="cuda")
+    dB.normal_()
+    plan = spmm.plan_create(M, K, row_ptr, col_idx, vals)
+    dC = plan.execute(dB)
+    torch.cuda.synchronize()
+    uniq, inverse = np.unique(col_idx, return_inverse=True)
+    B_small = dB[torch.from_numpy(uniq.astype(np.int64)).cuda()].cpu().numpy()
+    small = gen.Csr(M, len(uniq), row_ptr, inverse.astype(np.int32), vals)
+    check(oracle, small, B_small, dC.cpu().numpy())
+    del dB
