@@ -347,3 +347,20 @@ def test_b_beyond_four_gib_is_addressed_with_64_bits(torch_gpu, oracle):
     small = gen.Csr(M, len(uniq), row_ptr, inverse.astype(np.int32), vals)
     check(oracle, small, B_small, dC.cpu().numpy())
     del dB
+
+
+def test_many_short_rows_share_waves(torch_gpu, oracle):
+    """200 000 rows of 0-8 entries: the inspector packs 16 single-row panels per wave
+    (one group closes by the panel cap, not by the budget); whole product against the oracle."""
+    rng = np.random.default_rng(77)
+    M, K, N = 200_000, 512, 32
+    lens = rng.integers(0, 9, size=M)
+    row_ptr = np.concatenate(([0], np.cumsum(lens))).astype(np.int32)
+    col_idx = np.concatenate([np.sort(rng.choice(K, size=n, replace=False)) for n in lens]).astype(np.int32)
+    vals = rng.standard_normal(int(row_ptr[-1])).astype(np.float32)
+    csr = gen.Csr(M, K, row_ptr, col_idx, vals)
+    B = gen.dense_activations(K, N, 78)
+    C, plan = gpu_product(torch_gpu, csr, B, guard_rows=2, n_hint=N)
+    info = plan.describe()
+    assert info["ufi"] == 1 and info["group_panels"] == 16 and info["n_groups"] < M // 8
+    check(oracle, csr, B, C)
