@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path: fp32 CSR SpMM C = A x B on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conv|stress|ffn|matrix|sweep|narrow|ablation|tune]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conv|stress|ffn|ffn-all|matrix|sweep|narrow|ablation|tune]
 
 A step is one pass of the whole hot path (spmm_execute, every kernel it
 launches) over the workload's column counts, with the plan and all operands
@@ -20,7 +20,8 @@ Prints ONE JSON line:
                 inside a small C shim (baselines/)
 
 Other workloads print one JSON line of their own: `sweep` (48 matrices x 3 column
-counts against the two libraries), `narrow` (the same for 4 / 8 / 16 columns), `ablation` (the method's ingredients switched
+counts against the two libraries), `narrow` (the same for 4 / 8 / 16 columns), `ffn-all` (the same for the eight
+feed-forward matrices), `ablation` (the method's ingredients switched
 on one by one, the ladder of the paper's Figure 7) and `tune` (every panel height
 and three group budgets forced per matrix: what the closed schedule rule loses
 against the best candidate, and the plan's size against CSR and dense).
@@ -167,12 +168,14 @@ def kernel_shape(N, ufi):
     return "S=8,VW=4,D=%d" % depth[2]
 
 
-def run_sweep(args, cols=(32, 64, 128), narrow=False):
+def run_sweep(args, cols=(32, 64, 128), narrow=False, ffn=False):
     """Configuration 4: 48 magnitude-pruned matrices x bCols 32/64/128 against
     hipSPARSE CSR SpMM and rocBLAS SGEMM; geometric means of the speedups and the
     share of points where this library is faster (the shape of the paper's Table 1).
     narrow: the same on the 30 matrices with M, K >= 1024 for bCols 4/8/16, the
-    widths below the kernel's narrowest tile (the paper's Figure 9 measures bCols 4)."""
+    widths below the kernel's narrowest tile (the paper's Figure 9 measures bCols 4).
+    ffn: the same on the eight feed-forward matrices of configuration 2 (two shapes x four
+    sparsities, lognormal row lengths)."""
     import math
     import numpy as np
     import torch
@@ -181,8 +184,13 @@ def run_sweep(args, cols=(32, 64, 128), narrow=False):
     torch.cuda.set_device(0)
     rows_out = []
     t_start = time.perf_counter()
-    for entry in (_ladder_matrices(gen) if narrow else gen.sweep_entries()):
-        csr = gen.sweep_matrix(entry)
+    if ffn:
+        entries = [dict(index=4 * si + pi, sparsity=gen.FFN_SPARSITIES[pi], ffn=(si, pi))
+                   for si in range(len(gen.FFN_SHAPES)) for pi in range(len(gen.FFN_SPARSITIES))]
+    else:
+        entries = _ladder_matrices(gen) if narrow else gen.sweep_entries()
+    for entry in entries:
+        csr = gen.ffn(*entry["ffn"]) if ffn else gen.sweep_matrix(entry)
         nnz = int(csr.row_ptr[-1])
         # one plan per column count: the schedule constants are chosen per bCols
         plans = {N: spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, n_hint=N) for N in cols}
@@ -217,7 +225,8 @@ def run_sweep(args, cols=(32, 64, 128), narrow=False):
     out = {"metric": "fp32 CSR SpMM GFLOP/s (2*nnz*bCols)", "value": round(total_flops / total_s / 1e9, 2),
            "unit": "GFLOP/s", "n_gpus": 1, "steps": 1, "warmup": 10, "ms_per_step": round(total_s * 1e3, 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": ("narrow B: 30 magnitude-pruned matrices (M, K >= 1024) x bCols 4/8/16" if narrow else
+           "config": {"workload": ("ffn: 8 feed-forward matrices (lognormal rows) x bCols 32/64/128 (configs[2])" if ffn else
+                                   "narrow B: 30 magnitude-pruned matrices (M, K >= 1024) x bCols 4/8/16" if narrow else
                                    "sweep: 48 magnitude-pruned matrices x bCols 32/64/128 (configs[4])"),
                       "wall_s": round(time.perf_counter() - t_start, 1)},
            "summary": summary, "points": rows_out}
@@ -378,6 +387,8 @@ def main():
     args = ap.parse_args()
     if args.gpus == 1 and args.workload == "narrow":
         return run_sweep(args, cols=(4, 8, 16), narrow=True)
+    if args.gpus == 1 and args.workload == "ffn-all":
+        return run_sweep(args, ffn=True)
     if args.gpus == 1 and args.workload in ("sweep", "ablation", "tune"):
         return {"sweep": run_sweep, "ablation": run_ablation, "tune": run_tune}[args.workload](args)
     if args.gpus != 1:
