@@ -106,7 +106,9 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
  *
  *   B       DEVICE  const float[K*N], row-major, leading dimension N, finite values
  *   N       columns of B and C, >= 1 (32, 64 and 128 have tuned kernels; every
- *           other N runs through masked column tiles)
+ *           other N runs through masked column tiles of at most 128 columns, one
+ *           kernel launch per tile; tiles of 64 when 128 columns of B exceed one
+ *           L2 cache and 64 fit)
  *   C       DEVICE  float[M*N], row-major, leading dimension N; every element is
  *           overwritten (rows of A without nonzeros become +0.0); must not alias B
  *   stream  hipStream_t passed as void* (NULL = the default stream)

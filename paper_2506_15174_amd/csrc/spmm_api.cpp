@@ -164,6 +164,10 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
     a.n_blocks = (int32_t)h.n_blocks;
     a.ldn = N;
     a.col_mask = h.K <= ((int64_t)1 << spmm_fmt::COL_PATTERN_SHIFT) ? spmm_fmt::COL_INDEX_MASK : 0xFFFFFFFFu;
+    // A 128-column tile of B that exceeds one L2 (4 MiB) while a 64-column tile fits: two
+    // narrower tiles read the plan twice but keep their rows of B L2-resident (measured on a
+    // 16384-column matrix of 13 M nonzeros: 275 against 295 us).
+    const bool narrow_tiles = (int64_t)h.K * 512 > ((int64_t)4 << 20) && (int64_t)h.K * 256 <= ((int64_t)4 << 20);
     // Column tiles run one after another on the stream.
     int32_t j0 = 0;
     while (j0 < N) {
@@ -171,7 +175,7 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
         int slices;
         int32_t tile;
         if (quads) {
-            slices = left > 64 ? 2 : left > 32 ? 4 : 8;
+            slices = left > 64 ? (narrow_tiles ? 4 : 2) : left > 32 ? 4 : 8;
             tile = 256 / slices;
         } else {
             slices = 1;
