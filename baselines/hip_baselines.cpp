@@ -7,6 +7,7 @@
 #include <rocblas/rocblas.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cstdio>
 #include <vector>
 
@@ -18,8 +19,12 @@ template <typename F> float time_ms(F &&call, int samples, int inner, float *mea
 {
     hipEvent_t a, b;
     if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -1.f;
-    for (int i = 0; i < 3; ++i) call();
-    (void)hipDeviceSynchronize();
+    // warm up for at least 10 ms of queued work: after an idle spell the clocks need that long
+    const auto t0 = std::chrono::steady_clock::now();
+    do {
+        for (int i = 0; i < inner; ++i) call();
+        (void)hipDeviceSynchronize();
+    } while (std::chrono::steady_clock::now() - t0 < std::chrono::milliseconds(10));
     std::vector<float> t;
     for (int s = 0; s < samples; ++s) {
         (void)hipEventRecord(a, nullptr);
@@ -124,6 +129,22 @@ int baseline_time_spmm_execute(spmm_execute_fn fn, const void *plan, const float
     bool ok = true;
     auto call = [&]() {
         if (fn(plan, B, N, C, nullptr) != 0) ok = false;
+    };
+    ms_out[0] = time_ms(call, samples, inner, &ms_out[1]);
+    return ok ? 0 : 2;
+}
+
+// The same loop over `copies` independent (plan, B, C) triples taken in turn, so that a
+// call finds none of its operands in the caches when the triples together exceed them.
+int baseline_time_spmm_execute_rotating(spmm_execute_fn fn, const void *const *plans, const float *const *Bs,
+                                        float *const *Cs, int copies, int N, int samples, int inner, float *ms_out)
+{
+    if (copies < 1) return 1;
+    bool ok = true;
+    int next = 0;
+    auto call = [&]() {
+        if (fn(plans[next], Bs[next], N, Cs[next], nullptr) != 0) ok = false;
+        next = next + 1 == copies ? 0 : next + 1;
     };
     ms_out[0] = time_ms(call, samples, inner, &ms_out[1]);
     return ok ? 0 : 2;

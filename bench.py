@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path: fp32 CSR SpMM C = A x B on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conv|stress|ffn|ffn-all|matrix|sweep|narrow|ablation|tune]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conv|stress|ffn|ffn-all|matrix|sweep|narrow|sparsity|ablation|tune]
 
 A step is one pass of the whole hot path (spmm_execute, every kernel it
 launches) over the workload's column counts, with the plan and all operands
@@ -14,6 +14,10 @@ Prints ONE JSON line:
                 algorithmic bytes 4(M+1) + 8 nnz + 4 K N + 4 M N per launch over
                 the kernel's average duration, measured with HIP events on the
                 launch stream inside the timed region, against 8 TB/s
+                (hot: the same operands every call, the paper's protocol);
+                roofline.gather: wave-wide loads of B rows per second against the
+                measured gather ceiling; per_bcols[N].cold: the same launch with
+                plan, B and C rotated over more copies than the caches hold
   cpu_baseline  the CPU oracle timed on the host cores for the same products
   baselines     hipSPARSE CSR SpMM (fastest of its CSR algorithms) and rocBLAS
                 SGEMM on the densified matrix, same inputs, timed with HIP events
@@ -21,7 +25,8 @@ Prints ONE JSON line:
 
 Other workloads print one JSON line of their own: `sweep` (48 matrices x 3 column
 counts against the two libraries), `narrow` (the same for 4 / 8 / 16 columns), `ffn-all` (the same for the eight
-feed-forward matrices), `ablation` (the method's ingredients switched
+feed-forward matrices), `sparsity` (the same for a 512 x 512 matrix from 50 to 99 % pruned at 64 and 4 columns,
+the sweep of the paper's Figure 9), `ablation` (the method's ingredients switched
 on one by one, the ladder of the paper's Figure 7) and `tune` (every panel height
 and three group budgets forced per matrix: what the closed schedule rule loses
 against the best candidate, and the plan's size against CSR and dense).
@@ -88,6 +93,7 @@ def _baseline_lib():
         lib.baseline_hipsparse_spmm.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, vp, ci, ci, vp]
         lib.baseline_rocblas_sgemm.argtypes = [ci, ci, ci, vp, vp, vp, ci, ci, vp]
         lib.baseline_time_spmm_execute.argtypes = [vp, vp, vp, ci, vp, ci, ci, vp]
+        lib.baseline_time_spmm_execute_rotating.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, vp]
         _BASE = lib
     return _BASE
 
@@ -178,14 +184,19 @@ def kernel_shape(N, ufi, K=0):
     return "S=8,VW=4,D=%d" % depth[2]
 
 
-def run_sweep(args, cols=(32, 64, 128), narrow=False, ffn=False):
+SPARSITY_SWEEP = (0.5, 0.6, 0.7, 0.8, 0.85, 0.9, 0.95, 0.98, 0.99)
+
+
+def run_sweep(args, cols=(32, 64, 128), narrow=False, ffn=False, square512=False):
     """Configuration 4: 48 magnitude-pruned matrices x bCols 32/64/128 against
     hipSPARSE CSR SpMM and rocBLAS SGEMM; geometric means of the speedups and the
     share of points where this library is faster (the shape of the paper's Table 1).
     narrow: the same on the 30 matrices with M, K >= 1024 for bCols 4/8/16, the
     widths below the kernel's narrowest tile (the paper's Figure 9 measures bCols 4).
     ffn: the same on the eight feed-forward matrices of configuration 2 (two shapes x four
-    sparsities, lognormal row lengths)."""
+    sparsities, lognormal row lengths).
+    square512: the same on one 512 x 512 magnitude-pruned matrix per sparsity from 50 to
+    99 % for bCols 64 and 4 (the sweep of the paper's Figure 9)."""
     import math
     import numpy as np
     import torch
@@ -197,10 +208,13 @@ def run_sweep(args, cols=(32, 64, 128), narrow=False, ffn=False):
     if ffn:
         entries = [dict(index=4 * si + pi, sparsity=gen.FFN_SPARSITIES[pi], ffn=(si, pi))
                    for si in range(len(gen.FFN_SHAPES)) for pi in range(len(gen.FFN_SPARSITIES))]
+    elif square512:
+        entries = [dict(index=i, sparsity=sp, seed=9000 + i) for i, sp in enumerate(SPARSITY_SWEEP)]
     else:
         entries = _ladder_matrices(gen) if narrow else gen.sweep_entries()
     for entry in entries:
-        csr = gen.ffn(*entry["ffn"]) if ffn else gen.sweep_matrix(entry)
+        csr = (gen.ffn(*entry["ffn"]) if ffn else
+               gen.magnitude_pruned(512, 512, entry["sparsity"], entry["seed"]) if square512 else gen.sweep_matrix(entry))
         nnz = int(csr.row_ptr[-1])
         # one plan per column count: the schedule constants are chosen per bCols
         plans = {N: spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, n_hint=N) for N in cols}
@@ -236,6 +250,7 @@ def run_sweep(args, cols=(32, 64, 128), narrow=False, ffn=False):
            "unit": "GFLOP/s", "n_gpus": 1, "steps": 1, "warmup": 10, "ms_per_step": round(total_s * 1e3, 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": ("ffn: 8 feed-forward matrices (lognormal rows) x bCols 32/64/128 (configs[2])" if ffn else
+                                   "sparsity sweep: 512 x 512 magnitude-pruned, 50 to 99 % pruned, bCols 64 and 4" if square512 else
                                    "narrow B: 30 magnitude-pruned matrices (M, K >= 1024) x bCols 4/8/16" if narrow else
                                    "sweep: 48 magnitude-pruned matrices x bCols 32/64/128 (configs[4])"),
                       "wall_s": round(time.perf_counter() - t_start, 1)},
@@ -279,6 +294,46 @@ def time_execute(torch, plan, B, C, N, samples=SAMPLES, inner=INNER):
         ts.append(e0.elapsed_time(e1) / inner)
     ts.sort()
     return sum(ts) / len(ts), ts[len(ts) // 2]
+
+
+GATHER_CEILING_GWLS = 32.0      # G wave-wide 16-byte-per-lane loads per second, measured (baselines/microbench_paths.hip)
+COLD_WORKING_SET = 1 << 30      # bytes the rotating copies must exceed (four times the 256 MiB Infinity Cache)
+COLD_MAX_COPIES = 256
+
+
+def time_execute_cold(torch, csr, plan, B, N, samples=SAMPLES, inner=INNER):
+    """Cold-cache duration of one spmm_execute: independent copies of (plan, B, C), at
+    least 1 GiB together or 256 of them, taken in turn by the shim's C loop, so that no
+    call finds its plan, B or C in L2 or in the Infinity Cache.  Returns a dict, or None
+    without the shim."""
+    import ctypes
+    import paper_2506_15174_amd as spmm
+    try:
+        lib = _baseline_lib()
+    except Exception:
+        return None
+    info = plan.describe()
+    one = info["device_bytes"] + 4 * N * (csr.K + csr.M)
+    copies = max(2, min(COLD_MAX_COPIES, -(-COLD_WORKING_SET // max(one, 1))))
+    plans = [plan] + [spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, n_hint=N)
+                      for _ in range(copies - 1)]
+    Bs = [B] + [B.clone() for _ in range(copies - 1)]
+    Cs = [torch.empty((csr.M, N), dtype=torch.float32, device="cuda") for _ in range(copies)]
+    vp = ctypes.c_void_p * copies
+    fn = ctypes.cast(spmm.load().spmm_execute, ctypes.c_void_p)
+    ms = (ctypes.c_float * 2)(-1, -1)
+    torch.cuda.synchronize()
+    # every sample walks all copies at least once
+    inner = max(inner, copies)
+    rc = lib.baseline_time_spmm_execute_rotating(fn, vp(*[p.handle for p in plans]), vp(*[b.data_ptr() for b in Bs]),
+                                                 vp(*[c.data_ptr() for c in Cs]), copies, N, samples, inner, ms)
+    torch.cuda.synchronize()
+    for p in plans[1:]:
+        p.destroy()
+    if rc != 0 or ms[0] <= 0:
+        raise RuntimeError("cold timing loop failed (status %d)" % rc)
+    return {"copies": copies, "working_set_bytes": one * copies, "us": round(ms[0] * 1e3, 3),
+            "mean_us": round(ms[1] * 1e3, 3)}
 
 
 def _time_plan(torch, plan, B, C, N, reps=SAMPLES, batch=INNER):
@@ -413,11 +468,15 @@ def main():
     ap.add_argument("--seed", type=int, default=11, help="--workload matrix: generator seed")
     ap.add_argument("--no-baselines", action="store_true")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-cold", action="store_true",
+                    help="skip the cold-cache timing (copies of plan, B and C beyond the Infinity Cache, in turn)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus == 1 and args.workload == "narrow":
         return run_sweep(args, cols=(4, 8, 16), narrow=True)
+    if args.gpus == 1 and args.workload == "sparsity":
+        return run_sweep(args, cols=(64, 4), square512=True)
     if args.gpus == 1 and args.workload == "ffn-all":
         return run_sweep(args, ffn=True)
     if args.gpus == 1 and args.workload in ("sweep", "ablation", "tune"):
@@ -489,11 +548,28 @@ def main():
                 "launches_per_execute": launches, "algorithmic_bytes": bmin, "kernel_tflops": round(kernel_tflops, 3),
                 "frac_of_fp32_valu_peak": round(kernel_tflops / FP32_VALU_PEAK_TFLOPS, 5)}
 
+    # On-chip gather: each chunk of 8 enumerated columns costs 8 / S wave-wide loads of B
+    # rows (S rows of B per load); the ceiling is the rate the gather microbenchmark
+    # reaches on distinct rows of an L2-resident B.
+    S = {"S=2": 2, "S=4": 4, "S=8": 8}[kernel_shape(Nd, infos[Nd]["ufi"], csr.K)[:3]]
+    wave_loads = infos[Nd]["n_chunks"] * 8 // S
+    roofline["gather"] = {"wave_loads_per_launch": wave_loads,
+                          "g_wave_loads_per_s": round(wave_loads / (avg_ms * 1e-3) / 1e9, 2),
+                          "measured_ceiling": GATHER_CEILING_GWLS,
+                          "frac": round(wave_loads / (avg_ms * 1e-3) / 1e9 / GATHER_CEILING_GWLS, 4)}
+
     per_cols = {}
     for N in cols:
         a, m = time_execute(torch, plans[N], Bs[N], Cs[N], N, samples=20)
         per_cols[str(N)] = {"us": round(m * 1e3, 3), "gflops": round(2.0 * nnz * N / (m * 1e-3) / 1e9, 1),
                             "hbm_model_gbs": round(bytes_min(csr.M, csr.K, nnz, N) / (m * 1e-3) / 1e9, 1)}
+    # cold timings after every hot one: creating their copies leaves the GPU idle for a while
+    for N in () if args.no_cold else cols:
+        cold = time_execute_cold(torch, csr, plans[N], Bs[N], N)
+        if cold is not None:
+            cold["hbm_model_gbs"] = round(bytes_min(csr.M, csr.K, nnz, N) / (cold["us"] * 1e-6) / 1e9, 1)
+            cold["frac_of_hbm_peak"] = round(cold["hbm_model_gbs"] / HBM_PEAK_GBS, 5)
+            per_cols[str(N)]["cold"] = cold
 
     baselines = {}
     if not args.no_baselines:
