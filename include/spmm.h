@@ -170,7 +170,7 @@ spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_
  *                      (1 piece of a split panel, 2 idle slot, 4 workgroup with split
  *                      panels), the slot's share of the split-panel sums (pieces to
  *                      add, first piece's slot, tile row, row of C), first window,
- *                      windows
+ *                      windows, a copy of the first window's SPMM_ARRAY_WINS entry
  *   out   HOST, cap_words 32-bit words of room; *n_words (may be NULL) receives the
  *         array's length.  out == NULL only queries the length.  A too small
  *         cap_words copies nothing and returns SPMM_ERR_INVALID_ARG.

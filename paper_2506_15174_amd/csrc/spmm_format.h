@@ -94,7 +94,8 @@ enum ItemField {
     IT_RED_R = 8,     // ... row of the tile to add
     IT_RED_ROW = 9,   // ... row of C to write
     IT_WIN0 = 10,     // first window of the group
-    IT_NWINS = 11     // windows of the group (0 for an idle slot)
+    IT_NWINS = 11,    // windows of the group (0 for an idle slot)
+    IT_WIN_FIRST = 12 // copy of the first window's entry of the window table (saves a dependent load)
 };
 constexpr int FLAG_SPLIT = 1;  // the group is one piece of a split panel: its tile goes to LDS
 constexpr int FLAG_IDLE = 2;   // no group in this wave slot

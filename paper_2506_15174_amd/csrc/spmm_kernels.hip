@@ -252,8 +252,10 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
 #pragma unroll
         for (int r = 0; r < UFI; ++r) acc[r] = Vec<VW>::zero();
 
+        uint32_t wd_next = it[IT_WIN_FIRST];
         for (uint32_t w = 0; w < n_wins; ++w) {
-            const uint32_t wd = wins[w];
+            const uint32_t wd = wd_next;
+            if (w + 1 < n_wins) wd_next = wins[w + 1];  // in flight while this window is consumed
             const uint32_t wc = wd & 0xFFFFu;   // chunks in this window
             const uint32_t ww = wd >> 16;       // words in this window
             // ---- stage the window (the wave's LDS traffic is in order: no wait needed

@@ -508,6 +508,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
             it[IT_FLAGS] = (uint32_t)g.flags;
             it[IT_WIN0] = win0;
             it[IT_NWINS] = (uint32_t)out.wins.size() - win0;
+            it[IT_WIN_FIRST] = out.wins.size() > win0 ? out.wins[win0] : 0u;
             c_at += g.n_chunks;
         };
         auto new_block = [&](uint32_t flags) {

@@ -163,6 +163,7 @@ def walk_chunks(it, hdr, stream, wins):
     host-side header copy."""
     row0, nrows, chunk0, nchunks, stream0, flags = (int(x) for x in it[:6])
     win0, nwins = int(it[10]), int(it[11])
+    assert int(it[12]) == (int(wins[win0]) if nwins else 0), "descriptor's copy of the first window entry"
     at = stream0
     c = chunk0
     for w in range(win0, win0 + nwins):
