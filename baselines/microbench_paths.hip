@@ -4,7 +4,9 @@
 //      vector path (16-byte global loads);
 //   2. gathering random rows of a small matrix with 4-, 8- and 16-byte loads per lane;
 //   3. the same with the executor's access shape: every slice of a wave reads a
-//      different row with 16-byte loads (rows of 512 / 256 / 128 bytes = 2 / 4 / 8 slices).
+//      different row with 16-byte loads (rows of 512 / 256 / 128 bytes = 2 / 4 / 8 slices);
+//   4. what a small launch costs: one workgroup of 8 waves per CU, launched back to back,
+//      each wave following 0 to 4 dependent loads before it stores one word.
 // hipEvent timing, best of 5 launches.  Build and run:
 //   hipcc --offload-arch=gfx950 -O3 baselines/microbench_paths.hip -o microbench_paths && ./microbench_paths
 #include <hip/hip_runtime.h>
@@ -91,6 +93,27 @@ __global__ __launch_bounds__(512) void gather(const float *__restrict__ B, uint3
     out[(blockIdx.x * 8 + wave) * 64 + lane] = acc;
 }
 
+// ---- 4. launch cost and dependent loads -------------------------------------------------
+template <int HOPS> __global__ __launch_bounds__(512) void chase(const uint32_t *__restrict__ table, uint32_t n, uint32_t *out)
+{
+    const uint32_t wave = blockIdx.x * 8 + (threadIdx.x >> 6);
+    uint32_t at = (wave * 9973u + (threadIdx.x & 63u)) % n;
+#pragma unroll
+    for (int h = 0; h < HOPS; ++h) at = table[at];
+    out[blockIdx.x * 512 + threadIdx.x] = at;
+}
+
+template <int HOPS> void run_chase(const uint32_t *table, uint32_t n, uint32_t *out, int cus)
+{
+    const int launches = 50;
+    const float ms = best_ms([&] {
+        for (int i = 0; i < launches; ++i) hipLaunchKernelGGL((chase<HOPS>), dim3(cus), dim3(512), 0, 0, table, n, out);
+    });
+    printf("launch of %d workgroups x 8 waves, %d dependent loads per wave: %5.2f us per launch (50 back to back)\n", cus, HOPS,
+           ms * 1e3 / launches);
+    fflush(stdout);
+}
+
 template <typename F> float best_ms(F f, int reps = 5)
 {
     hipEvent_t a, b;
@@ -170,6 +193,20 @@ int main()
             run_gather<4, 16, 8, true>("4 slices", B, fo, K, wpc, cus, ghz);
             run_gather<4, 8, 8, true>("8 slices", B, fo, K, wpc, cus, ghz);
         }
+    }
+    printf("-- small launches\n");
+    {
+        const uint32_t n = 1u << 20;
+        uint32_t *host = (uint32_t *)malloc(n * 4), *table;
+        for (uint32_t i = 0; i < n; ++i) host[i] = (uint32_t)(((uint64_t)i * 2654435761ull + 40503ull) % n);
+        CK(hipMalloc(&table, n * 4));
+        CK(hipMemcpy(table, host, n * 4, hipMemcpyHostToDevice));
+        run_chase<0>(table, n, out, cus);
+        run_chase<1>(table, n, out, cus);
+        run_chase<2>(table, n, out, cus);
+        run_chase<3>(table, n, out, cus);
+        run_chase<4>(table, n, out, cus);
+        free(host);
     }
     return 0;
 }

@@ -16,6 +16,7 @@ struct spmm_launch_args {
     int32_t ldn;            // leading dimension of B and C (= N)
     int32_t width;          // columns in this tile
     uint32_t col_mask;      // bits of a column word that hold the column index
+    uint32_t lds_pad = 0;   // extra LDS bytes per workgroup (never touched): caps the workgroups per CU
 };
 
 // Enqueues one column tile.  ufi = rows per panel of the plan (1, 2, 4, 8).  slices = 2 / 4 / 8: four columns per lane, tile of up

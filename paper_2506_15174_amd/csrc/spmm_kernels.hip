@@ -413,7 +413,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
 
 #define SPMM_LAUNCH(U, S, VW, D, WIDE)                                                                \
     hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE>), dim3((unsigned)a.n_blocks),           \
-                       dim3(64 * WAVES_PER_WG), 0, (hipStream_t)stream, a.stream, a.wins, a.items,    \
+                       dim3(64 * WAVES_PER_WG), a.lds_pad, (hipStream_t)stream, a.stream, a.wins, a.items,    \
                        a.B, a.b_bytes, a.C, a.ldn, a.width, a.col_mask)
 
 // Pipeline depths: as deep as the 128 VGPRs of a wave allow.  The eight-row tile
