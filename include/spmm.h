@@ -50,6 +50,8 @@ typedef struct {
     int64_t n_chunks;      /* chunks: runs of at most ufk enumerated columns of one pattern */
     int64_t stream_words;  /* 32-bit words of the staged stream (headers, column indices, values, padding) */
     int64_t device_bytes;  /* device memory the plan holds (0 for a host-only plan) */
+    int64_t sorted_rows;   /* 1: the plan's rows are the matrix's rows sorted by length, longest first
+                              (SPMM_ARRAY_ROWMAP gives the order); 0: the plan's rows are the matrix's */
 } spmm_plan_info_t;
 
 /* Optional inspector settings; zero in a field means "let the inspector choose". */
@@ -63,6 +65,10 @@ typedef struct {
                               (0 = unknown, >= 0).  Only the choice of the schedule
                               constants looks at it, as the paper's tuner does per bCols
                               (Section 3.5); the plan stays valid for every N. */
+    int32_t sort_rows;     /* > 0: sort the rows by length, longest first, before forming panels
+                              (C is still written in the caller's row order); < 0: keep the row
+                              order; 0: sort when the rows longer than four times the mean hold
+                              a quarter of the entries and the chosen panels are taller than one row */
 } spmm_options_t;
 
 /*
@@ -70,7 +76,9 @@ typedef struct {
  * transformation", Section 3.4 "Data transformer"; here from CSR in O(nnz log)
  * rather than from dense A).  Validates the CSR, orders the columns of every
  * row, picks the panel height `ufi` and the group budget from the shape, the
- * number of nonzeros and the B-column hint, enumerates nnz-balanced row groups,
+ * number of nonzeros and the B-column hint, sorts the rows by length when their
+ * lengths are very uneven (so that a panel holds rows of like length; C keeps
+ * the caller's row order), enumerates nnz-balanced row groups,
  * merges the columns of each panel of `ufi` rows into enumerated columns tagged
  * with their nonzero pattern, re-stores the values in schedule order and
  * uploads the result.
@@ -92,8 +100,8 @@ spmm_status_t spmm_plan_create(spmm_plan_t **plan, int64_t M, int64_t K,
 
 /*
  * Same, with explicit settings (opts may be NULL).  For experiments the
- * environment variables SPMM_UFI, SPMM_GROUP_NNZ and SPMM_GROUP_PANELS set the
- * corresponding field wherever the caller left it 0 (this is how bench.py forces
+ * environment variables SPMM_UFI, SPMM_GROUP_NNZ, SPMM_GROUP_PANELS and
+ * SPMM_SORT_ROWS set the corresponding field wherever the caller left it 0 (this is how bench.py forces
  * a panel height for counter runs), and SPMM_FORCE_WIDE=1 makes spmm_execute use
  * the 64-bit addressing kernels on inputs that do not need them.
  */
@@ -135,10 +143,13 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
 
 /*
  * Row groups in launch order, five int32 each:
- *   row_begin, row_end   rows of A (and of C) the group covers
+ *   row_begin, row_end   rows of the plan the group covers: rows of A (and of C),
+ *                        or, when info.sorted_rows is set, positions in the
+ *                        length-sorted row order (SPMM_ARRAY_ROWMAP)
  *   nnz_begin, nnz_end   its range in the schedule-ordered value sequence; for a
- *                        group of whole panels this equals the CSR range
- *                        row_ptr[row_begin] .. row_ptr[row_end]
+ *                        group of whole panels this equals the range
+ *                        ptr[row_begin] .. ptr[row_end] of the row pointer of the
+ *                        plan's row order (row_ptr itself unless rows are sorted)
  *   flags                bit 0: the group is one piece of a split panel
  * Order: pieces of split panels first (heaviest panel first, pieces in order),
  * then groups of whole panels (heaviest first); ties keep row order.
@@ -171,11 +182,16 @@ spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_
  *                      panels), the slot's share of the split-panel sums (pieces to
  *                      add, first piece's slot, tile row, row of C), first window,
  *                      windows, a copy of the first window's SPMM_ARRAY_WINS entry
+ *                      (rows are rows of the plan, except the row of C, which is
+ *                      always a row of the matrix)
+ *   SPMM_ARRAY_ROWMAP  M words when info.sorted_rows is set, else none: the row of
+ *                      A and C that each row of the plan stands for (rows by
+ *                      decreasing length, equal lengths in ascending row order)
  *   out   HOST, cap_words 32-bit words of room; *n_words (may be NULL) receives the
  *         array's length.  out == NULL only queries the length.  A too small
  *         cap_words copies nothing and returns SPMM_ERR_INVALID_ARG.
  */
-enum { SPMM_ARRAY_HDR = 0, SPMM_ARRAY_STREAM = 1, SPMM_ARRAY_WINS = 2, SPMM_ARRAY_ITEMS = 3 };
+enum { SPMM_ARRAY_HDR = 0, SPMM_ARRAY_STREAM = 1, SPMM_ARRAY_WINS = 2, SPMM_ARRAY_ITEMS = 3, SPMM_ARRAY_ROWMAP = 4 };
 spmm_status_t spmm_plan_get_array(const spmm_plan_t *plan, int32_t which,
                                   uint32_t *out, int64_t cap_words, int64_t *n_words);
 

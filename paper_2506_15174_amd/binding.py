@@ -19,7 +19,7 @@ SPMM_ERR_ALLOC = 3
 SPMM_ERR_HIP = 4
 SPMM_ERR_UNSUPPORTED = 5
 
-ARRAY_HDR, ARRAY_STREAM, ARRAY_WINS, ARRAY_ITEMS = 0, 1, 2, 3
+ARRAY_HDR, ARRAY_STREAM, ARRAY_WINS, ARRAY_ITEMS, ARRAY_ROWMAP = 0, 1, 2, 3, 4
 
 EXPORTS = ("spmm_plan_create", "spmm_plan_create_ex", "spmm_execute",
            "spmm_plan_destroy", "spmm_plan_describe", "spmm_plan_get_groups",
@@ -33,7 +33,8 @@ class PlanInfo(ctypes.Structure):
                 ("n_groups", ctypes.c_int64), ("n_blocks", ctypes.c_int64),
                 ("n_split", ctypes.c_int64),
                 ("n_enum", ctypes.c_int64), ("n_chunks", ctypes.c_int64),
-                ("stream_words", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
+                ("stream_words", ctypes.c_int64), ("device_bytes", ctypes.c_int64),
+                ("sorted_rows", ctypes.c_int64)]
 
     def as_dict(self):
         return {name: int(getattr(self, name)) for name, _ in self._fields_}
@@ -42,7 +43,7 @@ class PlanInfo(ctypes.Structure):
 class Options(ctypes.Structure):
     _fields_ = [("group_nnz", ctypes.c_int32), ("group_panels", ctypes.c_int32),
                 ("host_only", ctypes.c_int32), ("ufi", ctypes.c_int32),
-                ("n_hint", ctypes.c_int32)]
+                ("n_hint", ctypes.c_int32), ("sort_rows", ctypes.c_int32)]
 
 
 class SpmmError(RuntimeError):
@@ -179,15 +180,16 @@ class Plan:
 
 
 def plan_create(M, K, row_ptr, col_idx, vals, group_nnz=0, group_panels=0, host_only=False, ufi=0,
-                n_hint=0):
+                n_hint=0, sort_rows=0):
     """spmm_plan_create / spmm_plan_create_ex on numpy host arrays."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
     vals = np.ascontiguousarray(vals, dtype=np.float32)
     handle = ctypes.c_void_p()
     lib = load()
-    if group_nnz or group_panels or host_only or ufi or n_hint:
-        opts = Options(int(group_nnz), int(group_panels), 1 if host_only else 0, int(ufi), int(n_hint))
+    if group_nnz or group_panels or host_only or ufi or n_hint or sort_rows:
+        opts = Options(int(group_nnz), int(group_panels), 1 if host_only else 0, int(ufi), int(n_hint),
+                       int(sort_rows))
         st = lib.spmm_plan_create_ex(ctypes.byref(handle), int(M), int(K), _ptr(row_ptr),
                                      _ptr(col_idx), _ptr(vals), ctypes.byref(opts))
     else:

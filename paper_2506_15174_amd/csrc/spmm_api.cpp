@@ -19,7 +19,7 @@ struct spmm_plan {
     HostPlan host;
     bool on_device = false;
     int device = -1;
-    uint32_t *d_stream = nullptr, *d_wins = nullptr, *d_items = nullptr;
+    uint32_t *d_stream = nullptr, *d_wins = nullptr, *d_items = nullptr, *d_rowmap = nullptr;
     int64_t device_bytes = 0;
     int64_t stream_words = 0;  // length of host.stream at creation (a device plan drops its host mirror)
     bool force_wide = false;  // test hook: exercise the 64-bit addressing kernels on small inputs
@@ -66,7 +66,8 @@ void release_device(spmm_plan *p)
     if (p->d_stream) (void)hipFree(p->d_stream);
     if (p->d_wins) (void)hipFree(p->d_wins);
     if (p->d_items) (void)hipFree(p->d_items);
-    p->d_stream = p->d_wins = p->d_items = nullptr;
+    if (p->d_rowmap) (void)hipFree(p->d_rowmap);
+    p->d_stream = p->d_wins = p->d_items = p->d_rowmap = nullptr;
     (void)hipGetLastError();
 }
 
@@ -83,6 +84,7 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
     io.group_nnz = env_int("SPMM_GROUP_NNZ");
     io.group_panels = env_int("SPMM_GROUP_PANELS");
     io.ufi = env_int("SPMM_UFI");
+    io.sort_rows = env_int("SPMM_SORT_ROWS");
     bool host_only = false;
     if (opts) {
         if (opts->group_nnz < 0 || opts->group_panels < 0 || opts->n_hint < 0) return SPMM_ERR_INVALID_ARG;
@@ -93,6 +95,7 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
         if (opts->group_panels > 0) io.group_panels = opts->group_panels;
         host_only = opts->host_only != 0;
         io.n_hint = opts->n_hint;
+        if (opts->sort_rows != 0) io.sort_rows = opts->sort_rows;
     }
     spmm_plan *p = new (std::nothrow) spmm_plan();
     if (!p) return SPMM_ERR_ALLOC;
@@ -112,6 +115,7 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
         if (st == SPMM_OK) st = upload(&p->d_stream, h.stream.data(), h.stream.size() * 4, p->device_bytes);
         if (st == SPMM_OK) st = upload(&p->d_wins, h.wins.data(), h.wins.size() * 4, p->device_bytes);
         if (st == SPMM_OK) st = upload(&p->d_items, h.items.data(), h.items.size() * 4, p->device_bytes);
+        if (st == SPMM_OK) st = upload(&p->d_rowmap, h.rowmap.data(), h.rowmap.size() * 4, p->device_bytes);
         if (st != SPMM_OK) {
             release_device(p);
             delete p;
@@ -126,6 +130,7 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
         std::vector<uint32_t>().swap(p->host.hdr);
         std::vector<uint32_t>().swap(p->host.wins);
         std::vector<uint32_t>().swap(p->host.items);
+        // the row map stays: one bit of it (sorted or not) is part of the description
     }
     *plan = p;
     return SPMM_OK;
@@ -161,6 +166,7 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
     a.stream = plan->d_stream;
     a.wins = plan->d_wins;
     a.items = plan->d_items;
+    a.rowmap = plan->d_rowmap;
     a.n_blocks = (int32_t)h.n_blocks;
     a.ldn = N;
     a.col_mask = h.K <= ((int64_t)1 << spmm_fmt::COL_PATTERN_SHIFT) ? spmm_fmt::COL_INDEX_MASK : 0xFFFFFFFFu;
@@ -222,6 +228,7 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
     out->n_chunks = h.n_chunks;
     out->stream_words = plan->stream_words;
     out->device_bytes = plan->device_bytes;
+    out->sorted_rows = h.rowmap.empty() ? 0 : 1;
     return SPMM_OK;
 }
 
@@ -241,6 +248,15 @@ spmm_status_t spmm_plan_get_array(const spmm_plan_t *plan, int32_t which, uint32
     if (!plan) return SPMM_ERR_INVALID_ARG;
     if (plan->on_device) return SPMM_ERR_INVALID_ARG;  // only host-only plans keep the mirror
     const HostPlan &h = plan->host;
+    if (which == SPMM_ARRAY_ROWMAP) {
+        // M entries for a plan with sorted rows (the vector carries padding for the kernel), else none
+        const int64_t n = h.rowmap.empty() ? 0 : h.M;
+        if (n_words) *n_words = n;
+        if (!out) return SPMM_OK;
+        if (cap_words < n) return SPMM_ERR_INVALID_ARG;
+        if (n) std::memcpy(out, h.rowmap.data(), (size_t)n * 4);
+        return SPMM_OK;
+    }
     const std::vector<uint32_t> *v = nullptr;
     switch (which) {
     case SPMM_ARRAY_HDR: v = &h.hdr; break;

@@ -9,6 +9,7 @@ struct spmm_launch_args {
     const uint32_t *stream; // DEVICE staging windows: headers, column indices, value bits
     const uint32_t *wins;   // DEVICE window table
     const uint32_t *items;  // DEVICE wave-slot descriptors, 16 per block
+    const uint32_t *rowmap = nullptr; // DEVICE row of C per row of the plan, or null (same rows)
     int32_t n_blocks;       // workgroups to launch
     const float *B;         // DEVICE first column of the column tile
     uint32_t b_bytes;       // bytes of B reachable from that pointer (narrow addressing only)

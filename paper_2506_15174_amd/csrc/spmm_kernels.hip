@@ -18,11 +18,10 @@
 //     panel (the paper's register tile, Listing 6).
 //   * A chunk is UFK = 8 enumerated columns of one nonzero pattern (or leftovers
 //     of several patterns under the union of their patterns, with zeros where a
-//     column lacks a row).  Its column
-//     indices and values are staged through LDS, a window of the group's stream
-//     at a time, with coalesced 16-byte loads (the scalar data path tops out far
-//     below what the stream needs); a slice reads its own slots back with one
-//     broadcast LDS read per row of the pattern.  The one-word chunk header comes
+//     column lacks a row).  Its column indices and values are staged through LDS,
+//     a window of the group's stream at a time, with coalesced 16-byte loads (the
+//     scalar data path tops out far below what the stream needs); a slice reads
+//     its own slots back with one broadcast LDS read per row of the pattern.  The one-word chunk header comes
 //     from the same window: its pattern selects, with wave-uniform branches,
 //     which of the UFI row blocks run, so no lane ever tests a sparsity condition
 //     (Section 3.2.2: enumerated blocks carry no conditionals).  No scalar load
@@ -207,7 +206,7 @@ template <int UFI, int S, int VW, int D, bool WIDE>
 __global__ __launch_bounds__(64 * WAVES_PER_WG, (waves_per_simd(S, UFI))) void
 spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                    const uint32_t *__restrict__ wins_g, const uint32_t *__restrict__ items_g,
-                   const float *__restrict__ B, uint32_t b_bytes, float *__restrict__ C, int32_t ldn,
+                   const uint32_t *__restrict__ rowmap_g, const float *__restrict__ B, uint32_t b_bytes, float *__restrict__ C, int32_t ldn,
                    int32_t width, uint32_t col_mask)
 {
     typedef typename Vec<VW>::type vec_t;
@@ -369,11 +368,20 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                                 for (int r = 0; r < UFI; ++r)
                                     *reinterpret_cast<vec_t *>(win + (r * L + sl) * VW) = acc[r];
                             } else if (active) {
-                                float *c_panel = C + (size_t)row * (size_t)ldn + sl * VW;
+                                if (rowmap_g) {
+                                    // rows sorted by length: the plan's row `row + r` is another row of C
+                                    cword_t *map = (cword_t *)(rowmap_g) + row;
 #pragma unroll
-                                for (int r = 0; r < UFI; ++r)
-                                    if ((uint32_t)r < rows_here)
-                                        *reinterpret_cast<vec_t *>(c_panel + (size_t)r * ldn) = acc[r];
+                                    for (int r = 0; r < UFI; ++r)
+                                        if ((uint32_t)r < rows_here)
+                                            *reinterpret_cast<vec_t *>(C + (size_t)map[r] * (size_t)ldn + sl * VW) = acc[r];
+                                } else {
+                                    float *c_panel = C + (size_t)row * (size_t)ldn + sl * VW;
+#pragma unroll
+                                    for (int r = 0; r < UFI; ++r)
+                                        if ((uint32_t)r < rows_here)
+                                            *reinterpret_cast<vec_t *>(c_panel + (size_t)r * ldn) = acc[r];
+                                }
                             }
                         }
                         row += rows_here;
@@ -413,8 +421,8 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
 
 #define SPMM_LAUNCH(U, S, VW, D, WIDE)                                                                \
     hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE>), dim3((unsigned)a.n_blocks),           \
-                       dim3(64 * WAVES_PER_WG), a.lds_pad, (hipStream_t)stream, a.stream, a.wins, a.items,    \
-                       a.B, a.b_bytes, a.C, a.ldn, a.width, a.col_mask)
+                       dim3(64 * WAVES_PER_WG), a.lds_pad, (hipStream_t)stream, a.stream, a.wins,     \
+                       a.items, a.rowmap, a.B, a.b_bytes, a.C, a.ldn, a.width, a.col_mask)
 
 // Pipeline depths: as deep as the 128 VGPRs of a wave allow.  The eight-row tile
 // holds 32 accumulators, which leaves room for fewer B rows in flight.

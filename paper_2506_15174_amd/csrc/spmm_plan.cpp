@@ -87,6 +87,31 @@ int choose_ufi(int64_t M, int64_t K, int64_t nnz, int32_t n_hint)
     return 1;
 }
 
+// Panel height for a matrix whose rows are sorted by length (skewed_rows below).
+// The longest rows then sit in the same panels and share most of their columns,
+// but a panel is processed by one workgroup, cut into at most eight pieces: a
+// panel much heavier than a compute unit's fair share of the matrix (nnz / 256)
+// becomes the tail of the launch.  The height is the largest power of two h <= 8
+// with h * (longest row) <= 2 * fair share (measured on Zipf-distributed row
+// lengths from 1024 to 16384 rows: the best forced height follows this bound
+// within 12 %); narrow B halves the gain of a tall panel, so it takes two rows
+// where wide B would take four or more, else single rows.  A tile of B beyond one
+// L2 keeps single rows as above (for more than 64 columns the executor narrows
+// the tile to 64 columns first).  Height 1 means the rows are not sorted at all.
+int choose_ufi_skewed(int64_t K, int64_t nnz, int64_t max_row, int32_t n_hint)
+{
+    const bool narrow = n_hint > 0 && n_hint <= 32;
+    const bool medium = n_hint > 32 && n_hint <= 64;
+    const int64_t l2 = (int64_t)4 << 20;
+    const int64_t tile_row_bytes = narrow ? 128 : medium ? 256 : K * 512 > l2 ? 256 : 512;
+    if (K * tile_row_bytes > l2) return 1;
+    const int64_t fair = std::max<int64_t>(1, nnz / 256);
+    int h = 1;
+    while (h < MAX_UFI && 2 * h * max_row <= 2 * fair) h *= 2;
+    if (narrow) return h >= 4 ? 2 : 1;
+    return h;
+}
+
 // Nonzero budget G of a row group and the cap GP on the panels one group packs.
 // P panels of mean weight `mean`:
 //   * fewer than 4096 panels: a typical panel is cut into ppt = min(8, ceil(8192 / P))
@@ -107,6 +132,19 @@ void choose_group_budget(int64_t M, int64_t nnz, int ufi, int32_t &G_out, int32_
     if (g > 1024) g = 1024;
     G_out = (int32_t)g;
     GP_out = (int32_t)GP;
+}
+
+// Row lengths so uneven that sorting the rows pays: the rows longer than four
+// times the mean hold at least a quarter of the entries.
+bool skewed_rows(const int32_t *row_ptr, int64_t M, int64_t nnz)
+{
+    if (M < 2 || nnz == 0) return false;
+    int64_t heavy = 0;
+    for (int64_t i = 0; i < M; ++i) {
+        const int64_t len = row_ptr[i + 1] - row_ptr[i];
+        if (len * M > 4 * nnz) heavy += len;
+    }
+    return 4 * heavy >= nnz;
 }
 
 struct Emitter {
@@ -273,16 +311,49 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         out.M = M;
         out.K = K;
         out.nnz = nnz;
-        // ---- 1. panel height, group budget and row groups, from row_ptr alone ---
+        // ---- 0. row order ------------------------------------------------------
+        // Rows of very different lengths: the plan's rows are the matrix's rows
+        // sorted by length, longest first (stable), so that a panel holds rows of
+        // like length (long rows share most of their columns, which is what a
+        // tall panel turns into fewer loads of B) and C is written through a map.
+        int64_t max_row = 0;
+        for (int64_t i = 0; i < M; ++i) max_row = std::max<int64_t>(max_row, row_ptr[i + 1] - row_ptr[i]);
         int ufi = opts.ufi;
-        if (ufi != 1 && ufi != 2 && ufi != 4 && ufi != 8) ufi = choose_ufi(M, K, nnz, opts.n_hint);
+        const bool forced_ufi = ufi == 1 || ufi == 2 || ufi == 4 || ufi == 8;
+        const bool skewed = skewed_rows(row_ptr, M, nnz);
+        if (!forced_ufi) {
+            // a forced sort asks for the height a sorted matrix would get
+            const bool as_sorted = opts.sort_rows > 0 || (opts.sort_rows == 0 && skewed);
+            ufi = as_sorted ? choose_ufi_skewed(K, nnz, max_row, opts.n_hint) : choose_ufi(M, K, nnz, opts.n_hint);
+        }
+        // single rows share nothing: sorting them would only scatter the rows of C
+        const bool sorted = opts.sort_rows > 0 || (opts.sort_rows == 0 && skewed && ufi > 1);
+        std::vector<int32_t> sorted_ptr;
+        if (sorted) {
+            out.rowmap.resize((size_t)M);
+            std::iota(out.rowmap.begin(), out.rowmap.end(), 0u);
+            std::stable_sort(out.rowmap.begin(), out.rowmap.end(), [&](uint32_t x, uint32_t y) {
+                return row_ptr[x + 1] - row_ptr[x] > row_ptr[y + 1] - row_ptr[y];
+            });
+            sorted_ptr.resize((size_t)M + 1);
+            sorted_ptr[0] = 0;
+            for (int64_t i = 0; i < M; ++i) {
+                const uint32_t r = out.rowmap[(size_t)i];
+                sorted_ptr[(size_t)i + 1] = sorted_ptr[(size_t)i] + (row_ptr[r + 1] - row_ptr[r]);
+            }
+        }
+        // row i of the plan: entries [row_ptr[src(i)], row_ptr[src(i) + 1]) of the CSR;
+        // plan_ptr is the row pointer of the plan's own row order
+        auto src = [&](int64_t i) -> int64_t { return sorted ? (int64_t)out.rowmap[(size_t)i] : i; };
+        const int32_t *plan_ptr = sorted ? sorted_ptr.data() : row_ptr;
+        // ---- 1. group budget and row groups, from the row pointer alone ----------
         int32_t auto_g = 0, auto_gp = 0;
         choose_group_budget(M, nnz, ufi, auto_g, auto_gp);
         out.group_nnz = opts.group_nnz > 0 ? std::max(8, opts.group_nnz) : auto_g;
         out.group_panels = opts.group_panels > 0 ? opts.group_panels : auto_gp;
         const int64_t G = out.group_nnz;
         const int64_t GP = out.group_panels;
-        std::vector<Group> groups = make_groups(row_ptr, M, ufi, G, GP);
+        std::vector<Group> groups = make_groups(plan_ptr, M, ufi, G, GP);
         out.ufi = ufi;
         const int UFI = ufi;  // panel height of this plan
         const int N_PATTERNS = (1 << UFI) - 1;
@@ -321,7 +392,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                 const int rows = (int)(r1 - r0);
                 // canonical rows: stable order by column (duplicates keep stored order)
                 for (int r = 0; r < rows; ++r) {
-                    const int64_t a = row_ptr[r0 + r], b = row_ptr[r0 + r + 1];
+                    const int64_t a = row_ptr[src(r0 + r)], b = row_ptr[src(r0 + r) + 1];
                     const int64_t len = b - a;
                     ccol[r].resize((size_t)len);
                     cval[r].resize((size_t)len);
@@ -543,7 +614,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                     it[IT_RED_NSEG] = (uint32_t)nseg;
                     it[IT_RED_SLOT0] = (uint32_t)used;
                     it[IT_RED_R] = (uint32_t)r;
-                    it[IT_RED_ROW] = (uint32_t)(g0.row_begin + r);
+                    it[IT_RED_ROW] = (uint32_t)src(g0.row_begin + r);
                 }
                 used += nseg;
                 panels += 1;
@@ -566,6 +637,8 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         out.stream.resize(out.stream.size() + STREAM_TAIL_PAD, 0u);
         out.n_chunks = total_chunks;
         out.n_enum = em.n_enum;
+        // the kernel may fetch the map entries of a whole panel at once
+        if (sorted) out.rowmap.resize((size_t)M + MAX_UFI, 0u);
     } catch (const std::bad_alloc &) {
         out = HostPlan();
         return ST_ALLOC;

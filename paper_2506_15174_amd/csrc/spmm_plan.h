@@ -23,6 +23,9 @@ struct HostPlan {
     int64_t n_chunks = 0;      // real chunks (without the padding)
     int64_t n_enum = 0;        // enumerated columns (real column slots)
     int64_t n_split = 0;       // groups that are pieces of split panels
+    // Rows sorted by length (skewed matrices): rowmap[i] = row of A and C that the
+    // plan's row i stands for.  Empty = the plan's rows are the matrix's rows.
+    std::vector<uint32_t> rowmap;
 };
 
 struct InspectorOptions {
@@ -30,6 +33,7 @@ struct InspectorOptions {
     int32_t group_panels = 0;  // 0 = choose
     int32_t ufi = 0;           // 0 = choose; else 1, 2, 4 or 8
     int32_t n_hint = 0;        // B columns the plan is meant for; 0 = unknown
+    int32_t sort_rows = 0;     // 0 = choose; > 0 = sort rows by length; < 0 = keep the row order
 };
 
 // Status codes follow spmm_status_t (0 ok, 1 invalid argument, 2 invalid CSR,

@@ -91,6 +91,57 @@ def choose_ufi(M, K, nnz, n_hint=0):
     return 2 if (M >= 512 and row >= 128) else 1
 
 
+def skewed_rows(row_ptr):
+    """True when the rows longer than four times the mean hold at least a quarter of
+    the entries: the inspector then considers sorting the rows by length."""
+    lens = np.diff(np.asarray(row_ptr, dtype=np.int64))
+    M, nnz = len(lens), int(lens.sum())
+    if M < 2 or nnz == 0:
+        return False
+    heavy = int(lens[lens * M > 4 * nnz].sum())
+    return 4 * heavy >= nnz
+
+
+def choose_ufi_skewed(K, nnz, max_row, n_hint=0):
+    """Panel height for rows sorted by length: the largest power of two h <= 8 with
+    h * (longest row) <= 2 * (nnz // 256); narrow B takes 2 where that gives 4 or 8,
+    else 1; single rows when the tile of B exceeds one L2 (wide tiles narrow to 64
+    columns first)."""
+    narrow, medium = 0 < n_hint <= 32, 32 < n_hint <= 64
+    l2 = 4 << 20
+    tile_row_bytes = 128 if narrow else 256 if medium else 256 if K * 512 > l2 else 512
+    if K * tile_row_bytes > l2:
+        return 1
+    fair = max(1, nnz // 256)
+    h = 1
+    while h < MAX_UFI and 2 * h * max_row <= 2 * fair:
+        h *= 2
+    if narrow:
+        return 2 if h >= 4 else 1
+    return h
+
+
+def choose_schedule(row_ptr, M, K, n_hint=0, ufi=0, sort_rows=0):
+    """(panel height, rows sorted?) as the inspector decides them: `ufi` and
+    `sort_rows` are the caller's settings (0 = choose; sort_rows > 0 sort, < 0 keep)."""
+    lens = np.diff(np.asarray(row_ptr, dtype=np.int64))
+    nnz = int(lens.sum())
+    skewed = skewed_rows(row_ptr)
+    if ufi not in (1, 2, 4, 8):
+        as_sorted = sort_rows > 0 or (sort_rows == 0 and skewed)
+        ufi = (choose_ufi_skewed(K, nnz, int(lens.max()) if M else 0, n_hint) if as_sorted
+               else choose_ufi(M, K, nnz, n_hint))
+    return ufi, bool(sort_rows > 0 or (sort_rows == 0 and skewed and ufi > 1))
+
+
+def sorted_row_order(row_ptr):
+    """Rows by decreasing length, equal lengths in ascending row order; also the row
+    pointer of that order."""
+    lens = np.diff(np.asarray(row_ptr, dtype=np.int64))
+    order = np.argsort(-lens, kind="stable")
+    return order, np.concatenate(([0], np.cumsum(lens[order])))
+
+
 def choose_group_budget(M, nnz, ufi):
     """(nonzero budget, panel cap) of a row group for panels of `ufi` rows."""
     P = max(1, -(-M // ufi))
@@ -119,9 +170,11 @@ def canonical_csr(row_ptr, col_idx, vals):
     return rows[order], np.asarray(col_idx)[order], np.asarray(vals, dtype=np.float32).view(np.uint32)[order]
 
 
-def check_blocks(items, ufi):
-    """Structural invariants of the wave-slot table."""
+def check_blocks(items, ufi, rowmap=None):
+    """Structural invariants of the wave-slot table.  rowmap: the matrix row of every
+    plan row when the plan's rows are sorted by length."""
     items = items.reshape(-1, WAVES_PER_WG, ITEM_WORDS)
+    to_c = (lambda r: int(rowmap[r])) if rowmap is not None and len(rowmap) else (lambda r: r)
     for blk in items:
         flags = blk[:, 5]
         sync = (flags & FLAG_SYNC) != 0
@@ -146,7 +199,7 @@ def check_blocks(items, ufi):
             pieces = blk[slot0:slot0 + nseg]
             assert np.all((pieces[:, 5] & FLAG_SPLIT) != 0)
             assert len(set(pieces[:, 0])) == 1 and len(set(pieces[:, 1])) == 1
-            assert crow == int(pieces[0, 0]) + r and r < int(pieces[0, 1])
+            assert crow == to_c(int(pieces[0, 0]) + r) and r < int(pieces[0, 1])
             assert crow not in rows_written
             rows_written.add(crow)
             if r == 0:
@@ -154,7 +207,7 @@ def check_blocks(items, ufi):
         assert np.all(covered[slots] == 1) and covered.sum() == len(slots)
         for w in slots:
             for r in range(int(blk[w, 1])):
-                assert int(blk[w, 0]) + r in rows_written
+                assert to_c(int(blk[w, 0]) + r) in rows_written
 
 
 def walk_chunks(it, hdr, stream, wins):
@@ -188,11 +241,12 @@ def walk_chunks(it, hdr, stream, wins):
     assert c == chunk0 + nchunks
 
 
-def decode_plan(items, hdr, stream, wins, ufi):
+def decode_plan(items, hdr, stream, wins, ufi, rowmap=None):
     """Chunk arrays -> (row, col, value bits) arrays in the order the kernel
     consumes them.  Also checks the structural invariants of the format and
     raises AssertionError on any violation."""
-    check_blocks(items, ufi)
+    check_blocks(items, ufi, rowmap)
+    to_c = (lambda r: int(rowmap[r])) if rowmap is not None and len(rowmap) else (lambda r: r)
     items = items.reshape(-1, ITEM_WORDS)
     out_rows, out_cols, out_bits = [], [], []
     for it in items:
@@ -231,7 +285,7 @@ def decode_plan(items, hdr, stream, wins, ufi):
                 assert not block[count:].any(), "unused value slots must be zero"
                 for u in range(count):
                     if (own[u] >> r) & 1:
-                        out_rows.append(row + r)
+                        out_rows.append(to_c(row + r))
                         out_cols.append(int(cc[u]) & COL_INDEX_MASK)
                         out_bits.append(int(block[u]))
                     else:
@@ -246,12 +300,13 @@ def decode_plan(items, hdr, stream, wins, ufi):
             np.array(out_bits, dtype=np.uint32))
 
 
-def interpret_plan(items, hdr, stream, wins, B, M, ufi):
+def interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap=None):
     """Evaluates C from the chunk arrays in float32, block by block, chunk by
     chunk, FMA by FMA (row blocks in ascending row, slots in ascending order;
     pieces of a split panel added in slot order by the wave slot the table names).
     The kernel's slices add the same terms in a different order."""
     blocks = items.reshape(-1, WAVES_PER_WG, ITEM_WORDS)
+    to_c = (lambda r: int(rowmap[r])) if rowmap is not None and len(rowmap) else (lambda r: r)
     N = B.shape[1]
     C = np.full((M, N), np.nan, dtype=np.float32)
     B64 = B.astype(np.float64)
@@ -280,7 +335,8 @@ def interpret_plan(items, hdr, stream, wins, B, M, ufi):
                     if flags & FLAG_SPLIT:
                         tiles[w] = acc
                     else:
-                        C[row:row + rows_here] = acc[:rows_here]
+                        for r in range(rows_here):
+                            C[to_c(row + r)] = acc[r]
                     row += rows_here
                     rows_left -= rows_here
                     acc[:] = 0

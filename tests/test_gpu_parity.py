@@ -106,6 +106,38 @@ def test_any_column_count_with_ragged_rows_and_split_panels(torch_gpu, oracle, N
         check(oracle, csr, B, C)
 
 
+@pytest.mark.parametrize("N", [4, 32, 64, 100, 128, 200])
+@pytest.mark.parametrize("ufi", [1, 2, 4, 8])
+def test_rows_sorted_by_length_write_c_in_the_callers_order(torch_gpu, oracle, N, ufi):
+    # Zipf row lengths with empty rows, M % 8 != 0; the plan's rows are the matrix's
+    # rows sorted by length, so every panel writes scattered rows of C
+    csr = gen.zipf_rows(203, 1200, 0.85, 300 + ufi)
+    B = gen.dense_activations(csr.K, N, 310 + N)
+    C, plan = gpu_product(torch_gpu, csr, B, guard_rows=3, group_nnz=96, ufi=ufi, sort_rows=1)
+    info = plan.describe()
+    assert info["sorted_rows"] == 1 and info["ufi"] == ufi and info["n_split"] > 0
+    check(oracle, csr, B, C)
+    # the same product from the unsorted plan: same terms per element, maybe another order
+    C2, plan2 = gpu_product(torch_gpu, csr, B, group_nnz=96, ufi=ufi, sort_rows=-1)
+    assert plan2.describe()["sorted_rows"] == 0
+    check(oracle, csr, B, C2)
+
+
+def test_sorted_rows_with_small_integer_data_are_bit_exact(torch_gpu, oracle):
+    rng = np.random.default_rng(77)
+    M, K, N = 150, 640, 64
+    dens = np.clip(0.6 / (1 + np.arange(M)) ** 0.7, 0.01, 1.0)[rng.permutation(M)]
+    W = np.where(rng.random((M, K)) < dens[:, None], rng.integers(-8, 9, (M, K)), 0).astype(np.float32)
+    csr = gen.csr_from_dense(W)
+    B = rng.integers(-16, 17, (K, N)).astype(np.float32)
+    C_ref, _ = oracle.spmm(csr.row_ptr, csr.col_idx, csr.vals, B)
+    assert np.abs(C_ref).max() < 2 ** 24
+    for ufi in (2, 4, 8):
+        C, plan = gpu_product(torch_gpu, csr, B, group_nnz=64, ufi=ufi, sort_rows=1)
+        assert plan.describe()["sorted_rows"] == 1
+        assert np.array_equal(C.astype(np.float64), C_ref)
+
+
 @pytest.mark.parametrize("group_nnz", [32, 64, 1000, 100000])
 def test_group_budget_does_not_change_the_result_class(torch_gpu, oracle, group_nnz):
     csr = gen.lognormal_rows(300, 700, 0.8, 61)
@@ -255,6 +287,8 @@ def test_stress_config_sampled_rows_at_full_size(torch_gpu, oracle):
     csr = gen.stress()
     B = gen.activations_for(csr, 128)
     C, plan = gpu_product(torch_gpu, csr, B, n_hint=128)
+    # Zipf rows: the inspector sorts them by length and takes four-row panels
+    assert (plan.describe()["sorted_rows"], plan.describe()["ufi"]) == (1, 4)
     assert np.isfinite(C).all()
     rng = np.random.default_rng(123)
     lens = np.diff(csr.row_ptr)

@@ -16,8 +16,9 @@ import pytest
 import paper_2506_15174_amd as spmm
 from workloads import generators as gen
 
-from plan_reference import (UFK, canonical_csr, choose_group_budget, choose_ufi, decode_plan, derive_groups,
-                            interpret_plan,
+from plan_reference import (UFK, canonical_csr, choose_group_budget, choose_schedule, choose_ufi,
+                            choose_ufi_skewed, decode_plan, derive_groups, interpret_plan, skewed_rows,
+                            sorted_row_order,
                             walk_chunks)
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -30,6 +31,19 @@ def host_plan(csr, **kw):
 def arrays(plan):
     return (plan.get_array(spmm.ARRAY_ITEMS), plan.get_array(spmm.ARRAY_HDR),
             plan.get_array(spmm.ARRAY_STREAM), plan.get_array(spmm.ARRAY_WINS))
+
+
+def plan_rows(csr, plan):
+    """(row map, row pointer of the plan's row order); the map is None when the
+    plan's rows are the matrix's.  Checks the exported map against the sort the
+    header describes (decreasing length, equal lengths in ascending row order)."""
+    rowmap = plan.get_array(spmm.ARRAY_ROWMAP)
+    if not plan.describe()["sorted_rows"]:
+        assert len(rowmap) == 0
+        return None, np.asarray(csr.row_ptr, dtype=np.int64)
+    order, ptr = sorted_row_order(csr.row_ptr)
+    assert len(rowmap) == csr.M and np.array_equal(rowmap, order)
+    return rowmap, ptr
 
 
 def heavy_tail_matrix(M, K, seed, heavy_rows=(3, 10), empty_rows=(0, 5, 6, 7, 8)):
@@ -70,19 +84,21 @@ def test_library_exports_every_declared_symbol():
 @pytest.mark.parametrize("name", sorted(CASES))
 @pytest.mark.parametrize("group_nnz", [0, 32, 200])
 @pytest.mark.parametrize("force_ufi", [0, 1, 2, 4, 8])
-def test_row_groups_match_python_rederivation(name, group_nnz, force_ufi):
+@pytest.mark.parametrize("sort_rows", [0, 1, -1])
+def test_row_groups_match_python_rederivation(name, group_nnz, force_ufi, sort_rows):
     csr = CASES[name]()
-    plan = host_plan(csr, group_nnz=group_nnz, ufi=force_ufi)
+    plan = host_plan(csr, group_nnz=group_nnz, ufi=force_ufi, sort_rows=sort_rows)
     info = plan.describe()
     assert (info["M"], info["K"], info["nnz"]) == (csr.M, csr.K, int(csr.row_ptr[-1]))
     assert info["ufk"] == UFK and info["ufi"] in (1, 2, 4, 8)
     nnz = int(csr.row_ptr[-1])
-    UFI = force_ufi or choose_ufi(csr.M, csr.K, nnz)
-    assert info["ufi"] == UFI
+    UFI, is_sorted = choose_schedule(csr.row_ptr, csr.M, csr.K, 0, force_ufi, sort_rows)
+    assert info["ufi"] == UFI and info["sorted_rows"] == int(is_sorted)
     auto_g, auto_gp = choose_group_budget(csr.M, nnz, UFI)
     assert info["group_nnz"] == (group_nnz or auto_g) and info["group_panels"] == auto_gp
     got = plan.get_groups()
-    want, blocks = derive_groups(csr.row_ptr, csr.M, info["group_nnz"], info["group_panels"], UFI)
+    _, plan_ptr = plan_rows(csr, plan)
+    want, blocks = derive_groups(plan_ptr, csr.M, info["group_nnz"], info["group_panels"], UFI)
     assert blocks == info["n_blocks"]
     assert got.shape == want.shape and np.array_equal(got, want)
     assert info["n_groups"] == len(want) and info["n_split"] == int((want[:, 4] & 1).sum())
@@ -96,12 +112,12 @@ def test_row_groups_match_python_rederivation(name, group_nnz, force_ufi):
         if fl & 1:
             assert re_ - rb <= UFI and rb % UFI == 0 and ne > nb
             assert rb in (next_row, next_row - (re_ - rb))  # pieces share their panel's rows
-            pn = int(csr.row_ptr[re_] - csr.row_ptr[rb])
+            pn = int(plan_ptr[re_] - plan_ptr[rb])
             assert pn > info["group_nnz"]
             assert ne - nb <= max(info["group_nnz"], -(-pn // 8))
         else:
             assert rb == next_row and rb % UFI == 0
-            assert (nb, ne) == (csr.row_ptr[rb], csr.row_ptr[re_])
+            assert (nb, ne) == (plan_ptr[rb], plan_ptr[re_])
             assert ne - nb <= info["group_nnz"]
         assert nb == nnz_cover
         nnz_cover = ne
@@ -167,6 +183,76 @@ def test_schedule_constants_rule(case, want):
     assert (ufi,) + choose_group_budget(M, nnz, ufi) == want
 
 
+def _plan_from_row_lengths(lens, K, **kw):
+    """A host plan whose row i holds columns 0 .. lens[i]-1."""
+    lens = np.asarray(lens, dtype=np.int64)
+    row_ptr = np.concatenate(([0], np.cumsum(lens))).astype(np.int32)
+    col_idx = np.concatenate([np.arange(n, dtype=np.int32) for n in lens]) if len(lens) else np.zeros(0, np.int32)
+    return row_ptr, spmm.plan_create(len(lens), K, row_ptr, col_idx, np.ones(len(col_idx), np.float32),
+                                     host_only=True, **kw)
+
+
+# (rows as (count, length) runs, K, hint) -> (ufi, sorted), worked by hand from the
+# rule for skewed matrices in the header of spmm_plan.cpp
+SKEWED_CASES = [
+    # 256 rows of 2048 among 16128 of 60: nnz 1 491 968, mean 91, the long rows hold 35 %:
+    # skewed; fair share 5828: 4 x 2048 <= 11656 < 8 x 2048 -> four rows, sorted
+    (((256, 2048), (16128, 60)), 2048, 128, (4, 1)),
+    (((256, 2048), (16128, 60)), 2048, 64, (4, 1)),
+    # narrow B takes two rows where wide B takes four or eight
+    (((256, 2048), (16128, 60)), 2048, 32, (2, 1)),
+    # 256 rows of 2048 among 16128 of 20: nnz 846 848, fair share 3308: 2 x 2048 <= 6616 < 4 x 2048
+    # -> two rows; narrow B: single rows, not sorted
+    (((256, 2048), (16128, 20)), 2048, 128, (2, 1)),
+    (((256, 2048), (16128, 20)), 2048, 32, (1, 0)),
+    # 64 rows of 4096 among 4032 of 100: skewed (39 %), fair share 2599: 2 x 4096 > 5198: single rows
+    (((64, 4096), (4032, 100)), 4096, 128, (1, 0)),
+    # 512 rows of 1024 among 15872 of 200: nnz 3 698 688, mean 226, 1024 > 4 x 226 holds 14 %:
+    # not skewed, the ordinary rule (16384 rows, rows of 225 >= 192) gives eight rows
+    (((512, 1024), (15872, 200)), 1024, 128, (8, 0)),
+    # 1024 rows of 2000 among 15360 of 100: nnz 3 584 000, the long rows hold 57 %; fair share
+    # 14000: 8 x 2000 <= 28000 -> eight rows; narrow B: two rows
+    (((1024, 2000), (15360, 100)), 2048, 0, (8, 1)),
+    (((1024, 2000), (15360, 100)), 2048, 32, (2, 1)),
+    # K = 16384: 128 columns of B exceed one L2 but the executor's 64-column tiles fit;
+    # 64 columns of a K = 32768 matrix do not: single rows
+    (((1024, 2000), (15360, 100)), 16384, 128, (8, 1)),
+    (((1024, 2000), (15360, 100)), 32768, 128, (1, 0)),
+]
+
+
+@pytest.mark.parametrize("runs,K,hint,want", SKEWED_CASES)
+def test_schedule_of_skewed_matrices(runs, K, hint, want):
+    lens = np.concatenate([np.full(c, n) for c, n in runs])
+    lens = lens[np.random.default_rng(5).permutation(len(lens))]
+    row_ptr, plan = _plan_from_row_lengths(lens, K, n_hint=hint)
+    info = plan.describe()
+    assert (info["ufi"], info["sorted_rows"]) == want
+    assert choose_schedule(row_ptr, len(lens), K, hint) == (want[0], bool(want[1]))
+    if want[1]:
+        rowmap = plan.get_array(spmm.ARRAY_ROWMAP)
+        assert sorted(rowmap.tolist()) == list(range(len(lens)))
+        sl = lens[rowmap]
+        assert np.all(np.diff(sl) <= 0), "longest rows first"
+        same = np.flatnonzero(np.diff(sl) == 0)
+        assert np.all(rowmap[same] < rowmap[same + 1]), "equal lengths keep the row order"
+
+
+def test_sorting_can_be_forced_and_forbidden():
+    lens = [5, 300, 0, 17, 300, 2, 64, 0, 9]
+    row_ptr, plan = _plan_from_row_lengths(lens, 400, sort_rows=1, ufi=2)
+    assert plan.describe()["sorted_rows"] == 1
+    assert plan.get_array(spmm.ARRAY_ROWMAP).tolist() == [1, 4, 6, 3, 8, 0, 5, 2, 7]
+    # groups are stated in the sorted order: the first panel is rows (1, 4) = 600 entries
+    g = plan.get_groups()
+    assert g[np.lexsort((g[:, 2], g[:, 0]))][0, :2].tolist() == [0, 2]
+    assert not skewed_rows(row_ptr)      # 300 x 9 rows < 4 x 697 entries: left alone, the order would stay
+    _, plan = _plan_from_row_lengths(lens, 400, sort_rows=-1, ufi=2)
+    assert plan.describe()["sorted_rows"] == 0 and len(plan.get_array(spmm.ARRAY_ROWMAP)) == 0
+    with pytest.raises(spmm.SpmmError):
+        plan.get_array(5)
+
+
 def test_empty_matrix_schedule():
     info = spmm.plan_create(0, 5, np.array([0], np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32),
                             host_only=True).describe()
@@ -190,11 +276,12 @@ def test_split_panels_have_power_of_two_piece_counts():
 @pytest.mark.parametrize("name", sorted(CASES))
 @pytest.mark.parametrize("group_nnz", [0, 32, 200])
 @pytest.mark.parametrize("force_ufi", [0, 1, 2, 4, 8])
-def test_format_round_trip_is_bit_exact(name, group_nnz, force_ufi):
+@pytest.mark.parametrize("sort_rows", [0, 1])
+def test_format_round_trip_is_bit_exact(name, group_nnz, force_ufi, sort_rows):
     csr = CASES[name]()
-    plan = host_plan(csr, group_nnz=group_nnz, ufi=force_ufi)
+    plan = host_plan(csr, group_nnz=group_nnz, ufi=force_ufi, sort_rows=sort_rows)
     items, hdr, stream, wins = arrays(plan)
-    rows, cc, bits = decode_plan(items, hdr, stream, wins, plan.describe()["ufi"])
+    rows, cc, bits = decode_plan(items, hdr, stream, wins, plan.describe()["ufi"], plan_rows(csr, plan)[0])
     assert len(rows) == csr.row_ptr[-1] == plan.describe()["nnz"]
     order = np.lexsort((cc, rows))
     want_rows, want_cols, want_bits = canonical_csr(csr.row_ptr, csr.col_idx, csr.vals)
@@ -332,11 +419,12 @@ def test_pattern_histogram_of_uniform_sparsity_matches_closed_form():
 @pytest.mark.parametrize("name", ["tiny", "ragged_rows", "heavy_tail", "all_empty", "single_row"])
 @pytest.mark.parametrize("group_nnz", [0, 32])
 @pytest.mark.parametrize("force_ufi", [0, 1, 2, 4, 8])
-def test_chunk_arrays_evaluate_to_the_product(oracle, name, group_nnz, force_ufi):
+@pytest.mark.parametrize("sort_rows", [0, 1])
+def test_chunk_arrays_evaluate_to_the_product(oracle, name, group_nnz, force_ufi, sort_rows):
     csr = CASES[name]()
     B = gen.dense_activations(csr.K, 5, 99)
-    plan = host_plan(csr, group_nnz=group_nnz, ufi=force_ufi)
-    C = interpret_plan(*arrays(plan), B, csr.M, plan.describe()["ufi"])
+    plan = host_plan(csr, group_nnz=group_nnz, ufi=force_ufi, sort_rows=sort_rows)
+    C = interpret_plan(*arrays(plan), B, csr.M, plan.describe()["ufi"], plan_rows(csr, plan)[0])
     C_ref, S = oracle.spmm(csr.row_ptr, csr.col_idx, csr.vals, B)
     err, bad_zero = oracle.parity_error(C, C_ref, S)
     assert err <= 1e-5 and bad_zero == 0
