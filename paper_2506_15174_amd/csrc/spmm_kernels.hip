@@ -198,9 +198,9 @@ __device__ __forceinline__ uint32_t value_block(uint32_t at, uint32_t pattern, i
 // keep few B rows in flight per wave and walk a long dependent chain per chunk
 // (header, row branches, LDS reads), so they need more resident waves to cover
 // it: 8 (64 VGPRs) with eight slices, 6 (80 VGPRs) with four, 4 (128 VGPRs)
-// with two.  The eight-row tile alone is 32 registers: 6 waves with eight slices,
-// else 4.
-constexpr int waves_per_simd(int S, int UFI) { return UFI > 4 ? (S >= 8 ? 6 : 4) : S >= 8 ? 8 : S >= 4 ? 6 : 4; }
+// with two.  The eight-row tile alone is 32 registers: 4 waves whatever the slices
+// (sized for 6, the eight-slice instance spilled 68 registers and ran 10-28 % slower).
+constexpr int waves_per_simd(int S, int UFI) { return UFI > 4 ? 4 : S >= 8 ? 8 : S >= 4 ? 6 : 4; }
 
 template <int UFI, int S, int VW, int D, bool WIDE>
 __global__ __launch_bounds__(64 * WAVES_PER_WG, (waves_per_simd(S, UFI))) void
