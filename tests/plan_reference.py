@@ -75,7 +75,9 @@ def choose_ufi(M, K, nnz, n_hint=0):
     row = nnz // M if M else 0
     narrow, medium = 0 < n_hint <= 32, 32 < n_hint <= 64
     if K * (128 if narrow else 256 if medium else 512) > 4 << 20:
-        return 1
+        # wide B run as 64-column tiles that still fit one L2
+        wide_tiles = not narrow and not medium and K * 256 <= 4 << 20
+        return 8 if (wide_tiles and M >= 4096 and row >= 1024) else 1
     if narrow:
         if M >= 4096:
             return 4 if row >= 1024 else 1

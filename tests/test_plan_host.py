@@ -170,6 +170,11 @@ SCHEDULE_CASES = [
     ((1024, 1024, 102, 128), (2, 32, 1)),
     # 16384 rows of B of 512 bytes do not fit one L2: single rows; 2 panels per wave, capped budget
     ((16384, 16384, 800, 128), (1, 1024, 2)),
+    # ... but rows of 1100 take eight rows there (the product runs as 64-column tiles that fit):
+    # 2048 panels of 8800 -> 4 pieces -> ceil(5*8800/16) = 2750 -> capped at 1024
+    ((16384, 16384, 1100, 128), (8, 1024, 1)),
+    # K = 32768: no tile fits, single rows whatever the rows
+    ((4096, 32768, 2000, 128), (1, 1024, 1)),
 ]
 
 
