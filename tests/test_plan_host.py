@@ -452,6 +452,50 @@ def test_many_empty_panels_in_one_group_keep_windows_short():
     assert all(-(-wc // 8) * 8 + (wc + 8) * 8 <= 1024 for wc in counts) and max(counts) == 106
 
 
+def _random_csr(rng, M, K, mode):
+    """Random CSR with unsorted columns and duplicates; mode picks the row-length law."""
+    lens = {0: lambda: rng.integers(0, K + 1, M),
+            1: lambda: np.where(rng.random(M) < 0.15, K, rng.integers(0, 4, M)),       # a few dense rows
+            2: lambda: rng.integers(0, 3, M),
+            3: lambda: np.where(rng.random(M) < 0.2, 0, rng.integers(0, 2 * K, M))}[mode]()
+    row_ptr = np.concatenate(([0], np.cumsum(lens))).astype(np.int32)
+    col_idx = rng.integers(0, K, int(row_ptr[-1])).astype(np.int32)
+    vals = rng.integers(-8, 9, int(row_ptr[-1])).astype(np.float32)
+    return gen.Csr(M, K, row_ptr, col_idx, vals)
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_matrices_and_settings_round_trip(seed):
+    """Random shapes, row-length laws, heights, budgets and row orders: the plan decodes
+    to the canonical CSR bit for bit, its groups are those the reference derives, and
+    the chunk arrays evaluate to the exact product (small integers: any order is exact)."""
+    rng = np.random.default_rng(1000 + seed)
+    M, K = int(rng.integers(0, 60)), int(rng.integers(1, 200))
+    csr = _random_csr(rng, M, K, seed % 4)
+    ufi = int(rng.choice([0, 1, 2, 4, 8]))
+    group_nnz = int(rng.choice([0, 8, 40, 300]))
+    sort_rows = int(rng.choice([-1, 0, 1]))
+    hint = int(rng.choice([0, 32, 64, 128]))
+    plan = host_plan(csr, group_nnz=group_nnz, ufi=ufi, sort_rows=sort_rows, n_hint=hint)
+    info = plan.describe()
+    want_ufi, want_sorted = choose_schedule(csr.row_ptr, M, K, hint, ufi, sort_rows)
+    assert (info["ufi"], info["sorted_rows"]) == (want_ufi, int(want_sorted))
+    rowmap, plan_ptr = plan_rows(csr, plan)
+    want, blocks = derive_groups(plan_ptr, M, info["group_nnz"], info["group_panels"], info["ufi"])
+    assert np.array_equal(plan.get_groups(), want) and blocks == info["n_blocks"]
+    items, hdr, stream, wins = arrays(plan)
+    rows, cc, bits = decode_plan(items, hdr, stream, wins, info["ufi"], rowmap)
+    # the same multiset of (row, column, value): values of a column stored twice in a row keep their order
+    want_rows, want_cols, want_bits = canonical_csr(csr.row_ptr, csr.col_idx, csr.vals)
+    got = sorted(zip(rows.tolist(), cc.tolist(), bits.tolist()))
+    assert got == sorted(zip(want_rows.tolist(), want_cols.tolist(), want_bits.tolist()))
+    B = rng.integers(-4, 5, (K, 3)).astype(np.float32)
+    C = interpret_plan(items, hdr, stream, wins, B, M, info["ufi"], rowmap)
+    dense = np.zeros((M, K), dtype=np.float64)
+    np.add.at(dense, (np.repeat(np.arange(M), np.diff(csr.row_ptr)), csr.col_idx), csr.vals.astype(np.float64))
+    assert np.array_equal(C.astype(np.float64), dense @ B.astype(np.float64))
+
+
 def test_plan_bytes_against_csr_bytes_trend():
     # Paper Section 4.4: the transformed format is smaller than CSR at moderate
     # sparsity (one index per merged column instead of one per nonzero) and larger
