@@ -103,14 +103,14 @@ template <int HOPS> __global__ __launch_bounds__(512) void chase(const uint32_t 
     out[blockIdx.x * 512 + threadIdx.x] = at;
 }
 
-template <int HOPS> void run_chase(const uint32_t *table, uint32_t n, uint32_t *out, int cus)
+template <int HOPS> void run_chase(const uint32_t *table, uint32_t n, uint32_t *out, int groups)
 {
     const int launches = 50;
     const float ms = best_ms([&] {
-        for (int i = 0; i < launches; ++i) hipLaunchKernelGGL((chase<HOPS>), dim3(cus), dim3(512), 0, 0, table, n, out);
+        for (int i = 0; i < launches; ++i) hipLaunchKernelGGL((chase<HOPS>), dim3(groups), dim3(512), 0, 0, table, n, out);
     });
-    printf("launch of %d workgroups x 8 waves, %d dependent loads per wave: %5.2f us per launch (50 back to back)\n", cus, HOPS,
-           ms * 1e3 / launches);
+    printf("launch of %d workgroups x 8 waves, %d dependent loads per wave: %5.2f us per launch (50 back to back)\n", groups,
+           HOPS, ms * 1e3 / launches);
     fflush(stdout);
 }
 
@@ -206,6 +206,7 @@ int main()
         run_chase<2>(table, n, out, cus);
         run_chase<3>(table, n, out, cus);
         run_chase<4>(table, n, out, cus);
+        for (int groups : {cus / 4, cus / 2, 2 * cus, 4 * cus, 8 * cus}) run_chase<3>(table, n, out, groups);
         free(host);
     }
     return 0;
