@@ -320,6 +320,43 @@ def test_largest_sweep_entry_sampled_rows_at_full_size(torch_gpu, oracle, N, wan
     check_sampled_rows(oracle, csr, B, C, sample)
 
 
+@pytest.mark.parametrize("N", [128, 96])
+def test_wide_b_beyond_one_l2_runs_as_tiles_of_64_columns(torch_gpu, oracle, N):
+    """4096 x 12288 with rows of 3686 entries: 128 columns of B (6 MiB) exceed one L2, 64
+    fit, so the product runs as 64-column tiles (with the 24 KiB of idle LDS that caps
+    the workgroups per CU) over eight-row panels; sampled panels against the oracle."""
+    csr = gen.magnitude_pruned(4096, 12288, 0.7, 91)
+    B = gen.activations_for(csr, N)
+    C, plan = gpu_product(torch_gpu, csr, B, n_hint=N)
+    assert plan.describe()["ufi"] == 8 and plan.describe()["sorted_rows"] == 0 and np.isfinite(C).all()
+    rng = np.random.default_rng(500 + N)
+    sample = set()
+    for p in rng.choice(csr.M // 8, size=24, replace=False):
+        sample.update(range(8 * p, 8 * p + 8))
+    sample.update((0, csr.M - 1))
+    check_sampled_rows(oracle, csr, B, C, sample)
+
+
+def test_sorted_zipf_matrix_with_eight_row_panels_at_full_size(torch_gpu, oracle):
+    """16384 x 4096 with Zipf row lengths: rows sorted by length, eight-row panels
+    (the longest row, 4096, is within twice a compute unit's share); the oracle checks
+    the rows of sampled panels of the sorted order plus dense and empty rows."""
+    csr = gen.zipf_rows(16384, 4096, 0.9, 13)
+    B = gen.activations_for(csr, 128)
+    C, plan = gpu_product(torch_gpu, csr, B, n_hint=128)
+    assert (plan.describe()["sorted_rows"], plan.describe()["ufi"]) == (1, 8) and np.isfinite(C).all()
+    lens = np.diff(csr.row_ptr)
+    order = np.argsort(-lens, kind="stable")
+    rng = np.random.default_rng(77)
+    sample = set()
+    for p in rng.choice(csr.M // 8, size=48, replace=False):
+        sample.update(order[8 * p:8 * p + 8].tolist())
+    sample.update(order[:8].tolist())
+    sample.update(np.flatnonzero(lens == 0)[:32].tolist())
+    check_sampled_rows(oracle, csr, B, C, sample)
+    assert not C[lens == 0].any()
+
+
 def test_execute_can_be_captured_in_a_graph_and_replayed(torch_gpu, oracle):
     """spmm_execute allocates nothing, clears nothing and never synchronises, so it can
     sit in a captured graph: every replay (with eager work in between) reproduces the
