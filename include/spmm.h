@@ -115,7 +115,7 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
  *   B       DEVICE  const float[K*N], row-major, leading dimension N, finite values
  *   N       columns of B and C, >= 1 (32, 64 and 128 have tuned kernels; every
  *           other N runs through masked column tiles of at most 128 columns, one
- *           kernel launch per tile; tiles of 64 when 128 columns of B exceed one
+ *           kernel launch per tile, so N = 130 costs a launch of 128 and one of 2; tiles of 64 when 128 columns of B exceed one
  *           L2 cache and 64 fit)
  *   C       DEVICE  float[M*N], row-major, leading dimension N; every element is
  *           overwritten (rows of A without nonzeros become +0.0); must not alias B
@@ -127,10 +127,11 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
  * allocates nothing and does not synchronise.  The plan is read-only during
  * execution (pieces of a split panel meet in on-chip memory, not in the plan),
  * so any number of executes of one plan may be in flight on any streams.
- * Results are bit-identical from run to run.  B and C must be 4-byte aligned;
- * 16-byte alignment of both with N a multiple of 4 enables the kernels that
- * handle four columns per lane (all the tuned ones); anything else runs on the
- * one-column-per-lane kernel.
+ * Results are bit-identical from run to run.  B and C must be 4-byte aligned.
+ * Every N runs on the kernels that handle four columns per lane (the last lane of
+ * a row stores only the columns that exist; rows that are not 16-byte aligned cost
+ * some cache efficiency), except products that need 64-bit addressing of B with N
+ * not a multiple of 4, which run on a one-column-per-lane kernel.
  */
 spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N,
                            float *C, void *stream);

@@ -160,8 +160,10 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
     // Narrow addressing: 32-bit byte offsets into B formed by a 24 x 24-bit multiply.
     const bool narrow_ok = b_total <= 0xFFFFFFFFull && h.K < (1 << 24) && (uint64_t)N * 4u < (1u << 24);
     const bool wide = !narrow_ok || (plan->force_wide && b_total > 0);
-    // Four columns per lane need 16-byte aligned rows.
-    const bool quads = (N % 4 == 0) && !((uintptr_t)B & 15u) && !((uintptr_t)C & 15u);
+    // Four columns per lane: 16-byte loads and stores at 4-byte alignment are legal, and a
+    // last lane with fewer than four columns reads past the end of its rows of B, which is
+    // safe through the buffer descriptor of the narrow addressing only (range-checked).
+    const bool quads = !wide || N % 4 == 0;
     spmm_launch_args a;
     a.stream = plan->d_stream;
     a.wins = plan->d_wins;

@@ -68,6 +68,20 @@ __device__ __forceinline__ void fma_acc(f32x4_t &acc, float a, const f32x4_t &b)
     acc[2] = __builtin_fmaf(a, b[2], acc[2]);
     acc[3] = __builtin_fmaf(a, b[3], acc[3]);
 }
+// Stores of a lane's columns to C: rows of C are only 4-byte aligned in general, and
+// the last lane of a tile may own fewer than four columns.
+typedef float f32x4_unaligned_t __attribute__((ext_vector_type(4), aligned(4)));
+__device__ __forceinline__ void store_cols(float *p, float v, int) { *p = v; }
+__device__ __forceinline__ void store_cols(float *p, const f32x4_t &v, int valid)
+{
+    if (valid >= 4) {
+        *reinterpret_cast<f32x4_unaligned_t *>(p) = v;
+    } else {
+        p[0] = v[0];
+        if (valid > 1) p[1] = v[1];
+        if (valid > 2) p[2] = v[2];
+    }
+}
 __device__ __forceinline__ void add_to(float &a, float b) { a += b; }
 __device__ __forceinline__ void add_to(f32x4_t &a, const f32x4_t &b) { a += b; }
 template <int MASK> __device__ __forceinline__ void add_across(float &a) { a += __shfl_xor(a, MASK); }
@@ -234,7 +248,11 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
 
     // Lanes beyond the tile width compute on the tile's first columns and store
     // nothing: no divergent control flow in the hot loop, no out-of-range access.
-    const bool active = sl * VW < width;
+    // The last active lane may own fewer than VW columns: it loads past the end of
+    // its rows of B (the next row, or zeros past the end of B through the buffer
+    // descriptor's range check) and stores only its own columns.
+    const int valid = width - sl * VW;  // columns of C this lane owns (all VW when larger)
+    const bool active = valid > 0;
 
     if (n_wins != 0) {
         uint32_t row = it[IT_ROW0];
@@ -374,13 +392,12 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
 #pragma unroll
                                     for (int r = 0; r < UFI; ++r)
                                         if ((uint32_t)r < rows_here)
-                                            *reinterpret_cast<vec_t *>(C + (size_t)map[r] * (size_t)ldn + sl * VW) = acc[r];
+                                            store_cols(C + (size_t)map[r] * (size_t)ldn + sl * VW, acc[r], valid);
                                 } else {
                                     float *c_panel = C + (size_t)row * (size_t)ldn + sl * VW;
 #pragma unroll
                                     for (int r = 0; r < UFI; ++r)
-                                        if ((uint32_t)r < rows_here)
-                                            *reinterpret_cast<vec_t *>(c_panel + (size_t)r * ldn) = acc[r];
+                                        if ((uint32_t)r < rows_here) store_cols(c_panel + (size_t)r * ldn, acc[r], valid);
                                 }
                             }
                         }
@@ -412,7 +429,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
             vec_t sum = Vec<VW>::zero();
             for (uint32_t p = 0; p < nseg; ++p)
                 add_to(sum, *reinterpret_cast<const vec_t *>(&lds[first + p][(r * L + sl) * VW]));
-            *reinterpret_cast<vec_t *>(C + (size_t)it[IT_RED_ROW] * (size_t)ldn + sl * VW) = sum;
+            store_cols(C + (size_t)it[IT_RED_ROW] * (size_t)ldn + sl * VW, sum, valid);
         }
     }
 }

@@ -232,20 +232,42 @@ def test_wide_addressing_kernels(torch_gpu, oracle):
         del os.environ["SPMM_FORCE_WIDE"]
 
 
-def test_unaligned_rows_take_the_one_column_per_lane_kernels(torch_gpu, oracle):
-    """N a multiple of 4 but B and C only 4-byte aligned: the 16-byte kernels
-    do not apply and the generic kernel must give the same class of result."""
+@pytest.mark.parametrize("N", [64, 66, 3, 127])
+def test_pointers_with_only_four_byte_alignment(torch_gpu, oracle, N):
+    """B and C that start 4 bytes past a 16-byte boundary, with rows that are (N = 64)
+    or are not a multiple of 16 bytes long: the 16-byte loads and stores of the
+    four-columns-per-lane kernels run at 4-byte alignment, the last lane of a tile
+    with N % 4 columns stores only those, and nothing outside C is written."""
     csr = heavy_tail(45, 600, 97)
-    N = 64
-    B = gen.dense_activations(csr.K, N, 98)
+    B = gen.dense_activations(csr.K, N, 98 + N)
     plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, group_nnz=64)
     flatB = torch_gpu.zeros(csr.K * N + 1, dtype=torch_gpu.float32, device="cuda")
-    flatC = torch_gpu.full((csr.M * N + 1,), float("nan"), dtype=torch_gpu.float32, device="cuda")
+    flatC = torch_gpu.full((csr.M * N + 9,), float("nan"), dtype=torch_gpu.float32, device="cuda")
     flatB[1:] = torch_gpu.from_numpy(B).cuda().reshape(-1)
     plan.execute_raw(flatB.data_ptr() + 4, N, flatC.data_ptr() + 4, None)
     torch_gpu.cuda.synchronize()
-    assert np.isnan(flatC[0].item())
-    check(oracle, csr, B, flatC[1:].reshape(csr.M, N).cpu().numpy())
+    host = flatC.cpu().numpy()
+    assert np.isnan(host[0]) and np.isnan(host[csr.M * N + 1:]).all(), "words outside C were written"
+    check(oracle, csr, B, host[1:csr.M * N + 1].reshape(csr.M, N))
+
+
+def test_b_ending_at_the_end_of_its_allocation_is_not_overrun(torch_gpu, oracle):
+    """N = 5: the last active lane of the tile asks for columns 4 .. 7 of every row of B;
+    for the last row that is past the end of B, which the buffer descriptor's range
+    check answers with zeros.  B is the tail of an allocation, C is guarded."""
+    csr = heavy_tail(40, 512, 131)
+    N = 5
+    B = gen.dense_activations(csr.K, N, 132)
+    pool = torch_gpu.zeros(1 << 20, dtype=torch_gpu.float32, device="cuda")
+    dB = pool[pool.numel() - csr.K * N:]
+    dB.copy_(torch_gpu.from_numpy(B).cuda().reshape(-1))
+    plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, ufi=4)
+    flatC = torch_gpu.full((csr.M * N + 8,), float("nan"), dtype=torch_gpu.float32, device="cuda")
+    plan.execute_raw(dB.data_ptr(), N, flatC.data_ptr(), None)
+    torch_gpu.cuda.synchronize()
+    host = flatC.cpu().numpy()
+    assert np.isnan(host[csr.M * N:]).all()
+    check(oracle, csr, B, host[:csr.M * N].reshape(csr.M, N))
 
 
 def test_execute_rejects_bad_arguments(torch_gpu):
