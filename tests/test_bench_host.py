@@ -1,0 +1,41 @@
+"""Host-side checks of bench.py: the byte model, the kernel label it prints against the
+launch table of the kernels' source, and the refusal of more than one GPU."""
+import os
+import re
+import subprocess
+import sys
+
+import bench
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_algorithmic_bytes_model():
+    # int32 row_ptr and col_idx, fp32 values, B read once, C written once
+    M, K, nnz, N = 512, 2048, 209715, 128
+    assert bench.bytes_min(M, K, nnz, N) == 4 * (M + 1) + 8 * nnz + 4 * K * N + 4 * M * N == 2990492
+
+
+def test_kernel_label_follows_the_launch_table():
+    src = open(os.path.join(ROOT, "paper_2506_15174_amd", "csrc", "spmm_kernels.hip")).read()
+    table = {int(u): (int(d2), int(d4), int(d8))
+             for u, d2, d4, d8 in re.findall(r"case (\d): SPMM_LAUNCH_SLICES\(\d, (\d), (\d), (\d)\) break;", src)}
+    assert sorted(table) == [1, 2, 4, 8]
+    for ufi, (d2, d4, d8) in table.items():
+        assert bench.kernel_shape(128, ufi) == "S=2,VW=4,D=%d" % d2
+        assert bench.kernel_shape(64, ufi) == "S=4,VW=4,D=%d" % d4
+        assert bench.kernel_shape(32, ufi) == "S=8,VW=4,D=%d" % d8
+        # 128 columns of a 16384-row B exceed one L2, 64 fit: tiles of 64
+        assert bench.kernel_shape(128, ufi, 16384).startswith("S=4,VW=4,D=%d" % d4)
+    assert bench.tiles_of_64(128, 16384) and not bench.tiles_of_64(128, 8192)
+    assert not bench.tiles_of_64(64, 16384) and not bench.tiles_of_64(128, 16385)
+    # the executor's own condition, as written in its source
+    api = open(os.path.join(ROOT, "paper_2506_15174_amd", "csrc", "spmm_api.cpp")).read()
+    assert "h.K * 512 > ((int64_t)4 << 20) && (int64_t)h.K * 256 <= ((int64_t)4 << 20)" in api
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
