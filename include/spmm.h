@@ -101,9 +101,12 @@ spmm_status_t spmm_plan_create(spmm_plan_t **plan, int64_t M, int64_t K,
 /*
  * Same, with explicit settings (opts may be NULL).  For experiments the
  * environment variables SPMM_UFI, SPMM_GROUP_NNZ, SPMM_GROUP_PANELS and
- * SPMM_SORT_ROWS set the corresponding field wherever the caller left it 0 (this is how bench.py forces
- * a panel height for counter runs), and SPMM_FORCE_WIDE=1 makes spmm_execute use
- * the 64-bit addressing kernels on inputs that do not need them.
+ * SPMM_SORT_ROWS set the corresponding field wherever the caller left it 0
+ * (this is how bench.py forces a panel height for counter runs),
+ * SPMM_FORCE_WIDE=1 makes spmm_execute use
+ * the 64-bit addressing kernels on inputs that do not need them, and
+ * SPMM_THREADS sets the number of host threads the inspector uses (by default
+ * one per two million entries, at most 16; the plan does not depend on it).
  */
 spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
                                   const int32_t *row_ptr, const int32_t *col_idx,

@@ -70,7 +70,7 @@ def build(verbose=False):
         _run(cmd + common + ["-c", os.path.join(CSRC, s), "-o", obj], verbose)
         objects.append(obj)
     _run([hipcc, "-shared", "-fPIC"] + objects +
-         ["-L", os.path.join(ROCM, "lib"), "-lamdhip64", "-o", LIB_PATH], verbose)
+         ["-L", os.path.join(ROCM, "lib"), "-lamdhip64", "-pthread", "-o", LIB_PATH], verbose)
     return LIB_PATH
 
 

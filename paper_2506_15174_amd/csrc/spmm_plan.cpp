@@ -7,13 +7,18 @@
 // transformer" (values re-stored in the order the schedule consumes them, one
 // column index per enumerated column).  The paper scans dense A in O(M K); this
 // builds the same structure from CSR in O(nnz) plus a per-row sort only for rows
-// whose columns arrive unsorted.
+// whose columns arrive unsorted.  Large inputs are enumerated and laid out by
+// several host threads over contiguous ranges of row groups; the result does not
+// depend on their number.
 #include "spmm_plan.h"
 
 #include <algorithm>
 #include <cstring>
 #include <new>
+#include <cstdlib>
 #include <numeric>
+#include <system_error>
+#include <thread>
 
 #include "spmm_format.h"
 
@@ -26,7 +31,8 @@ enum { ST_OK = 0, ST_INVALID_ARG = 1, ST_INVALID_CSR = 2, ST_ALLOC = 3, ST_UNSUP
 struct Group {
     int32_t row_begin, row_end, nnz_begin, nnz_end, flags;
     int32_t seg, nseg;  // piece index / pieces of the panel (split groups only)
-    // filled while emitting
+    // filled while emitting: the emitter that holds the group's chunks and the group's place in it
+    int32_t part = 0;
     int64_t chunk0 = 0, n_chunks = 0, words0 = 0, n_words = 0;
 };
 
@@ -300,6 +306,40 @@ std::vector<Group> make_groups(const int32_t *row_ptr, int64_t M, int ufi, int64
     return groups;
 }
 
+// Threads the enumeration may use: one per 2 M entries, at most 16 and at most what
+// the machine has (SPMM_THREADS overrides, for tests).
+int worker_count(int64_t nnz)
+{
+    int64_t n = std::min<int64_t>(16, std::max<int64_t>(1, nnz / (2 << 20)));
+    const unsigned hw = std::thread::hardware_concurrency();
+    if (hw > 0) n = std::min<int64_t>(n, hw);
+    if (const char *s = std::getenv("SPMM_THREADS")) {
+        const int v = std::atoi(s);
+        if (v >= 1) n = std::min(v, 64);
+    }
+    return (int)n;
+}
+
+// Cuts the groups (creation order) into at most `want` contiguous ranges of about
+// equal numbers of entries; a cut never falls between the pieces of one panel.
+// Returns the range boundaries, first 0 and last groups.size().
+std::vector<int64_t> range_cuts(const std::vector<Group> &groups, int want)
+{
+    const int64_t n = (int64_t)groups.size();
+    std::vector<int64_t> cuts{0};
+    if (n > 0 && want > 1) {
+        const int64_t total = (int64_t)groups.back().nnz_end - groups.front().nnz_begin + n;  // + n: empty groups weigh too
+        int64_t done = 0;
+        for (int64_t g = 0; g < n; ++g) {
+            const bool boundary = !(groups[(size_t)g].flags & FLAG_SPLIT) || groups[(size_t)g].seg == 0;
+            if (boundary && g > cuts.back() && done * want >= total * (int64_t)cuts.size()) cuts.push_back(g);
+            done += (int64_t)groups[(size_t)g].nnz_end - groups[(size_t)g].nnz_begin + 1;
+        }
+    }
+    if (cuts.back() != n || n == 0) cuts.push_back(n);
+    return cuts;
+}
+
 }  // namespace
 
 int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *col_idx,
@@ -367,143 +407,184 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         const int UFI = ufi;  // panel height of this plan
         const int N_PATTERNS = (1 << UFI) - 1;
         const int SPLIT_PANELS_PER_WG = WAVES_PER_WG / UFI;
-        const int64_t P = (M + UFI - 1) / UFI;
         const int64_t n_groups = (int64_t)groups.size();
 
         // ---- 2. enumeration and emission, panel by panel ----------------------
-        Emitter em;
-        em.ufi = UFI;
-        em.merge = K <= ((int64_t)1 << COL_PATTERN_SHIFT);  // the top byte of a column word must be free
-        em.hdr.reserve((size_t)(nnz / 4 + P + 16));
-        em.cols.reserve((size_t)(nnz / 4 + P + 16) * UFK);
-        em.vals.reserve((size_t)(nnz + nnz / 2 + 64));
-
-        std::vector<int32_t> order;                  // canonical order of one row
-        std::vector<int32_t> ccol[MAX_UFI];          // canonical columns per panel row
-        std::vector<float> cval[MAX_UFI];
-        std::vector<Entry> merged, by_pattern, piece;
-        struct Flat { int32_t entry; int32_t row; };
-        std::vector<Flat> flat;
-
-        int64_t gi = 0;
-        while (gi < n_groups) {
-            Group &g0 = groups[gi];
-            const bool split = (g0.flags & FLAG_SPLIT) != 0;
-            const int64_t g_last = split ? gi + g0.nseg - 1 : gi;  // pieces of a panel are adjacent
-            if (!split) {
-                g0.chunk0 = (int64_t)em.hdr.size();
-                g0.words0 = (int64_t)em.vals.size();
-            }
-            const int64_t first_panel = g0.row_begin / UFI;
-            const int64_t last_panel = (g0.row_end + UFI - 1) / UFI;  // exclusive
-            for (int64_t p = first_panel; p < last_panel; ++p) {
-                const int64_t r0 = p * UFI, r1 = std::min<int64_t>(M, r0 + UFI);
-                const int rows = (int)(r1 - r0);
-                // canonical rows: stable order by column (duplicates keep stored order)
-                for (int r = 0; r < rows; ++r) {
-                    const int64_t a = row_ptr[src(r0 + r)], b = row_ptr[src(r0 + r) + 1];
-                    const int64_t len = b - a;
-                    ccol[r].resize((size_t)len);
-                    cval[r].resize((size_t)len);
-                    bool sorted = true;
-                    for (int64_t q = a + 1; q < b; ++q)
-                        if (col_idx[q] < col_idx[q - 1]) { sorted = false; break; }
-                    if (sorted) {
-                        std::copy(col_idx + a, col_idx + b, ccol[r].begin());
-                        std::copy(vals + a, vals + b, cval[r].begin());
-                    } else {
-                        order.resize((size_t)len);
-                        std::iota(order.begin(), order.end(), 0);
-                        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
-                            return col_idx[a + x] < col_idx[a + y];
-                        });
-                        for (int64_t q = 0; q < len; ++q) {
-                            ccol[r][(size_t)q] = col_idx[a + order[(size_t)q]];
-                            cval[r][(size_t)q] = vals[a + order[(size_t)q]];
-                        }
-                    }
+        // The groups are cut into contiguous ranges of about equal weight (never
+        // between the pieces of one panel); every range is enumerated by a thread of
+        // its own into an emitter of its own, and the emitters are joined in order.
+        const bool merge_leftovers = K <= ((int64_t)1 << COL_PATTERN_SHIFT);  // the top byte of a column word must be free
+        auto emit_range = [&](int64_t g_begin, int64_t g_end, Emitter &em) {
+            std::vector<int32_t> order;                  // canonical order of one row
+            std::vector<int32_t> ccol[MAX_UFI];          // canonical columns per panel row
+            std::vector<float> cval[MAX_UFI];
+            std::vector<Entry> merged, by_pattern, piece;
+            struct Flat { int32_t entry; int32_t row; };
+            std::vector<Flat> flat;
+            int64_t gi = g_begin;
+            while (gi < g_end) {
+                Group &g0 = groups[gi];
+                const bool split = (g0.flags & FLAG_SPLIT) != 0;
+                const int64_t g_last = split ? gi + g0.nseg - 1 : gi;  // pieces of a panel are adjacent
+                if (!split) {
+                    g0.chunk0 = (int64_t)em.hdr.size();
+                    g0.words0 = (int64_t)em.vals.size();
                 }
-                // merge the rows' column lists.  The t-th occurrence of a column in
-                // a row meets the t-th occurrences in the other rows, so a column
-                // stored twice in one row yields two enumerated columns.
-                merged.clear();
-                size_t head[MAX_UFI] = {};
-                uint32_t layer[MAX_UFI] = {};
-                for (;;) {
-                    int32_t best_col = INT32_MAX;
-                    uint32_t best_layer = UINT32_MAX;
-                    bool any = false;
+                const int64_t first_panel = g0.row_begin / UFI;
+                const int64_t last_panel = (g0.row_end + UFI - 1) / UFI;  // exclusive
+                for (int64_t p = first_panel; p < last_panel; ++p) {
+                    const int64_t r0 = p * UFI, r1 = std::min<int64_t>(M, r0 + UFI);
+                    const int rows = (int)(r1 - r0);
+                    // canonical rows: stable order by column (duplicates keep stored order)
                     for (int r = 0; r < rows; ++r) {
-                        if (head[r] >= ccol[r].size()) continue;
-                        const int32_t c = ccol[r][head[r]];
-                        if (!any || c < best_col || (c == best_col && layer[r] < best_layer)) {
-                            best_col = c;
-                            best_layer = layer[r];
-                            any = true;
+                        const int64_t a = row_ptr[src(r0 + r)], b = row_ptr[src(r0 + r) + 1];
+                        const int64_t len = b - a;
+                        ccol[r].resize((size_t)len);
+                        cval[r].resize((size_t)len);
+                        bool sorted = true;
+                        for (int64_t q = a + 1; q < b; ++q)
+                            if (col_idx[q] < col_idx[q - 1]) { sorted = false; break; }
+                        if (sorted) {
+                            std::copy(col_idx + a, col_idx + b, ccol[r].begin());
+                            std::copy(vals + a, vals + b, cval[r].begin());
+                        } else {
+                            order.resize((size_t)len);
+                            std::iota(order.begin(), order.end(), 0);
+                            std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+                                return col_idx[a + x] < col_idx[a + y];
+                            });
+                            for (int64_t q = 0; q < len; ++q) {
+                                ccol[r][(size_t)q] = col_idx[a + order[(size_t)q]];
+                                cval[r][(size_t)q] = vals[a + order[(size_t)q]];
+                            }
                         }
                     }
-                    if (!any) break;
-                    Entry e{};
-                    e.col = best_col;
-                    e.pattern = 0;
-                    for (int r = 0; r < rows; ++r) {
-                        if (head[r] >= ccol[r].size()) continue;
-                        if (ccol[r][head[r]] == best_col && layer[r] == best_layer) {
-                            e.pattern |= 1u << r;
-                            e.v[r] = cval[r][head[r]];
-                            const size_t nx = head[r] + 1;
-                            layer[r] = (nx < ccol[r].size() && ccol[r][nx] == best_col) ? layer[r] + 1 : 0;
-                            head[r] = nx;
+                    // merge the rows' column lists.  The t-th occurrence of a column in
+                    // a row meets the t-th occurrences in the other rows, so a column
+                    // stored twice in one row yields two enumerated columns.
+                    merged.clear();
+                    size_t head[MAX_UFI] = {};
+                    uint32_t layer[MAX_UFI] = {};
+                    for (;;) {
+                        int32_t best_col = INT32_MAX;
+                        uint32_t best_layer = UINT32_MAX;
+                        bool any = false;
+                        for (int r = 0; r < rows; ++r) {
+                            if (head[r] >= ccol[r].size()) continue;
+                            const int32_t c = ccol[r][head[r]];
+                            if (!any || c < best_col || (c == best_col && layer[r] < best_layer)) {
+                                best_col = c;
+                                best_layer = layer[r];
+                                any = true;
+                            }
                         }
+                        if (!any) break;
+                        Entry e{};
+                        e.col = best_col;
+                        e.pattern = 0;
+                        for (int r = 0; r < rows; ++r) {
+                            if (head[r] >= ccol[r].size()) continue;
+                            if (ccol[r][head[r]] == best_col && layer[r] == best_layer) {
+                                e.pattern |= 1u << r;
+                                e.v[r] = cval[r][head[r]];
+                                const size_t nx = head[r] + 1;
+                                layer[r] = (nx < ccol[r].size() && ccol[r][nx] == best_col) ? layer[r] + 1 : 0;
+                                head[r] = nx;
+                            }
+                        }
+                        merged.push_back(e);
                     }
-                    merged.push_back(e);
-                }
-                // list columns of equal pattern together (stable: ascending column inside a pattern)
-                by_pattern.resize(merged.size());
-                {
-                    size_t count[(1 << MAX_UFI) + 1] = {0};
-                    for (const Entry &e : merged) count[e.pattern + 1]++;
-                    for (int q = 1; q <= N_PATTERNS + 1; ++q) count[q] += count[q - 1];
-                    for (const Entry &e : merged) by_pattern[count[e.pattern]++] = e;
+                    // list columns of equal pattern together (stable: ascending column inside a pattern)
+                    by_pattern.resize(merged.size());
+                    {
+                        size_t count[(1 << MAX_UFI) + 1] = {0};
+                        for (const Entry &e : merged) count[e.pattern + 1]++;
+                        for (int q = 1; q <= N_PATTERNS + 1; ++q) count[q] += count[q - 1];
+                        for (const Entry &e : merged) by_pattern[count[e.pattern]++] = e;
+                    }
+                    if (!split) {
+                        em.panel(by_pattern);
+                        continue;
+                    }
+                    // split panel: cut the schedule order (pattern by pattern, column by
+                    // column, row by row) at multiples of the budget; an enumerated
+                    // column that straddles a cut is divided between the two pieces.
+                    flat.clear();
+                    for (size_t e = 0; e < by_pattern.size(); ++e)
+                        for (int r = 0; r < UFI; ++r)
+                            if (by_pattern[e].pattern & (1u << r)) flat.push_back(Flat{(int32_t)e, r});
+                    const int64_t base = g0.nnz_begin;
+                    for (int64_t s = gi; s <= g_last; ++s) {
+                        Group &gs = groups[s];
+                        gs.chunk0 = (int64_t)em.hdr.size();
+                        gs.words0 = (int64_t)em.vals.size();
+                        piece.clear();
+                        for (int64_t q = gs.nnz_begin - base; q < gs.nnz_end - base; ++q) {
+                            const Flat &f = flat[(size_t)q];
+                            if (piece.empty() || q == gs.nnz_begin - base || flat[(size_t)q - 1].entry != f.entry) {
+                                Entry e{};
+                                e.col = by_pattern[(size_t)f.entry].col;
+                                e.pattern = 0;
+                                piece.push_back(e);
+                            }
+                            piece.back().pattern |= 1u << f.row;
+                            piece.back().v[f.row] = by_pattern[(size_t)f.entry].v[f.row];
+                        }
+                        em.panel(piece);
+                        gs.n_chunks = (int64_t)em.hdr.size() - gs.chunk0;
+                        gs.n_words = (int64_t)em.vals.size() - gs.words0;
+                    }
                 }
                 if (!split) {
-                    em.panel(by_pattern);
-                    continue;
+                    g0.n_chunks = (int64_t)em.hdr.size() - g0.chunk0;
+                    g0.n_words = (int64_t)em.vals.size() - g0.words0;
                 }
-                // split panel: cut the schedule order (pattern by pattern, column by
-                // column, row by row) at multiples of the budget; an enumerated
-                // column that straddles a cut is divided between the two pieces.
-                flat.clear();
-                for (size_t e = 0; e < by_pattern.size(); ++e)
-                    for (int r = 0; r < UFI; ++r)
-                        if (by_pattern[e].pattern & (1u << r)) flat.push_back(Flat{(int32_t)e, r});
-                const int64_t base = g0.nnz_begin;
-                for (int64_t s = gi; s <= g_last; ++s) {
-                    Group &gs = groups[s];
-                    gs.chunk0 = (int64_t)em.hdr.size();
-                    gs.words0 = (int64_t)em.vals.size();
-                    piece.clear();
-                    for (int64_t q = gs.nnz_begin - base; q < gs.nnz_end - base; ++q) {
-                        const Flat &f = flat[(size_t)q];
-                        if (piece.empty() || q == gs.nnz_begin - base || flat[(size_t)q - 1].entry != f.entry) {
-                            Entry e{};
-                            e.col = by_pattern[(size_t)f.entry].col;
-                            e.pattern = 0;
-                            piece.push_back(e);
-                        }
-                        piece.back().pattern |= 1u << f.row;
-                        piece.back().v[f.row] = by_pattern[(size_t)f.entry].v[f.row];
-                    }
-                    em.panel(piece);
-                    gs.n_chunks = (int64_t)em.hdr.size() - gs.chunk0;
-                    gs.n_words = (int64_t)em.vals.size() - gs.words0;
+
+                gi = g_last + 1;
+            }
+        };
+        std::vector<int64_t> cuts = range_cuts(groups, worker_count(nnz));
+        const size_t n_ranges = cuts.size() - 1;
+        std::vector<Emitter> parts(n_ranges);
+        for (size_t t = 0; t < n_ranges; ++t) {
+            parts[t].ufi = UFI;
+            parts[t].merge = merge_leftovers;
+            const int64_t share = cuts[t + 1] > cuts[t] ? (int64_t)groups[(size_t)cuts[t + 1] - 1].nnz_end -
+                                                              groups[(size_t)cuts[t]].nnz_begin
+                                                        : 0;
+            parts[t].hdr.reserve((size_t)(share / 4 + (cuts[t + 1] - cuts[t]) + 16));
+            parts[t].cols.reserve((size_t)(share / 4 + (cuts[t + 1] - cuts[t]) + 16) * UFK);
+            parts[t].vals.reserve((size_t)(share + share / 2 + 64));
+        }
+        if (n_ranges == 1) {
+            emit_range(cuts[0], cuts[1], parts[0]);
+        } else {
+            std::vector<std::thread> workers;
+            std::vector<int> failed(n_ranges, 0);
+            auto job = [&](size_t t) {
+                try {
+                    emit_range(cuts[t], cuts[t + 1], parts[t]);
+                } catch (const std::bad_alloc &) {
+                    failed[t] = 1;
+                }
+            };
+            for (size_t t = 0; t < n_ranges; ++t) {
+                try {
+                    workers.emplace_back(job, t);
+                } catch (const std::system_error &) {
+                    job(t);  // no thread to be had: this one does the range itself
                 }
             }
-            if (!split) {
-                g0.n_chunks = (int64_t)em.hdr.size() - g0.chunk0;
-                g0.n_words = (int64_t)em.vals.size() - g0.words0;
-            }
-            gi = g_last + 1;
+            for (std::thread &w : workers) w.join();
+            for (int f : failed)
+                if (f) throw std::bad_alloc();
+        }
+        int64_t total_chunks = 0, total_value_words = 0, total_enum = 0;
+        for (size_t t = 0; t < n_ranges; ++t) {
+            for (int64_t g = cuts[t]; g < cuts[t + 1]; ++g) groups[(size_t)g].part = (int32_t)t;
+            total_chunks += (int64_t)parts[t].hdr.size();
+            total_value_words += (int64_t)parts[t].vals.size();
+            total_enum += parts[t].n_enum;
         }
 
         // ---- 3. launch order and blocks ---------------------------------------
@@ -529,32 +610,34 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                    (groups[(size_t)y].nnz_end - groups[(size_t)y].nnz_begin);
         });
 
-        const int64_t total_chunks = (int64_t)em.hdr.size();
         // upper bound of the stream: headers (padded per window), columns, values
-        const int64_t bound_words = total_chunks * (1 + UFK) + (int64_t)em.vals.size() + 8 * total_chunks / 4 + 64;
+        const int64_t bound_words = total_chunks * (1 + UFK) + total_value_words + 8 * total_chunks / 4 + 64;
         if (total_chunks + CHUNK_TAIL_PAD >= ((int64_t)1 << 31) - 8 || bound_words >= ((int64_t)1 << 32) ||
             n_groups >= ((int64_t)1 << 31) - WAVES_PER_WG)
             return ST_UNSUPPORTED;
 
         out.hdr.resize((size_t)(total_chunks + CHUNK_TAIL_PAD), 0u);
-        out.stream.reserve((size_t)(total_chunks * (2 + UFK) + (int64_t)em.vals.size() + STREAM_TAIL_PAD));
         out.groups.reserve((size_t)n_groups * 5);
         int64_t c_at = 0;
+        uint64_t stream_at = 0;
 
-        // appends one group to the launch-ordered arrays: cuts its chunks into
-        // staging windows, lays every window out as [headers | column slots |
-        // value blocks] and fills the group's descriptor
-        auto place = [&](const Group &g, uint32_t *it) {
-            std::copy(em.hdr.begin() + g.chunk0, em.hdr.begin() + g.chunk0 + g.n_chunks, out.hdr.begin() + c_at);
+        // One group's place in the launch-ordered arrays.  `place` cuts the group's
+        // chunks into staging windows and fills its descriptor; the windows' words
+        // are written afterwards (fill_group), many groups at a time.
+        struct Placed { int64_t group; uint64_t stream0; uint32_t win0; int64_t chunk_at; };
+        std::vector<Placed> placed;
+        placed.reserve((size_t)n_groups);
+        auto place = [&](int64_t gi, uint32_t *it) {
+            const Group &g = groups[(size_t)gi];
+            const Emitter &em = parts[(size_t)g.part];
             out.groups.push_back(g.row_begin);
             out.groups.push_back(g.row_end);
             out.groups.push_back(g.nnz_begin);
             out.groups.push_back(g.nnz_end);
             out.groups.push_back(g.flags);
             const uint32_t win0 = (uint32_t)out.wins.size();
-            const uint64_t stream0 = out.stream.size();
+            const uint64_t stream0 = stream_at;
             int64_t c = 0;
-            int64_t v_at = g.words0;
             while (c < g.n_chunks) {
                 // widest run of chunks whose window still fits
                 int64_t wc = 0, vw = 0;
@@ -569,17 +652,12 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                     wc += 1;
                     vw += add;
                 }
-                const int64_t hdr_words = ((wc + 7) / 8) * 8;
-                const int64_t ww = hdr_words + wc * UFK + vw;
-                for (int64_t k = 0; k < hdr_words; ++k)
-                    out.stream.push_back(k < wc ? em.hdr[(size_t)(g.chunk0 + c + k)] : 0u);
-                out.stream.insert(out.stream.end(), em.cols.begin() + (g.chunk0 + c) * UFK,
-                                  em.cols.begin() + (g.chunk0 + c + wc) * UFK);
-                out.stream.insert(out.stream.end(), em.vals.begin() + v_at, em.vals.begin() + v_at + vw);
+                const int64_t ww = ((wc + 7) / 8) * 8 + wc * UFK + vw;
                 out.wins.push_back((uint32_t)wc | ((uint32_t)ww << 16));
+                stream_at += (uint64_t)ww;
                 c += wc;
-                v_at += vw;
             }
+            placed.push_back(Placed{gi, stream0, win0, c_at});
             it[IT_ROW0] = (uint32_t)g.row_begin;
             it[IT_NROWS] = (uint32_t)(g.row_end - g.row_begin);
             it[IT_CHUNK0] = (uint32_t)c_at;
@@ -590,6 +668,27 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
             it[IT_NWINS] = (uint32_t)out.wins.size() - win0;
             it[IT_WIN_FIRST] = out.wins.size() > win0 ? out.wins[win0] : 0u;
             c_at += g.n_chunks;
+        };
+        // writes one placed group: its headers into the header list and every window as
+        // [headers (padded to 8 words) | column slots | value blocks] into the stream
+        auto fill_group = [&](const Placed &pl) {
+            const Group &g = groups[(size_t)pl.group];
+            const Emitter &em = parts[(size_t)g.part];
+            std::copy(em.hdr.begin() + g.chunk0, em.hdr.begin() + g.chunk0 + g.n_chunks, out.hdr.begin() + pl.chunk_at);
+            uint32_t *dst = out.stream.data() + pl.stream0;
+            int64_t c = 0, v_at = g.words0;
+            for (uint32_t w = pl.win0; c < g.n_chunks; ++w) {
+                const int64_t wc = out.wins[w] & 0xFFFFu, ww = out.wins[w] >> 16;
+                const int64_t hdr_words = ((wc + 7) / 8) * 8;
+                const int64_t vw = ww - hdr_words - wc * UFK;
+                std::copy(em.hdr.begin() + g.chunk0 + c, em.hdr.begin() + g.chunk0 + c + wc, dst);
+                std::fill(dst + wc, dst + hdr_words, 0u);
+                std::copy(em.cols.begin() + (g.chunk0 + c) * UFK, em.cols.begin() + (g.chunk0 + c + wc) * UFK, dst + hdr_words);
+                std::copy(em.vals.begin() + v_at, em.vals.begin() + v_at + vw, dst + hdr_words + wc * UFK);
+                dst += ww;
+                c += wc;
+                v_at += vw;
+            }
         };
         auto new_block = [&](uint32_t flags) {
             const size_t at = out.items.size();
@@ -612,7 +711,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                 }
                 for (int sidx = 0; sidx < nseg; ++sidx) {
                     uint32_t *it = &out.items[at + (size_t)(used + sidx) * ITEM_WORDS];
-                    place(groups[(size_t)(head + sidx)], it);
+                    place(head + sidx, it);
                     it[IT_FLAGS] |= FLAG_SYNC;
                     out.n_split += 1;
                 }
@@ -638,14 +737,47 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                     at = new_block(0);
                     used = 0;
                 }
-                place(groups[(size_t)gi2], &out.items[at + (size_t)used * ITEM_WORDS]);
+                place(gi2, &out.items[at + (size_t)used * ITEM_WORDS]);
                 used += 1;
             }
         }
         out.wins.push_back(0u);  // look-ahead slot
-        out.stream.resize(out.stream.size() + STREAM_TAIL_PAD, 0u);
+        // the windows' words, contiguous runs of placed groups per thread
+        out.stream.resize((size_t)stream_at + STREAM_TAIL_PAD, 0u);
+        {
+            const int want = worker_count(nnz);
+            const size_t n_placed = placed.size();
+            std::vector<size_t> from{0};
+            for (int t = 1; t < want; ++t) {
+                // first placed group at or past the t-th share of the stream
+                const uint64_t target = stream_at / (uint64_t)want * (uint64_t)t;
+                size_t lo = from.back(), hi = n_placed;
+                while (lo < hi) {
+                    const size_t mid = (lo + hi) / 2;
+                    if (placed[mid].stream0 < target) lo = mid + 1; else hi = mid;
+                }
+                from.push_back(lo);
+            }
+            from.push_back(n_placed);
+            auto fill_range = [&](size_t a, size_t b) {
+                for (size_t i = a; i < b; ++i) fill_group(placed[i]);
+            };
+            if (want == 1) {
+                fill_range(0, n_placed);
+            } else {
+                std::vector<std::thread> workers;
+                for (int t = 0; t < want; ++t) {
+                    try {
+                        workers.emplace_back(fill_range, from[(size_t)t], from[(size_t)t + 1]);
+                    } catch (const std::system_error &) {
+                        fill_range(from[(size_t)t], from[(size_t)t + 1]);
+                    }
+                }
+                for (std::thread &w : workers) w.join();
+            }
+        }
         out.n_chunks = total_chunks;
-        out.n_enum = em.n_enum;
+        out.n_enum = total_enum;
         // the kernel may fetch the map entries of a whole panel at once
         if (sorted) out.rowmap.resize((size_t)M + MAX_UFI, 0u);
     } catch (const std::bad_alloc &) {

@@ -496,6 +496,21 @@ def test_random_matrices_and_settings_round_trip(seed):
     assert np.array_equal(C.astype(np.float64), dense @ B.astype(np.float64))
 
 
+@pytest.mark.parametrize("name", ["heavy_tail", "lognormal", "uniform_half", "all_empty"])
+def test_plan_does_not_depend_on_the_number_of_inspector_threads(name, monkeypatch):
+    """The inspector enumerates contiguous ranges of groups on several threads for large
+    inputs; SPMM_THREADS forces that on small ones.  Every array must come out the same."""
+    csr = CASES[name]()
+    plans = {}
+    for threads in ("1", "2", "5", "64"):
+        monkeypatch.setenv("SPMM_THREADS", threads)
+        for ufi in (1, 4):
+            plan = host_plan(csr, ufi=ufi, group_nnz=40, sort_rows=1)
+            got = [plan.get_array(w) for w in range(5)] + [plan.get_groups()]
+            want = plans.setdefault(ufi, got)
+            assert all(np.array_equal(x, y) for x, y in zip(got, want)), (threads, ufi)
+
+
 def test_plan_bytes_against_csr_bytes_trend():
     # Paper Section 4.4: the transformed format is smaller than CSR at moderate
     # sparsity (one index per merged column instead of one per nonzero) and larger
