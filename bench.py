@@ -176,7 +176,7 @@ def kernel_shape(N, ufi, K=0):
     tiles of 64 columns."""
     depth = {8: (2, 4, 4), 4: (3, 3, 4), 2: (3, 4, 6), 1: (3, 4, 8)}[ufi]
     if tiles_of_64(N, K):
-        return "S=4,VW=4,D=%d, one launch per 64 columns" % depth[1]
+        return "S=4,VW=4,D=%d, tiles of 64 columns" % depth[1]
     if N > 64:
         return "S=2,VW=4,D=%d" % depth[0]
     if N > 32:
@@ -530,17 +530,14 @@ def main():
     flops_step = 2.0 * nnz * sum(cols)
     value = flops_step / (ms_per_step * 1e-3) / 1e9
 
-    # dominant kernel: the widest column count; one launch per execute there, unless the
-    # product runs as tiles of 64 columns (then every figure below is per kernel launch)
+    # dominant kernel: the widest column count; one launch per execute there (column tiles
+    # of one width share a launch)
     Nd = max(cols)
-    exec_avg_ms, exec_med_ms = time_execute(torch, plans[Nd], Bs[Nd], Cs[Nd], Nd, samples=20)
-    launches = -(-Nd // 64) if tiles_of_64(Nd, csr.K) else 1
-    avg_ms, med_ms = exec_avg_ms / launches, exec_med_ms / launches
-    # the product's algorithmic bytes shared among its launches: reading A once more per
-    # tile is this library's choice, not part of the product
-    bmin = bytes_min(csr.M, csr.K, nnz, Nd) // launches
+    avg_ms, med_ms = time_execute(torch, plans[Nd], Bs[Nd], Cs[Nd], Nd, samples=20)
+    launches = 1
+    bmin = bytes_min(csr.M, csr.K, nnz, Nd)
     achieved = bmin / (avg_ms * 1e-3) / 1e9
-    kernel_tflops = 2.0 * nnz * (Nd // launches) / (avg_ms * 1e-3) / 1e12
+    kernel_tflops = 2.0 * nnz * Nd / (avg_ms * 1e-3) / 1e12
     roofline = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": measured_traffic(args.workload, Nd),
                 "kernel": "spmm_chunks_kernel<UFI=%d,%s> (bCols %d)" % (infos[Nd]["ufi"], kernel_shape(Nd, infos[Nd]["ufi"], csr.K), Nd),

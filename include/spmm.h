@@ -117,9 +117,11 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
  *
  *   B       DEVICE  const float[K*N], row-major, leading dimension N, finite values
  *   N       columns of B and C, >= 1 (32, 64 and 128 have tuned kernels; every
- *           other N runs through masked column tiles of at most 128 columns, one
- *           kernel launch per tile, so N = 130 costs a launch of 128 and one of 2; tiles of 64 when 128 columns of B exceed one
- *           L2 cache and 64 fit)
+ *           other N runs through masked column tiles of at most 128 columns; tiles
+ *           of one width share a kernel launch, a narrower rest takes a launch of
+ *           its own, so N = 256 is one launch and N = 130 costs one of 128 columns
+ *           and one of 2; tiles of 64 when 128 columns of B exceed one L2 cache
+ *           and 64 fit)
  *   C       DEVICE  float[M*N], row-major, leading dimension N; every element is
  *           overwritten (rows of A without nonzeros become +0.0); must not alias B
  *   stream  hipStream_t passed as void* (NULL = the default stream)

@@ -179,26 +179,41 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
     // Such a tile fills the L2: two workgroups per CU instead of three keep the rows of B that
     // concurrently running waves sweep inside it (same matrix: 262 against 275 us).
     a.lds_pad = narrow_tiles ? 24u << 10 : 0u;
-    // Column tiles run one after another on the stream.
+    // Column tiles of one width share a launch (its workgroups start tile by tile, so a
+    // tile begins while the previous one drains); a narrower rest takes a launch of its own.
+    auto tile_for = [&](int32_t left, int &slices) -> int32_t {
+        if (!quads) {
+            slices = 1;
+            return 64;
+        }
+        slices = left > 64 ? (narrow_tiles ? 4 : 2) : left > 32 ? 4 : 8;
+        return 256 / slices;
+    };
     int32_t j0 = 0;
     while (j0 < N) {
         const int32_t left = N - j0;
-        int slices;
-        int32_t tile;
-        if (quads) {
-            slices = left > 64 ? (narrow_tiles ? 4 : 2) : left > 32 ? 4 : 8;
-            tile = 256 / slices;
-        } else {
-            slices = 1;
-            tile = 64;
+        int slices = 0;
+        const int32_t tile = tile_for(left, slices);
+        int32_t n_tiles = left / tile, cols = n_tiles * tile;
+        int rest_slices = 0;
+        if (n_tiles == 0 || (left > cols && tile_for(left - cols, rest_slices) == tile)) {
+            n_tiles += 1;  // the narrower last tile runs on the same kernel
+            cols = left;
+        }
+        if (n_tiles > 65535) {  // grid limit; the loop takes the rest
+            n_tiles = 65535;
+            cols = n_tiles * tile;
         }
         a.B = B ? B + j0 : nullptr;
         a.C = C + j0;
-        a.width = left < tile ? left : tile;
-        a.b_bytes = wide ? 0u : (uint32_t)(b_total - (uint64_t)j0 * 4u);
+        a.width = cols;
+        a.tile_cols = tile;
+        a.n_tiles = n_tiles;
+        const uint64_t skipped = (uint64_t)j0 * 4u;
+        a.b_bytes = wide || b_total <= skipped ? 0u : (uint32_t)(b_total - skipped);
         const int e = spmm_launch_chunks(a, h.ufi, slices, wide, stream);
         if (e != 0) return SPMM_ERR_HIP;
-        j0 += a.width;
+        j0 += cols;
     }
     return SPMM_OK;
 }

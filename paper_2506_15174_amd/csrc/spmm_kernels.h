@@ -11,16 +11,18 @@ struct spmm_launch_args {
     const uint32_t *items;  // DEVICE wave-slot descriptors, 16 per block
     const uint32_t *rowmap = nullptr; // DEVICE row of C per row of the plan, or null (same rows)
     int32_t n_blocks;       // workgroups to launch
-    const float *B;         // DEVICE first column of the column tile
+    const float *B;         // DEVICE first column of the launch's first column tile
     uint32_t b_bytes;       // bytes of B reachable from that pointer (narrow addressing only)
-    float *C;               // DEVICE first column of the column tile
+    float *C;               // DEVICE first column of the launch's first column tile
     int32_t ldn;            // leading dimension of B and C (= N)
-    int32_t width;          // columns in this tile
+    int32_t width;          // columns of this launch: n_tiles tiles of tile_cols, the last maybe narrower
+    int32_t tile_cols;      // columns per tile (per blockIdx.y)
+    int32_t n_tiles;        // column tiles of this launch (grid y)
     uint32_t col_mask;      // bits of a column word that hold the column index
     uint32_t lds_pad = 0;   // extra LDS bytes per workgroup (never touched): caps the workgroups per CU
 };
 
-// Enqueues one column tile.  ufi = rows per panel of the plan (1, 2, 4, 8).  slices = 2 / 4 / 8: four columns per lane, tile of up
+// Enqueues one launch of n_tiles column tiles.  ufi = rows per panel of the plan (1, 2, 4, 8).  slices = 2 / 4 / 8: four columns per lane, tile of up
 // to 128 / 64 / 32 columns (width a multiple of 4, B and C 16-byte aligned);
 // slices = 1: one column per lane, tile of up to 64 columns, any alignment.
 // wide = 64-bit addressing of B.  Returns the hipError_t of the launch as int.

@@ -220,9 +220,18 @@ template <int UFI, int S, int VW, int D, bool WIDE>
 __global__ __launch_bounds__(64 * WAVES_PER_WG, (waves_per_simd(S, UFI))) void
 spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                    const uint32_t *__restrict__ wins_g, const uint32_t *__restrict__ items_g,
-                   const uint32_t *__restrict__ rowmap_g, const float *__restrict__ B, uint32_t b_bytes, float *__restrict__ C, int32_t ldn,
-                   int32_t width, uint32_t col_mask)
+                   const uint32_t *__restrict__ rowmap_g, const float *__restrict__ B_all, uint32_t b_bytes_all,
+                   float *__restrict__ C_all, int32_t ldn, int32_t width_all, int32_t tile_cols, uint32_t col_mask)
 {
+    // blockIdx.y: the column tile this workgroup computes (tiles of tile_cols columns of
+    // the width_all columns of this launch; the last one may be narrower).  Workgroups
+    // are started tile by tile, so a tile begins while the previous one drains.
+    const int32_t col0 = (int32_t)blockIdx.y * tile_cols;
+    const float *__restrict__ B = B_all + col0;
+    float *__restrict__ C = C_all + col0;
+    const int32_t width = width_all - col0 < tile_cols ? width_all - col0 : tile_cols;
+    const uint32_t b_bytes = b_bytes_all > (uint32_t)col0 * 4u ? b_bytes_all - (uint32_t)col0 * 4u : 0u;
+
     typedef typename Vec<VW>::type vec_t;
     typedef typename BSource<WIDE>::off_t off_t;
     constexpr int L = 64 / S;    // lanes per slice
@@ -437,9 +446,10 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
 }  // namespace
 
 #define SPMM_LAUNCH(U, S, VW, D, WIDE)                                                                \
-    hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE>), dim3((unsigned)a.n_blocks),           \
-                       dim3(64 * WAVES_PER_WG), a.lds_pad, (hipStream_t)stream, a.stream, a.wins,     \
-                       a.items, a.rowmap, a.B, a.b_bytes, a.C, a.ldn, a.width, a.col_mask)
+    hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE>),                                       \
+                       dim3((unsigned)a.n_blocks, (unsigned)a.n_tiles), dim3(64 * WAVES_PER_WG),       \
+                       a.lds_pad, (hipStream_t)stream, a.stream, a.wins, a.items, a.rowmap, a.B,       \
+                       a.b_bytes, a.C, a.ldn, a.width, a.tile_cols, a.col_mask)
 
 // Pipeline depths: as deep as the 128 VGPRs of a wave allow.  The eight-row tile
 // holds 32 accumulators, which leaves room for fewer B rows in flight.
@@ -453,7 +463,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
 
 int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int slices, bool wide, void *stream)
 {
-    if (a.n_blocks <= 0) return 0;
+    if (a.n_blocks <= 0 || a.n_tiles <= 0) return 0;
     switch (ufi) {
     case 8: SPMM_LAUNCH_SLICES(8, 2, 4, 4) break;
     case 4: SPMM_LAUNCH_SLICES(4, 3, 3, 4) break;
