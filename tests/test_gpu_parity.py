@@ -86,9 +86,11 @@ def test_conv_config(torch_gpu, oracle, N, hinted):
     assert plan.describe()["ufi"] < 4      # 512 rows: shorter panels give the chip enough workgroups
 
 
-@pytest.mark.parametrize("shape_index,sparsity_index,N", [
-    (0, 0, 128), (0, 1, 64), (0, 2, 32), (0, 3, 128), (1, 0, 32), (1, 1, 128), (1, 2, 64), (1, 3, 32)])
+@pytest.mark.parametrize("N", [32, 64, 128])
+@pytest.mark.parametrize("sparsity_index", [0, 1, 2, 3])
+@pytest.mark.parametrize("shape_index", [0, 1])
 def test_ffn_config(torch_gpu, oracle, shape_index, sparsity_index, N):
+    # all eight feed-forward matrices (two shapes x four sparsities) at the three widths
     csr = gen.ffn(shape_index, sparsity_index)
     B = gen.activations_for(csr, N)
     for hint in (N, 0):
