@@ -381,6 +381,24 @@ def test_sorted_zipf_matrix_with_eight_row_panels_at_full_size(torch_gpu, oracle
     assert not C[lens == 0].any()
 
 
+@pytest.mark.parametrize("index", range(48))
+def test_every_sweep_matrix_at_the_three_widths(torch_gpu, oracle, index):
+    """Configuration 4 as the benchmark runs it (one hinted plan per width): whole
+    products up to 1024 rows, else 96 sampled rows plus the first and last."""
+    entry = gen.sweep_entries()[index]
+    csr = gen.sweep_matrix(entry)
+    rng = np.random.default_rng(900 + index)
+    for N in (32, 64, 128):
+        B = gen.activations_for(csr, N)
+        C, _ = gpu_product(torch_gpu, csr, B, n_hint=N)
+        assert np.isfinite(C).all()
+        if csr.M <= 1024:
+            check(oracle, csr, B, C)
+        else:
+            rows = set(rng.choice(csr.M, size=96, replace=False).tolist()) | {0, csr.M - 1}
+            check_sampled_rows(oracle, csr, B, C, rows)
+
+
 def test_execute_can_be_captured_in_a_graph_and_replayed(torch_gpu, oracle):
     """spmm_execute allocates nothing, clears nothing and never synchronises, so it can
     sit in a captured graph: every replay (with eager work in between) reproduces the
