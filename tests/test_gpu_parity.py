@@ -381,6 +381,44 @@ def test_sorted_zipf_matrix_with_eight_row_panels_at_full_size(torch_gpu, oracle
     assert not C[lens == 0].any()
 
 
+@pytest.mark.parametrize("seed", range(48))
+def test_random_shapes_settings_and_widths(torch_gpu, oracle, seed):
+    """Random shape, row-length law (uniform, a few dense rows, very short rows, duplicates
+    and unsorted columns), panel height, budget, row order and width, with B and C at a
+    random 4-byte offset inside guarded buffers."""
+    rng = np.random.default_rng(4000 + seed)
+    M, K = int(rng.integers(1, 300)), int(rng.integers(1, 1500))
+    mode = seed % 4
+    if mode == 0:
+        lens = rng.integers(0, K + 1, M)
+    elif mode == 1:
+        lens = np.where(rng.random(M) < 0.1, K, rng.integers(0, 6, M))
+    elif mode == 2:
+        lens = rng.integers(0, 4, M)
+    else:
+        lens = np.where(rng.random(M) < 0.2, 0, rng.integers(0, 2 * K, M))       # duplicates
+    row_ptr = np.concatenate(([0], np.cumsum(lens))).astype(np.int32)
+    nnz = int(row_ptr[-1])
+    col_idx = rng.integers(0, K, nnz).astype(np.int32)
+    vals = rng.standard_normal(nnz).astype(np.float32)
+    csr = gen.Csr(M, K, row_ptr, col_idx, vals)
+    N = int(rng.choice([1, 3, 4, 7, 17, 32, 33, 64, 70, 100, 128, 129, 190, 260]))
+    B = rng.standard_normal((K, N)).astype(np.float32)
+    plan = spmm.plan_create(M, K, row_ptr, col_idx, vals, ufi=int(rng.choice([0, 1, 2, 4, 8])),
+                            group_nnz=int(rng.choice([0, 16, 100, 1000])), sort_rows=int(rng.choice([-1, 0, 1])),
+                            n_hint=int(rng.choice([0, 32, 64, 128])))
+    shift = int(rng.integers(0, 4))
+    flatB = torch_gpu.zeros(K * N + 8, dtype=torch_gpu.float32, device="cuda")
+    flatB[shift:shift + K * N] = torch_gpu.from_numpy(B).cuda().reshape(-1)
+    flatC = torch_gpu.full((M * N + 16,), float("nan"), dtype=torch_gpu.float32, device="cuda")
+    plan.execute_raw(flatB.data_ptr() + 4 * shift, N, flatC.data_ptr() + 4 * (4 + shift), None)
+    torch_gpu.cuda.synchronize()
+    host = flatC.cpu().numpy()
+    lo = 4 + shift
+    assert np.isnan(host[:lo]).all() and np.isnan(host[lo + M * N:]).all(), "words outside C were written"
+    check(oracle, csr, B, host[lo:lo + M * N].reshape(M, N))
+
+
 @pytest.mark.parametrize("index", range(48))
 def test_every_sweep_matrix_at_the_three_widths(torch_gpu, oracle, index):
     """Configuration 4 as the benchmark runs it (one hinted plan per width): whole
