@@ -143,23 +143,43 @@ def measure_baselines(torch, np, csr, cols, Bs, dense_limit=1 << 28):
     return out
 
 
+def kernel_source_hash():
+    """First 16 hex digits of the SHA-256 over the library's sources (kernels, format,
+    inspector, C ABI): counter summaries under profiles/ record the hash they were taken
+    at, so that a figure measured on other code is never passed on as this code's."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2506_15174_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".cpp", ".h")):
+            with open(os.path.join(csrc, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(workload, N):
-    """HBM bytes per launch (scaled FETCH_SIZE + WRITE_SIZE) that the committed
-    rocprofv3 counter summaries record for this workload and column count, from their
-    `traffic_bytes_per_launch <workload> <bCols> <bytes>` lines; None if there is none.
-    Counters cannot be read from inside this process, so the figure is the last
-    profiled one, not a live measurement."""
+    """HBM bytes per launch (scaled FETCH_SIZE + WRITE_SIZE) from the committed rocprofv3
+    counter summaries: lines `traffic_bytes_per_launch <workload> <bCols> <bytes> <source hash>`.
+    Counters cannot be read from inside this process, so the figure is the last profiled
+    one; it is passed on only when the summary was taken on the library sources that are
+    in the tree now (kernel_source_hash), else the bytes are withheld.
+    Returns (bytes or None, provenance dict or None)."""
     import glob
-    import os
-    here = os.path.dirname(os.path.abspath(__file__))
-    for path in sorted(glob.glob(os.path.join(here, "profiles", "*.md"))):
+    now = kernel_source_hash()
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
         with open(path) as f:
             for line in f:
                 parts = line.split()
-                if len(parts) == 4 and parts[0] == "traffic_bytes_per_launch" \
+                if len(parts) >= 4 and parts[0] == "traffic_bytes_per_launch" \
                         and parts[1] == workload and parts[2] == str(N):
-                    return int(parts[3])
-    return None
+                    taken_at = parts[4] if len(parts) > 4 else None
+                    prov = {"file": "profiles/" + os.path.basename(path), "source_hash_at_profile": taken_at,
+                            "source_hash_now": now, "current": taken_at == now}
+                    if taken_at != now:
+                        prov["withheld_bytes"] = int(parts[3])
+                        return None, prov
+                    return int(parts[3]), prov
+    return None, None
 
 
 def tiles_of_64(N, K):
@@ -187,40 +207,20 @@ def kernel_shape(N, ufi, K=0):
 SPARSITY_SWEEP = (0.5, 0.6, 0.7, 0.8, 0.85, 0.9, 0.95, 0.98, 0.99)
 
 
-def run_sweep(args, cols=(32, 64, 128), narrow=False, ffn=False, square512=False):
-    """Configuration 4: 48 magnitude-pruned matrices x bCols 32/64/128 against
-    hipSPARSE CSR SpMM and rocBLAS SGEMM; geometric means of the speedups and the
-    share of points where this library is faster (the shape of the paper's Table 1).
-    narrow: the same on the 30 matrices with M, K >= 1024 for bCols 4/8/16, the
-    widths below the kernel's narrowest tile (the paper's Figure 9 measures bCols 4).
-    ffn: the same on the eight feed-forward matrices of configuration 2 (two shapes x four
-    sparsities, lognormal row lengths).
-    square512: the same on one 512 x 512 magnitude-pruned matrix per sparsity from 50 to
-    99 % for bCols 64 and 4 (the sweep of the paper's Figure 9)."""
-    import math
-    import numpy as np
-    import torch
-    import paper_2506_15174_amd as spmm
-    from workloads import generators as gen
-    torch.cuda.set_device(0)
+def _measure_points(torch, np, spmm, gen, entries, cols, make_matrix, keep=None, with_baselines=True):
+    """Per (matrix, bCols): one hinted plan, the per-launch time of spmm_execute and of the
+    two comparison libraries on the same device-resident inputs.  With `keep` (a list) the
+    plan, B and C of every point stay alive and are appended to it as
+    (plan, B, C, N, nnz); otherwise they are released matrix by matrix."""
     rows_out = []
-    t_start = time.perf_counter()
-    if ffn:
-        entries = [dict(index=4 * si + pi, sparsity=gen.FFN_SPARSITIES[pi], ffn=(si, pi))
-                   for si in range(len(gen.FFN_SHAPES)) for pi in range(len(gen.FFN_SPARSITIES))]
-    elif square512:
-        entries = [dict(index=i, sparsity=sp, seed=9000 + i) for i, sp in enumerate(SPARSITY_SWEEP)]
-    else:
-        entries = _ladder_matrices(gen) if narrow else gen.sweep_entries()
     for entry in entries:
-        csr = (gen.ffn(*entry["ffn"]) if ffn else
-               gen.magnitude_pruned(512, 512, entry["sparsity"], entry["seed"]) if square512 else gen.sweep_matrix(entry))
+        csr = make_matrix(entry)
         nnz = int(csr.row_ptr[-1])
         # one plan per column count: the schedule constants are chosen per bCols
         plans = {N: spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, n_hint=N) for N in cols}
         Bs = {N: torch.from_numpy(gen.activations_for(csr, N)).cuda() for N in cols}
         Cs = {N: torch.empty((csr.M, N), dtype=torch.float32, device="cuda") for N in cols}
-        base = measure_baselines(torch, np, csr, cols, Bs)
+        base = measure_baselines(torch, np, csr, cols, Bs) if with_baselines else {}
         for N in cols:
             plan, info = plans[N], plans[N].describe()
             _, med = time_execute(torch, plan, Bs[N], Cs[N], N)
@@ -232,11 +232,21 @@ def run_sweep(args, cols=(32, 64, 128), narrow=False, ffn=False, square512=False
                              "hbm_model_gbs": round(bytes_min(csr.M, csr.K, nnz, N) / (med * 1e-3) / 1e9, 1),
                              "hipsparse_us": b.get("hipsparse_best_us"), "rocblas_us": b.get("rocblas_sgemm_us")})
             print(json.dumps(rows_out[-1]), file=sys.stderr, flush=True)
-        for plan in plans.values():
-            plan.destroy()
+            if keep is not None:
+                keep.append((plan, Bs[N], Cs[N], N, nnz))
+        if keep is None:
+            for plan in plans.values():
+                plan.destroy()
         del plans, Bs, Cs
+    return rows_out
+
+
+def _summarise(rows_out, cols):
+    """Geometric-mean speedups over the two libraries and the share of points faster, per
+    column count and over all points (the shape of the paper's Table 1)."""
+    import math
     summary = {}
-    for N in cols + ("all",):
+    for N in tuple(cols) + ("all",):
         sel = [r for r in rows_out if N == "all" or r["N"] == N]
         for key in ("hipsparse_us", "rocblas_us"):
             sp = [r[key] / r["us"] for r in sel if r[key]]
@@ -244,6 +254,37 @@ def run_sweep(args, cols=(32, 64, 128), narrow=False, ffn=False, square512=False
                 summary["%s_%s" % (key[:-3], N)] = {
                     "geomean_speedup": round(math.exp(sum(math.log(x) for x in sp) / len(sp)), 3),
                     "faster_pct": round(100.0 * sum(1 for x in sp if x > 1.0) / len(sp), 1), "points": len(sp)}
+    return summary
+
+
+def run_sweep(args, cols=(32, 64, 128), narrow=False, ffn=False, square512=False):
+    """Configuration 4: 48 magnitude-pruned matrices x bCols 32/64/128 against
+    hipSPARSE CSR SpMM and rocBLAS SGEMM; geometric means of the speedups and the
+    share of points where this library is faster (the shape of the paper's Table 1).
+    narrow: the same on the 30 matrices with M, K >= 1024 for bCols 4/8/16, the
+    widths below the kernel's narrowest tile (the paper's Figure 9 measures bCols 4).
+    ffn: the same on the eight feed-forward matrices of configuration 2 (two shapes x four
+    sparsities, lognormal row lengths).
+    square512: the same on one 512 x 512 magnitude-pruned matrix per sparsity from 50 to
+    99 % for bCols 64 and 4 (the sweep of the paper's Figure 9)."""
+    import numpy as np
+    import torch
+    import paper_2506_15174_amd as spmm
+    from workloads import generators as gen
+    torch.cuda.set_device(0)
+    t_start = time.perf_counter()
+    if ffn:
+        entries = [dict(index=4 * si + pi, sparsity=gen.FFN_SPARSITIES[pi], ffn=(si, pi))
+                   for si in range(len(gen.FFN_SHAPES)) for pi in range(len(gen.FFN_SPARSITIES))]
+        make = lambda e: gen.ffn(*e["ffn"])
+    elif square512:
+        entries = [dict(index=i, sparsity=sp, seed=9000 + i) for i, sp in enumerate(SPARSITY_SWEEP)]
+        make = lambda e: gen.magnitude_pruned(512, 512, e["sparsity"], e["seed"])
+    else:
+        entries = _ladder_matrices(gen) if narrow else gen.sweep_entries()
+        make = gen.sweep_matrix
+    rows_out = _measure_points(torch, np, spmm, gen, entries, cols, make)
+    summary = _summarise(rows_out, cols)
     total_flops = sum(2.0 * r["nnz"] * r["N"] for r in rows_out)
     total_s = sum(r["us"] for r in rows_out) * 1e-6
     out = {"metric": "fp32 CSR SpMM GFLOP/s (2*nnz*bCols)", "value": round(total_flops / total_s / 1e9, 2),
@@ -456,36 +497,163 @@ def run_tune(args):
                       "summary": summary, "plan_size_by_sparsity_bcols128": size, "points": pts}))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="conv")
-    ap.add_argument("--shape", default="4096x4096", help="--workload matrix: rows x columns of A")
-    ap.add_argument("--sparsity", type=float, default=0.5, help="--workload matrix: pruned share")
-    ap.add_argument("--bcols", type=int, default=128, help="--workload matrix: columns of B")
-    ap.add_argument("--seed", type=int, default=11, help="--workload matrix: generator seed")
-    ap.add_argument("--no-baselines", action="store_true")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
-    ap.add_argument("--no-cold", action="store_true",
-                    help="skip the cold-cache timing (copies of plan, B and C beyond the Infinity Cache, in turn)")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
-    args = ap.parse_args()
-    if args.gpus == 1 and args.workload == "narrow":
-        return run_sweep(args, cols=(4, 8, 16), narrow=True)
-    if args.gpus == 1 and args.workload == "sparsity":
-        return run_sweep(args, cols=(64, 4), square512=True)
-    if args.gpus == 1 and args.workload == "ffn-all":
-        return run_sweep(args, ffn=True)
-    if args.gpus == 1 and args.workload in ("sweep", "ablation", "tune"):
-        return {"sweep": run_sweep, "ablation": run_ablation, "tune": run_tune}[args.workload](args)
-    if args.gpus != 1:
-        raise SystemExit("this build runs on one GPU only: the path would shard by rows of A (each GPU "
-                         "plans and multiplies its own row range, B replicated), but no multi-GPU run "
-                         "exists; use --gpus 1")
+def kernel_report(torch, csr, plan, info, B, C, N, workload_key, samples=20):
+    """Roofline block of one launch: algorithmic bytes over the launch's average duration
+    (HIP events on the launch stream) against the HBM peak, the rate of wave-wide loads of
+    B rows against the measured gather ceiling, the share of the fp32 vector peak."""
+    nnz = int(csr.row_ptr[-1])
+    avg_ms, med_ms = time_execute(torch, plan, B, C, N, samples=samples)
+    bmin = bytes_min(csr.M, csr.K, nnz, N)
+    achieved = bmin / (avg_ms * 1e-3) / 1e9
+    kernel_tflops = 2.0 * nnz * N / (avg_ms * 1e-3) / 1e12
+    traffic, prov = measured_traffic(workload_key, N)
+    shape = kernel_shape(N, info["ufi"], csr.K)
+    roofline = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic, "traffic_source": prov,
+                "kernel": "spmm_chunks_kernel<UFI=%d,%s> (bCols %d)" % (info["ufi"], shape, N),
+                "cache_state": "hot",
+                "avg_launch_us": round(avg_ms * 1e3, 3), "median_launch_us": round(med_ms * 1e3, 3),
+                "launches_per_execute": 1, "algorithmic_bytes": bmin, "kernel_tflops": round(kernel_tflops, 3),
+                "frac_of_fp32_valu_peak": round(kernel_tflops / FP32_VALU_PEAK_TFLOPS, 5)}
+    # On-chip gather: each chunk of 8 enumerated columns costs 8 / S wave-wide loads of B
+    # rows (S rows of B per load); the ceiling is the rate the gather microbenchmark
+    # reaches on distinct rows of an L2-resident B.
+    S = {"S=2": 2, "S=4": 4, "S=8": 8}[shape[:3]]
+    tiles = 2 if tiles_of_64(N, csr.K) else 1
+    wave_loads = info["n_chunks"] * 8 // S * tiles
+    roofline["gather"] = {"wave_loads_per_launch": wave_loads,
+                          "g_wave_loads_per_s": round(wave_loads / (avg_ms * 1e-3) / 1e9, 2),
+                          "measured_ceiling": GATHER_CEILING_GWLS,
+                          "frac": round(wave_loads / (avg_ms * 1e-3) / 1e9 / GATHER_CEILING_GWLS, 4)}
+    return roofline
 
+
+def cpu_baseline(csr, cols, gen, skip=False):
+    """The oracle as it stands (row-parallel build of the same source), same products,
+    host cores of this machine, on a bounded sample: whole passes until about 1.5 s of wall
+    time have gone by (with 16 threads some 24 s of CPU work)."""
+    from oracle import spmm_oracle
+    nnz = int(csr.row_ptr[-1])
+    host_B = {N: gen.activations_for(csr, N) for N in cols}
+    cap_rows = csr.M
+    sample = "full workload"
+    if nnz * sum(cols) > 4e9:  # bound the CPU work to roughly 10-30 s
+        cap_rows = max(4, int(csr.M * 4e9 / (nnz * sum(cols))) // 4 * 4)
+        sample = "first %d of %d rows" % (cap_rows, csr.M)
+    sub_ptr = csr.row_ptr[:cap_rows + 1]
+    sub_nnz = int(sub_ptr[-1])
+    passes, spent = 0, 0.0
+    while not skip and (passes < 3 or spent < 1.5) and passes < 5000:
+        t0 = time.perf_counter()
+        for N in cols:
+            spmm_oracle.spmm(sub_ptr, csr.col_idx[:sub_nnz], csr.vals[:sub_nnz], host_B[N],
+                             K=csr.K, want_abs=False, parallel=True)
+        spent += time.perf_counter() - t0
+        passes += 1
+    return {"value": round(2.0 * sub_nnz * sum(cols) * passes / spent / 1e9, 3) if passes else None, "unit": "GFLOP/s",
+            "cores": spmm_oracle.threads(True), "kind": "oracle",
+            "sample": "%s, %d passes in %.2f s, double accumulation, OpenMP over rows" % (sample, passes, spent)}
+
+
+PLAN_KEYS = ("ufi", "ufk", "group_nnz", "group_panels", "n_groups", "n_blocks", "n_split", "n_enum", "n_chunks",
+             "device_bytes", "sorted_rows")
+
+
+def run_headline(args):
+    """The default workload: configuration 4 (48 magnitude-pruned matrices x bCols
+    32/64/128, the sweep the metric and its comparison with hipSPARSE are stated on)
+    together with configuration 3 (the 16384 x 16384 stress matrix at bCols 128, the
+    largest single launch, on which the roofline figures are taken).  A step is one pass
+    over all 145 products, every plan, B and C resident in HBM."""
+    import numpy as np
+    import torch
+    import paper_2506_15174_amd as spmm
+    from workloads import generators as gen
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    t_start = time.perf_counter()
+    cols = (32, 64, 128)
+    resident = []
+    points = _measure_points(torch, np, spmm, gen, gen.sweep_entries(), cols, gen.sweep_matrix, keep=resident,
+                             with_baselines=not args.no_baselines)
+    summary = _summarise(points, cols)
+    sweep_flops = sum(2.0 * r["nnz"] * r["N"] for r in points)
+    sweep_s = sum(r["us"] for r in points) * 1e-6
+
+    # the stress product: roofline figures on the largest launch of the batch
+    csr = gen.stress()
+    nnz = int(csr.row_ptr[-1])
+    Ns = 128
+    t0 = time.perf_counter()
+    plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, n_hint=Ns)
+    plan_s = time.perf_counter() - t0
+    info = plan.describe()
+    B = torch.from_numpy(gen.activations_for(csr, Ns)).cuda()
+    C = torch.empty((csr.M, Ns), dtype=torch.float32, device="cuda")
+    resident.append((plan, B, C, Ns, nnz))
+    hot = kernel_report(torch, csr, plan, info, B, C, Ns, "stress")
+    roofline = dict(hot)
+    cold = None if args.no_cold else time_execute_cold(torch, csr, plan, B, Ns)
+    if cold is not None:
+        # roofline claims are made on the cold figure: plan, B and C of every call come from HBM
+        bmin = hot["algorithmic_bytes"]
+        achieved = bmin / (cold["mean_us"] * 1e-6) / 1e9
+        tflops = 2.0 * nnz * Ns / (cold["mean_us"] * 1e-6) / 1e12
+        roofline.update({"achieved": round(achieved, 2), "frac": round(achieved / HBM_PEAK_GBS, 5),
+                         "cache_state": "cold: %d copies of plan, B and C in turn, %d MiB together"
+                                        % (cold["copies"], cold["working_set_bytes"] >> 20),
+                         "avg_launch_us": cold["mean_us"], "median_launch_us": cold["us"],
+                         "kernel_tflops": round(tflops, 3),
+                         "frac_of_fp32_valu_peak": round(tflops / FP32_VALU_PEAK_TFLOPS, 5),
+                         "hot": {k: hot[k] for k in ("achieved", "frac", "avg_launch_us", "median_launch_us",
+                                                     "kernel_tflops")}})
+        g = roofline["gather"]
+        rate = g["wave_loads_per_launch"] / (cold["mean_us"] * 1e-6) / 1e9
+        roofline["gather"] = dict(g, g_wave_loads_per_s=round(rate, 2), frac=round(rate / GATHER_CEILING_GWLS, 4))
+    stress_base = {} if args.no_baselines else measure_baselines(torch, np, csr, (Ns,), {Ns: B}).get(str(Ns), {})
+
+    # the timed steps: one pass over every product of the batch, launched back to back
+    st = torch.cuda.current_stream().cuda_stream or None
+    calls = [(p, b.data_ptr(), n, c.data_ptr()) for (p, b, c, n, _) in resident]
+
+    def step():
+        for p, pb, n, pc in calls:
+            p.execute_raw(pb, n, pc, st)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    flops_step = sum(2.0 * z * n for (_, _, _, n, z) in resident)
+    value = flops_step / (ms_per_step * 1e-3) / 1e9
+
+    cpu = cpu_baseline(csr, (Ns,), gen, skip=args.no_cpu)
+    out = {"metric": "fp32 CSR SpMM GFLOP/s (2*nnz*bCols)", "value": round(value, 2), "unit": "GFLOP/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "sweep: 48 magnitude-pruned matrices x bCols 32/64/128 (configs[4]) + stress "
+                                  "16384x16384 @95% Zipf(1.5) rows, 5% empty, bCols 128 (configs[3]); one step = "
+                                  "all 145 products",
+                      "products_per_step": len(resident), "flops_per_step": flops_step,
+                      "sweep_only": {"gflops_from_per_launch_medians": round(sweep_flops / sweep_s / 1e9, 2),
+                                     "sum_of_launch_medians_ms": round(sweep_s * 1e3, 4)},
+                      "stress": {"M": csr.M, "K": csr.K, "nnz": nnz, "bCols": Ns,
+                                 "plan": {k: info[k] for k in PLAN_KEYS}, "plan_create_s": round(plan_s, 4),
+                                 "row_stats": gen.row_stats(csr), "cold": cold,
+                                 "hipsparse_best_us": stress_base.get("hipsparse_best_us"),
+                                 "rocblas_sgemm_us": stress_base.get("rocblas_sgemm_us")},
+                      "wall_s": round(time.perf_counter() - t_start, 1)},
+           "roofline": roofline, "cpu_baseline": cpu, "summary": summary, "points": points}
+    print(json.dumps(out))
+
+
+def run_single(args):
     import numpy as np
     import torch
     import paper_2506_15174_amd as spmm
@@ -498,7 +666,8 @@ def main():
     t0 = time.perf_counter()
     # one plan per column count: the schedule constants are chosen per bCols, as the
     # paper's tuner does (Section 3.5)
-    plans = {N: spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, n_hint=N) for N in cols}
+    plans = {N: spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, n_hint=N, ufi=args.ufi,
+                                 depth=args.depth) for N in cols}
     plan_s = (time.perf_counter() - t0) / len(cols)
     infos = {N: plans[N].describe() for N in cols}
 
@@ -510,13 +679,10 @@ def main():
     st = torch.cuda.current_stream().cuda_stream or None
     calls = {N: (plans[N], Bs[N].data_ptr(), N, Cs[N].data_ptr()) for N in cols}
 
-    def run(N):
-        plan, pb, n, pc = calls[N]
-        plan.execute_raw(pb, n, pc, st)
-
     def step():
         for N in cols:
-            run(N)
+            plan, pb, n, pc = calls[N]
+            plan.execute_raw(pb, n, pc, st)
 
     for _ in range(args.warmup):
         step()
@@ -533,27 +699,7 @@ def main():
     # dominant kernel: the widest column count; one launch per execute there (column tiles
     # of one width share a launch)
     Nd = max(cols)
-    avg_ms, med_ms = time_execute(torch, plans[Nd], Bs[Nd], Cs[Nd], Nd, samples=20)
-    launches = 1
-    bmin = bytes_min(csr.M, csr.K, nnz, Nd)
-    achieved = bmin / (avg_ms * 1e-3) / 1e9
-    kernel_tflops = 2.0 * nnz * Nd / (avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": measured_traffic(args.workload, Nd),
-                "kernel": "spmm_chunks_kernel<UFI=%d,%s> (bCols %d)" % (infos[Nd]["ufi"], kernel_shape(Nd, infos[Nd]["ufi"], csr.K), Nd),
-                "avg_launch_us": round(avg_ms * 1e3, 3), "median_launch_us": round(med_ms * 1e3, 3),
-                "launches_per_execute": launches, "algorithmic_bytes": bmin, "kernel_tflops": round(kernel_tflops, 3),
-                "frac_of_fp32_valu_peak": round(kernel_tflops / FP32_VALU_PEAK_TFLOPS, 5)}
-
-    # On-chip gather: each chunk of 8 enumerated columns costs 8 / S wave-wide loads of B
-    # rows (S rows of B per load); the ceiling is the rate the gather microbenchmark
-    # reaches on distinct rows of an L2-resident B.
-    S = {"S=2": 2, "S=4": 4, "S=8": 8}[kernel_shape(Nd, infos[Nd]["ufi"], csr.K)[:3]]
-    wave_loads = infos[Nd]["n_chunks"] * 8 // S
-    roofline["gather"] = {"wave_loads_per_launch": wave_loads,
-                          "g_wave_loads_per_s": round(wave_loads / (avg_ms * 1e-3) / 1e9, 2),
-                          "measured_ceiling": GATHER_CEILING_GWLS,
-                          "frac": round(wave_loads / (avg_ms * 1e-3) / 1e9 / GATHER_CEILING_GWLS, 4)}
+    roofline = kernel_report(torch, csr, plans[Nd], infos[Nd], Bs[Nd], Cs[Nd], Nd, args.workload)
 
     per_cols = {}
     for N in cols:
@@ -579,43 +725,55 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    # CPU baseline: the oracle as it stands (row-parallel build of the same
-    # source), same products, host cores of this machine.
-    from oracle import spmm_oracle
-    host_B = {N: gen.activations_for(csr, N) for N in cols}
-    cap_rows = csr.M
-    sample = "full workload"
-    if nnz * sum(cols) > 4e9:  # bound the CPU work to roughly 10-30 s
-        cap_rows = max(4, int(csr.M * 4e9 / (nnz * sum(cols))) // 4 * 4)
-        sample = "first %d of %d rows" % (cap_rows, csr.M)
-    sub_ptr = csr.row_ptr[:cap_rows + 1]
-    sub_nnz = int(sub_ptr[-1])
-    # whole passes over the sample until about 1.5 s of wall time have gone by (with 16
-    # threads some 24 s of CPU work): a single pass of a small workload is a few
-    # milliseconds, too short for a steady figure
-    passes, spent = 0, 0.0
-    while not args.no_cpu and (passes < 3 or spent < 1.5) and passes < 5000:
-        t0 = time.perf_counter()
-        for N in cols:
-            spmm_oracle.spmm(sub_ptr, csr.col_idx[:sub_nnz], csr.vals[:sub_nnz], host_B[N],
-                             K=csr.K, want_abs=False, parallel=True)
-        spent += time.perf_counter() - t0
-        passes += 1
-    cpu = {"value": round(2.0 * sub_nnz * sum(cols) * passes / spent / 1e9, 3) if passes else None, "unit": "GFLOP/s",
-           "cores": spmm_oracle.threads(True), "kind": "oracle",
-           "sample": "%s, %d passes in %.2f s, double accumulation, OpenMP over rows" % (sample, passes, spent)}
-
+    cpu = cpu_baseline(csr, cols, gen, skip=args.no_cpu)
     out = {"metric": "fp32 CSR SpMM GFLOP/s (2*nnz*bCols)", "value": round(value, 2), "unit": "GFLOP/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
            "data": "synthetic",
            "config": {"workload": label, "M": csr.M, "K": csr.K, "nnz": nnz, "bCols": list(cols),
-                      "plans": {str(N): {k: infos[N][k] for k in ("ufi", "ufk", "group_nnz", "group_panels", "n_groups",
-                                                                  "n_blocks", "n_split", "n_enum", "n_chunks",
-                                                                  "device_bytes")} for N in cols},
+                      "plans": {str(N): {k: infos[N][k] for k in PLAN_KEYS} for N in cols},
                       "plan_create_s": round(plan_s, 4), "row_stats": gen.row_stats(csr)},
            "roofline": roofline, "cpu_baseline": cpu, "per_bcols": per_cols, "baselines": baselines}
     print(json.dumps(out))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="headline",
+                    help="headline (default: sweep + stress) | conv | stress | ffn | ffn-all | matrix | sweep | "
+                         "narrow | sparsity | ablation | tune")
+    ap.add_argument("--shape", default="4096x4096", help="--workload matrix: rows x columns of A")
+    ap.add_argument("--sparsity", type=float, default=0.5, help="--workload matrix: pruned share")
+    ap.add_argument("--bcols", type=int, default=128, help="--workload matrix: columns of B")
+    ap.add_argument("--seed", type=int, default=11, help="--workload matrix: generator seed")
+    ap.add_argument("--ufi", type=int, default=0, help="single workloads: force the rows per panel (1, 2, 4, 8)")
+    ap.add_argument("--depth", type=int, default=0,
+                    help="single workloads: chunks of B rows in flight per wave (1, 2, 3, 4, 8; 0 = tuned)")
+    ap.add_argument("--no-baselines", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-cold", action="store_true",
+                    help="skip the cold-cache timing (copies of plan, B and C beyond the Infinity Cache, in turn)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("this build runs on one GPU only: the path would shard by rows of A (each GPU "
+                         "plans and multiplies its own row range, B replicated), but no multi-GPU run "
+                         "exists; use --gpus 1")
+    if args.workload == "headline":
+        return run_headline(args)
+    if args.workload == "narrow":
+        return run_sweep(args, cols=(4, 8, 16), narrow=True)
+    if args.workload == "sparsity":
+        return run_sweep(args, cols=(64, 4), square512=True)
+    if args.workload == "ffn-all":
+        return run_sweep(args, ffn=True)
+    if args.workload in ("sweep", "ablation", "tune"):
+        return {"sweep": run_sweep, "ablation": run_ablation, "tune": run_tune}[args.workload](args)
+    return run_single(args)
 
 
 if __name__ == "__main__":

@@ -69,6 +69,14 @@ typedef struct {
                               (C is still written in the caller's row order); < 0: keep the row
                               order; 0: sort when the rows longer than four times the mean hold
                               a quarter of the entries and the chosen panels are taller than one row */
+    int32_t force_wide;    /* nonzero: spmm_execute uses the 64-bit addressing kernels also where B
+                              is small enough for 32-bit offsets (lets small inputs exercise them) */
+    int32_t threads;       /* host threads of the inspector, 1..64 (0 = one per two million entries,
+                              at most 16 and at most the machine's; the plan does not depend on it) */
+    int32_t depth;         /* chunks of B rows a wave keeps in flight (the software pipeline's depth,
+                              the paper's unroll(k, UFk) axis of Figure 2): 1, 2, 3, 4 or 8;
+                              0 = the depth tuned per kernel instance.  A depth the register budget
+                              of an instance cannot hold is lowered to the deepest one it can. */
 } spmm_options_t;
 
 /*
@@ -99,14 +107,9 @@ spmm_status_t spmm_plan_create(spmm_plan_t **plan, int64_t M, int64_t K,
                                const float *vals);
 
 /*
- * Same, with explicit settings (opts may be NULL).  For experiments the
- * environment variables SPMM_UFI, SPMM_GROUP_NNZ, SPMM_GROUP_PANELS and
- * SPMM_SORT_ROWS set the corresponding field wherever the caller left it 0
- * (this is how bench.py forces a panel height for counter runs),
- * SPMM_FORCE_WIDE=1 makes spmm_execute use
- * the 64-bit addressing kernels on inputs that do not need them, and
- * SPMM_THREADS sets the number of host threads the inspector uses (by default
- * one per two million entries, at most 16; the plan does not depend on it).
+ * Same, with explicit settings (opts may be NULL = all zero).  The settings are
+ * the only way to steer the inspector: the library reads no environment
+ * variable.
  */
 spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
                                   const int32_t *row_ptr, const int32_t *col_idx,

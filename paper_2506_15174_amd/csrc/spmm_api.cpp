@@ -4,7 +4,6 @@
 
 #include <hip/hip_runtime_api.h>
 
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -22,17 +21,11 @@ struct spmm_plan {
     uint32_t *d_stream = nullptr, *d_wins = nullptr, *d_items = nullptr, *d_rowmap = nullptr;
     int64_t device_bytes = 0;
     int64_t stream_words = 0;  // length of host.stream at creation (a device plan drops its host mirror)
-    bool force_wide = false;  // test hook: exercise the 64-bit addressing kernels on small inputs
+    bool force_wide = false;  // spmm_options_t.force_wide: 64-bit addressing kernels also on small inputs
+    int depth = 0;            // spmm_options_t.depth: pipeline depth asked for (0 = per-instance default)
 };
 
 namespace {
-
-int env_int(const char *name)
-{
-    const char *s = std::getenv(name);
-    if (!s || !*s) return 0;
-    return std::atoi(s);
-}
 
 spmm_status_t hip_fail()
 {
@@ -81,21 +74,25 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
     if (!plan) return SPMM_ERR_INVALID_ARG;
     *plan = nullptr;
     InspectorOptions io;
-    io.group_nnz = env_int("SPMM_GROUP_NNZ");
-    io.group_panels = env_int("SPMM_GROUP_PANELS");
-    io.ufi = env_int("SPMM_UFI");
-    io.sort_rows = env_int("SPMM_SORT_ROWS");
-    bool host_only = false;
+    bool host_only = false, force_wide = false;
+    int depth = 0;
     if (opts) {
         if (opts->group_nnz < 0 || opts->group_panels < 0 || opts->n_hint < 0) return SPMM_ERR_INVALID_ARG;
         if (opts->ufi != 0 && opts->ufi != 1 && opts->ufi != 2 && opts->ufi != 4 && opts->ufi != 8)
             return SPMM_ERR_INVALID_ARG;
-        if (opts->ufi > 0) io.ufi = opts->ufi;
-        if (opts->group_nnz > 0) io.group_nnz = opts->group_nnz;
-        if (opts->group_panels > 0) io.group_panels = opts->group_panels;
+        if (opts->threads < 0 || opts->threads > 64) return SPMM_ERR_INVALID_ARG;
+        if (opts->depth != 0 && opts->depth != 1 && opts->depth != 2 && opts->depth != 3 && opts->depth != 4 &&
+            opts->depth != 8)
+            return SPMM_ERR_INVALID_ARG;
+        io.ufi = opts->ufi;
+        io.group_nnz = opts->group_nnz;
+        io.group_panels = opts->group_panels;
         host_only = opts->host_only != 0;
         io.n_hint = opts->n_hint;
-        if (opts->sort_rows != 0) io.sort_rows = opts->sort_rows;
+        io.sort_rows = opts->sort_rows;
+        io.threads = opts->threads;
+        force_wide = opts->force_wide != 0;
+        depth = opts->depth;
     }
     spmm_plan *p = new (std::nothrow) spmm_plan();
     if (!p) return SPMM_ERR_ALLOC;
@@ -104,7 +101,8 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
         delete p;
         return (spmm_status_t)rc;
     }
-    p->force_wide = env_int("SPMM_FORCE_WIDE") != 0;
+    p->force_wide = force_wide;
+    p->depth = depth;
     if (!host_only) {
         if (hipGetDevice(&p->device) != hipSuccess) {
             delete p;
@@ -211,7 +209,7 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
         a.n_tiles = n_tiles;
         const uint64_t skipped = (uint64_t)j0 * 4u;
         a.b_bytes = wide || b_total <= skipped ? 0u : (uint32_t)(b_total - skipped);
-        const int e = spmm_launch_chunks(a, h.ufi, slices, wide, stream);
+        const int e = spmm_launch_chunks(a, h.ufi, slices, wide, plan->depth, stream);
         if (e != 0) return SPMM_ERR_HIP;
         j0 += cols;
     }

@@ -6,8 +6,8 @@
 // the values are stored in the order the kernel consumes them, one column index
 // is stored per *enumerated column* (a column of a panel of UFI rows together
 // with its nonzero pattern, Section 3.2), and the enumerated columns of a panel
-// that share a pattern are stored next to each other ("a list of pointers to the
-// same pattern", Section 3.2.2).  Each such run is cut into *chunks* of at most
+// that share a pattern are stored next to each other (the per-pattern column
+// lists of Section 3.2.2).  Each such run is cut into *chunks* of at most
 // UFK columns; a chunk is the unit the kernel keeps in flight (the paper's
 // unroll(k, UFk), Section 3.3.2).  Where the paper launches one thread block per
 // (panel, pattern) and meets in C with atomics, one wave here walks all chunks

@@ -22,10 +22,15 @@ struct spmm_launch_args {
     uint32_t lds_pad = 0;   // extra LDS bytes per workgroup (never touched): caps the workgroups per CU
 };
 
-// Enqueues one launch of n_tiles column tiles.  ufi = rows per panel of the plan (1, 2, 4, 8).  slices = 2 / 4 / 8: four columns per lane, tile of up
-// to 128 / 64 / 32 columns (width a multiple of 4, B and C 16-byte aligned);
-// slices = 1: one column per lane, tile of up to 64 columns, any alignment.
-// wide = 64-bit addressing of B.  Returns the hipError_t of the launch as int.
-int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int slices, bool wide, void *stream);
+// Enqueues one launch of n_tiles column tiles.  ufi = rows per panel of the plan (1, 2, 4, 8).
+// slices = 2 / 4 / 8: four columns per lane (16-byte loads and stores at 4-byte alignment;
+// the last lane of a tile may own fewer than four columns), tile of up to 128 / 64 / 32
+// columns; slices = 1: one column per lane, tile of up to 64 columns.  wide = 64-bit
+// addressing of B.  depth = chunks of B rows in flight (0 or anything deeper than the
+// instance's tuned depth = the tuned depth).  Returns the hipError_t of the launch as int.
+int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int slices, bool wide, int depth, void *stream);
+
+// The pipeline depth an instance is tuned for.
+int spmm_default_depth(int ufi, int slices);
 
 #endif

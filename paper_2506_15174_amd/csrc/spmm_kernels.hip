@@ -443,33 +443,61 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
     }
 }
 
+template <int U, int S, int VW, int D, bool WIDE> void launch_instance(const spmm_launch_args &a, void *stream)
+{
+    hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE>), dim3((unsigned)a.n_blocks, (unsigned)a.n_tiles),
+                       dim3(64 * WAVES_PER_WG), a.lds_pad, (hipStream_t)stream, a.stream, a.wins, a.items, a.rowmap,
+                       a.B, a.b_bytes, a.C, a.ldn, a.width, a.tile_cols, a.col_mask);
+}
+
+// One (height, slices) pair at the pipeline depth asked for.  DMAX is the depth the
+// instance is tuned for (as deep as its register budget allows); a caller may ask for a
+// shallower pipeline (1, 2, 3, 4, 8: the loads-in-flight axis of the paper's Figure 2),
+// a deeper request runs at DMAX.  The 64-bit addressing kernels exist at DMAX only.
+template <int U, int S, int VW, int DMAX, bool WIDE> void launch_depth(const spmm_launch_args &a, int depth, void *stream)
+{
+    if constexpr (!WIDE) {
+        if (depth == 1 && DMAX > 1) return launch_instance<U, S, VW, 1, WIDE>(a, stream);
+        if (depth == 2 && DMAX > 2) return launch_instance<U, S, VW, 2, WIDE>(a, stream);
+        if (depth == 3 && DMAX > 3) return launch_instance<U, S, VW, (DMAX > 3 ? 3 : DMAX), WIDE>(a, stream);
+        if (depth == 4 && DMAX > 4) return launch_instance<U, S, VW, (DMAX > 4 ? 4 : DMAX), WIDE>(a, stream);
+    }
+    launch_instance<U, S, VW, DMAX, WIDE>(a, stream);
+}
+
+// Pipeline depths per height (D2, D4, D8 for 2, 4, 8 slices): as deep as the VGPRs of a
+// wave allow.  The eight-row tile holds 32 accumulators, which leaves room for fewer B
+// rows in flight.
+template <int U, int D2, int D4, int D8> void launch_slices(const spmm_launch_args &a, int slices, bool wide, int depth, void *stream)
+{
+    switch (slices) {
+    case 2: wide ? launch_depth<U, 2, 4, D2, true>(a, depth, stream) : launch_depth<U, 2, 4, D2, false>(a, depth, stream); break;
+    case 4: wide ? launch_depth<U, 4, 4, D4, true>(a, depth, stream) : launch_depth<U, 4, 4, D4, false>(a, depth, stream); break;
+    case 8: wide ? launch_depth<U, 8, 4, D8, true>(a, depth, stream) : launch_depth<U, 8, 4, D8, false>(a, depth, stream); break;
+    default: wide ? launch_depth<U, 1, 1, 3, true>(a, depth, stream) : launch_depth<U, 1, 1, 3, false>(a, depth, stream); break;
+    }
+}
+
 }  // namespace
 
-#define SPMM_LAUNCH(U, S, VW, D, WIDE)                                                                \
-    hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE>),                                       \
-                       dim3((unsigned)a.n_blocks, (unsigned)a.n_tiles), dim3(64 * WAVES_PER_WG),       \
-                       a.lds_pad, (hipStream_t)stream, a.stream, a.wins, a.items, a.rowmap, a.B,       \
-                       a.b_bytes, a.C, a.ldn, a.width, a.tile_cols, a.col_mask)
-
-// Pipeline depths: as deep as the 128 VGPRs of a wave allow.  The eight-row tile
-// holds 32 accumulators, which leaves room for fewer B rows in flight.
-#define SPMM_LAUNCH_SLICES(U, D2, D4, D8)                                                             \
-    switch (slices) {                                                                                 \
-    case 2: if (wide) SPMM_LAUNCH(U, 2, 4, D2, true); else SPMM_LAUNCH(U, 2, 4, D2, false); break;    \
-    case 4: if (wide) SPMM_LAUNCH(U, 4, 4, D4, true); else SPMM_LAUNCH(U, 4, 4, D4, false); break;    \
-    case 8: if (wide) SPMM_LAUNCH(U, 8, 4, D8, true); else SPMM_LAUNCH(U, 8, 4, D8, false); break;    \
-    default: if (wide) SPMM_LAUNCH(U, 1, 1, 3, true); else SPMM_LAUNCH(U, 1, 1, 3, false); break;     \
-    }
-
-int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int slices, bool wide, void *stream)
+// The depth table (instances per height: 2, 4, 8 slices): kept in step with
+// spmm_default_depth below.
+int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int slices, bool wide, int depth, void *stream)
 {
     if (a.n_blocks <= 0 || a.n_tiles <= 0) return 0;
     switch (ufi) {
-    case 8: SPMM_LAUNCH_SLICES(8, 2, 4, 4) break;
-    case 4: SPMM_LAUNCH_SLICES(4, 3, 3, 4) break;
-    case 2: SPMM_LAUNCH_SLICES(2, 3, 4, 6) break;
-    case 1: SPMM_LAUNCH_SLICES(1, 3, 4, 8) break;
+    case 8: launch_slices<8, 2, 4, 4>(a, slices, wide, depth, stream); break;
+    case 4: launch_slices<4, 3, 3, 4>(a, slices, wide, depth, stream); break;
+    case 2: launch_slices<2, 3, 4, 6>(a, slices, wide, depth, stream); break;
+    case 1: launch_slices<1, 3, 4, 8>(a, slices, wide, depth, stream); break;
     default: return (int)hipErrorInvalidValue;
     }
     return (int)hipGetLastError();
+}
+
+int spmm_default_depth(int ufi, int slices)
+{
+    static const int table[4][3] = {{3, 4, 8}, {3, 4, 6}, {3, 3, 4}, {2, 4, 4}};  // rows: height 1, 2, 4, 8
+    const int u = ufi == 8 ? 3 : ufi == 4 ? 2 : ufi == 2 ? 1 : 0;
+    return slices == 2 ? table[u][0] : slices == 4 ? table[u][1] : slices == 8 ? table[u][2] : 3;
 }

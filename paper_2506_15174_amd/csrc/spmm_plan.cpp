@@ -15,7 +15,6 @@
 #include <algorithm>
 #include <cstring>
 #include <new>
-#include <cstdlib>
 #include <numeric>
 #include <system_error>
 #include <thread>
@@ -307,16 +306,13 @@ std::vector<Group> make_groups(const int32_t *row_ptr, int64_t M, int ufi, int64
 }
 
 // Threads the enumeration may use: one per 2 M entries, at most 16 and at most what
-// the machine has (SPMM_THREADS overrides, for tests).
-int worker_count(int64_t nnz)
+// the machine has, unless the caller names a count.
+int worker_count(int64_t nnz, int32_t asked)
 {
+    if (asked >= 1) return std::min(asked, 64);
     int64_t n = std::min<int64_t>(16, std::max<int64_t>(1, nnz / (2 << 20)));
     const unsigned hw = std::thread::hardware_concurrency();
     if (hw > 0) n = std::min<int64_t>(n, hw);
-    if (const char *s = std::getenv("SPMM_THREADS")) {
-        const int v = std::atoi(s);
-        if (v >= 1) n = std::min(v, 64);
-    }
     return (int)n;
 }
 
@@ -543,7 +539,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                 gi = g_last + 1;
             }
         };
-        std::vector<int64_t> cuts = range_cuts(groups, worker_count(nnz));
+        std::vector<int64_t> cuts = range_cuts(groups, worker_count(nnz, opts.threads));
         const size_t n_ranges = cuts.size() - 1;
         std::vector<Emitter> parts(n_ranges);
         for (size_t t = 0; t < n_ranges; ++t) {
@@ -564,8 +560,8 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
             auto job = [&](size_t t) {
                 try {
                     emit_range(cuts[t], cuts[t + 1], parts[t]);
-                } catch (const std::bad_alloc &) {
-                    failed[t] = 1;
+                } catch (...) {
+                    failed[t] = 1;  // no exception may leave a thread: reported as an allocation failure below
                 }
             };
             for (size_t t = 0; t < n_ranges; ++t) {
@@ -745,7 +741,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         // the windows' words, contiguous runs of placed groups per thread
         out.stream.resize((size_t)stream_at + STREAM_TAIL_PAD, 0u);
         {
-            const int want = worker_count(nnz);
+            const int want = worker_count(nnz, opts.threads);
             const size_t n_placed = placed.size();
             std::vector<size_t> from{0};
             for (int t = 1; t < want; ++t) {
@@ -759,8 +755,8 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                 from.push_back(lo);
             }
             from.push_back(n_placed);
-            auto fill_range = [&](size_t a, size_t b) {
-                for (size_t i = a; i < b; ++i) fill_group(placed[i]);
+            auto fill_range = [&](size_t a, size_t b) noexcept {
+                for (size_t i = a; i < b; ++i) fill_group(placed[i]);  // copies into sized arrays: nothing throws
             };
             if (want == 1) {
                 fill_range(0, n_placed);
@@ -783,6 +779,9 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
     } catch (const std::bad_alloc &) {
         out = HostPlan();
         return ST_ALLOC;
+    } catch (...) {
+        out = HostPlan();  // length errors of the containers and the like: the input is too large to lay out
+        return ST_UNSUPPORTED;
     }
     return ST_OK;
 }

@@ -34,6 +34,7 @@ struct InspectorOptions {
     int32_t ufi = 0;           // 0 = choose; else 1, 2, 4 or 8
     int32_t n_hint = 0;        // B columns the plan is meant for; 0 = unknown
     int32_t sort_rows = 0;     // 0 = choose; > 0 = sort rows by length; < 0 = keep the row order
+    int32_t threads = 0;       // 0 = choose; else host threads of the enumeration (1..64)
 };
 
 // Status codes follow spmm_status_t (0 ok, 1 invalid argument, 2 invalid CSR,

@@ -243,11 +243,14 @@ def walk_chunks(it, hdr, stream, wins):
     assert c == chunk0 + nchunks
 
 
-def decode_plan(items, hdr, stream, wins, ufi, rowmap=None):
+def decode_plan(items, hdr, stream, wins, ufi, rowmap=None, K=0):
     """Chunk arrays -> (row, col, value bits) arrays in the order the kernel
     consumes them.  Also checks the structural invariants of the format and
-    raises AssertionError on any violation."""
+    raises AssertionError on any violation.  K: columns of the matrix; beyond 2^24
+    columns a column word is all index (no slot pattern in its top byte)."""
     check_blocks(items, ufi, rowmap)
+    wide_cols = K > (1 << COL_PATTERN_SHIFT)
+    index_mask = 0xFFFFFFFF if wide_cols else COL_INDEX_MASK
     to_c = (lambda r: int(rowmap[r])) if rowmap is not None and len(rowmap) else (lambda r: r)
     items = items.reshape(-1, ITEM_WORDS)
     out_rows, out_cols, out_bits = [], [], []
@@ -268,15 +271,15 @@ def decode_plan(items, hdr, stream, wins, ufi, rowmap=None):
             rows_here = min(ufi, rows_left)
             assert pattern < (1 << rows_here), "pattern names a row beyond the panel"
             # a slot's own pattern: the top byte of its column word, or the chunk's
-            own = [(int(cc[u]) >> COL_PATTERN_SHIFT) or pattern for u in range(count)]
+            own = [pattern if wide_cols else (int(cc[u]) >> COL_PATTERN_SHIFT) or pattern for u in range(count)]
             union = 0
             for u in range(count):
                 assert own[u] & ~pattern == 0 and own[u] != 0, "a slot's pattern lies inside the chunk's"
-                assert (int(cc[u]) >> COL_PATTERN_SHIFT) != pattern, "a full slot pattern is stored as 0"
+                assert wide_cols or (int(cc[u]) >> COL_PATTERN_SHIFT) != pattern, "a full slot pattern is stored as 0"
                 union |= own[u]
             assert union == pattern, "the chunk's pattern is the union of its slots'"
             if count:
-                assert np.all((cc[count:] & COL_INDEX_MASK) == (cc[count - 1] & COL_INDEX_MASK)), \
+                assert np.all((cc[count:] & index_mask) == (cc[count - 1] & index_mask)), \
                     "unused slots repeat the last real column"
             t = 0
             for r in range(ufi):
@@ -288,7 +291,7 @@ def decode_plan(items, hdr, stream, wins, ufi, rowmap=None):
                 for u in range(count):
                     if (own[u] >> r) & 1:
                         out_rows.append(to_c(row + r))
-                        out_cols.append(int(cc[u]) & COL_INDEX_MASK)
+                        out_cols.append(int(cc[u]) & index_mask)
                         out_bits.append(int(block[u]))
                     else:
                         assert block[u] == 0, "a slot without the row holds a zero there"
@@ -302,7 +305,7 @@ def decode_plan(items, hdr, stream, wins, ufi, rowmap=None):
             np.array(out_bits, dtype=np.uint32))
 
 
-def interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap=None):
+def interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap=None, K=0):
     """Evaluates C from the chunk arrays in float32, block by block, chunk by
     chunk, FMA by FMA (row blocks in ascending row, slots in ascending order;
     pieces of a split panel added in slot order by the wave slot the table names).
@@ -312,6 +315,7 @@ def interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap=None):
     N = B.shape[1]
     C = np.full((M, N), np.nan, dtype=np.float32)
     B64 = B.astype(np.float64)
+    index_mask = 0xFFFFFFFF if K > (1 << COL_PATTERN_SHIFT) else COL_INDEX_MASK
     for blk in blocks:
         tiles = np.zeros((WAVES_PER_WG, ufi, N), dtype=np.float32)
         for w, it in enumerate(blk):
@@ -331,7 +335,7 @@ def interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap=None):
                     for u in range(UFK):
                         a = np.float64(fv[u])
                         # fused multiply-add: exact product and sum in double, one rounding
-                        acc[r] = (a * B64[cc[u] & COL_INDEX_MASK] + acc[r].astype(np.float64)).astype(np.float32)
+                        acc[r] = (a * B64[int(cc[u]) & index_mask] + acc[r].astype(np.float64)).astype(np.float32)
                 if end:
                     rows_here = min(ufi, rows_left)
                     if flags & FLAG_SPLIT:

@@ -19,7 +19,7 @@ def test_algorithmic_bytes_model():
 def test_kernel_label_follows_the_launch_table():
     src = open(os.path.join(ROOT, "paper_2506_15174_amd", "csrc", "spmm_kernels.hip")).read()
     table = {int(u): (int(d2), int(d4), int(d8))
-             for u, d2, d4, d8 in re.findall(r"case (\d): SPMM_LAUNCH_SLICES\(\d, (\d), (\d), (\d)\) break;", src)}
+             for u, d2, d4, d8 in re.findall(r"case (\d): launch_slices<\d, (\d), (\d), (\d)>\(", src)}
     assert sorted(table) == [1, 2, 4, 8]
     for ufi, (d2, d4, d8) in table.items():
         assert bench.kernel_shape(128, ufi) == "S=2,VW=4,D=%d" % d2

@@ -496,16 +496,75 @@ def test_random_matrices_and_settings_round_trip(seed):
     assert np.array_equal(C.astype(np.float64), dense @ B.astype(np.float64))
 
 
+@pytest.mark.parametrize("K", [(1 << 24) - 1, 1 << 24, (1 << 24) + 1, (1 << 24) + 77])
+@pytest.mark.parametrize("ufi", [1, 4])
+def test_column_words_at_and_beyond_the_24_bit_boundary(K, ufi):
+    """A column word keeps a slot pattern in its top byte only while every column index
+    fits 24 bits (K <= 2^24); beyond that the word is all index and leftovers of different
+    patterns never share a chunk.  Few entries, columns next to K - 1 and around 2^24,
+    rows that share and do not share columns; the plan decodes to the canonical CSR bit
+    for bit and its chunk arrays evaluate to the exact product."""
+    rng = np.random.default_rng(K % 1000 + ufi)
+    M = 11
+    near = [K - 1, K - 2, K - 3, (1 << 24) - 1, (1 << 24) - 2, 0, 1, 5, (1 << 23) + 3]
+    if K > (1 << 24):
+        near += [1 << 24]
+    near = sorted(set(c for c in near if 0 <= c < K))
+    rows = []
+    for i in range(M):
+        take = [c for c in near if rng.random() < 0.6]
+        extra = rng.integers(0, K, size=int(rng.integers(0, 12))).tolist()
+        rows.append(np.array(sorted(set(take + extra)), dtype=np.int32))
+    rows[4] = np.zeros(0, dtype=np.int32)
+    row_ptr = np.concatenate(([0], np.cumsum([len(r) for r in rows]))).astype(np.int32)
+    col_idx = np.concatenate(rows)
+    vals = rng.integers(-8, 9, len(col_idx)).astype(np.float32)
+    csr = gen.Csr(M, K, row_ptr, col_idx, vals)
+    plan = host_plan(csr, ufi=ufi, group_nnz=16)
+    info = plan.describe()
+    assert info["ufi"] == ufi and info["nnz"] == len(col_idx)
+    items, hdr, stream, wins = arrays(plan)
+    rows_d, cc, bits = decode_plan(items, hdr, stream, wins, ufi, K=K)
+    want_rows, want_cols, want_bits = canonical_csr(csr.row_ptr, csr.col_idx, csr.vals)
+    assert sorted(zip(rows_d.tolist(), cc.tolist(), bits.tolist())) == \
+        sorted(zip(want_rows.tolist(), want_cols.tolist(), want_bits.tolist()))
+    assert int(cc.max()) == K - 1
+    # which column words carry a slot pattern
+    col_words = []
+    for it in items.reshape(-1, 16):
+        if not int(it[5]) & 2:
+            for h, cw, _ in walk_chunks(it, hdr, stream, wins):
+                col_words += [int(w) for w in cw[:(h >> 8) & 15]]
+    tagged = [w for w in col_words if w >> 24]
+    if K > (1 << 24):
+        # all index: any top byte is part of a column number of 2^24 or more
+        assert all(w < K for w in col_words) and all(w >= (1 << 24) for w in tagged)
+        shared = [h for h in hdr[:info["n_chunks"]] if bin(int(h) & 255).count("1") > 1]
+        if ufi == 1:
+            assert not shared
+    elif ufi > 1:
+        assert tagged, "leftovers of different patterns share chunks and tag their slots"
+        assert all((w & 0xFFFFFF) < K for w in col_words)
+    B = np.zeros((K, 1), dtype=np.float32)
+    touched = np.unique(col_idx)
+    B[touched, 0] = rng.integers(-4, 5, len(touched)).astype(np.float32)
+    C = interpret_plan(items, hdr, stream, wins, B, M, ufi, K=K)
+    want = np.zeros((M, 1))
+    for i in range(M):
+        want[i, 0] = float(np.dot(vals[row_ptr[i]:row_ptr[i + 1]].astype(np.float64),
+                                  B[col_idx[row_ptr[i]:row_ptr[i + 1]], 0].astype(np.float64)))
+    assert np.array_equal(C.astype(np.float64), want)
+
+
 @pytest.mark.parametrize("name", ["heavy_tail", "lognormal", "uniform_half", "all_empty"])
-def test_plan_does_not_depend_on_the_number_of_inspector_threads(name, monkeypatch):
+def test_plan_does_not_depend_on_the_number_of_inspector_threads(name):
     """The inspector enumerates contiguous ranges of groups on several threads for large
-    inputs; SPMM_THREADS forces that on small ones.  Every array must come out the same."""
+    inputs; the `threads` setting forces that on small ones.  Every array must come out the same."""
     csr = CASES[name]()
     plans = {}
-    for threads in ("1", "2", "5", "64"):
-        monkeypatch.setenv("SPMM_THREADS", threads)
+    for threads in (1, 2, 5, 64):
         for ufi in (1, 4):
-            plan = host_plan(csr, ufi=ufi, group_nnz=40, sort_rows=1)
+            plan = host_plan(csr, ufi=ufi, group_nnz=40, sort_rows=1, threads=threads)
             got = [plan.get_array(w) for w in range(5)] + [plan.get_groups()]
             want = plans.setdefault(ufi, got)
             assert all(np.array_equal(x, y) for x, y in zip(got, want)), (threads, ufi)
