@@ -52,6 +52,9 @@ typedef struct {
     int64_t device_bytes;  /* device memory the plan holds (0 for a host-only plan) */
     int64_t sorted_rows;   /* 1: the plan's rows are the matrix's rows sorted by length, longest first
                               (SPMM_ARRAY_ROWMAP gives the order); 0: the plan's rows are the matrix's */
+    int64_t n_cross;       /* panels cut into more pieces than one workgroup has waves: their
+                              workgroups' sums meet in scratch memory of the plan */
+    int64_t scratch_bytes; /* that scratch memory (part of device_bytes); 0 when n_cross is 0 */
 } spmm_plan_info_t;
 
 /* Optional inspector settings; zero in a field means "let the inspector choose". */
@@ -77,6 +80,12 @@ typedef struct {
                               the paper's unroll(k, UFk) axis of Figure 2): 1, 2, 3, 4 or 8;
                               0 = the depth tuned per kernel instance.  A depth the register budget
                               of an instance cannot hold is lowered to the deepest one it can. */
+    int32_t cross;         /* whether a panel heavier than eight group budgets and than 1/1024 of all
+                              entries is cut across workgroups (their sums meet in scratch memory of
+                              the plan and a second, small launch adds them): < 0 never (no scratch,
+                              any number of executes of the plan may overlap); > 0 always; 0: when the
+                              row lengths are skewed (see sort_rows), A holds 2^20 entries or more and
+                              n_hint is 0 or above 32.  Such a plan also halves its group budget. */
 } spmm_options_t;
 
 /*

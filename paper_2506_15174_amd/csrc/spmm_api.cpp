@@ -19,6 +19,12 @@ struct spmm_plan {
     bool on_device = false;
     int device = -1;
     uint32_t *d_stream = nullptr, *d_wins = nullptr, *d_items = nullptr, *d_rowmap = nullptr;
+    // Panels cut across workgroups: one scratch slot of ufi x CROSS_ROW_FLOATS floats per
+    // (column tile of a launch, workgroup of such a panel), written by every execute, and the
+    // table of those panels.
+    float *d_cross_sums = nullptr;
+    uint32_t *d_cross_table = nullptr;
+    int64_t scratch_bytes = 0;
     int64_t device_bytes = 0;
     int64_t stream_words = 0;  // length of host.stream at creation (a device plan drops its host mirror)
     bool force_wide = false;  // spmm_options_t.force_wide: 64-bit addressing kernels also on small inputs
@@ -60,7 +66,10 @@ void release_device(spmm_plan *p)
     if (p->d_wins) (void)hipFree(p->d_wins);
     if (p->d_items) (void)hipFree(p->d_items);
     if (p->d_rowmap) (void)hipFree(p->d_rowmap);
-    p->d_stream = p->d_wins = p->d_items = p->d_rowmap = nullptr;
+    if (p->d_cross_sums) (void)hipFree(p->d_cross_sums);
+    if (p->d_cross_table) (void)hipFree(p->d_cross_table);
+    p->d_stream = p->d_wins = p->d_items = p->d_rowmap = p->d_cross_table = nullptr;
+    p->d_cross_sums = nullptr;
     (void)hipGetLastError();
 }
 
@@ -91,6 +100,7 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
         io.n_hint = opts->n_hint;
         io.sort_rows = opts->sort_rows;
         io.threads = opts->threads;
+        io.cross = opts->cross;
         force_wide = opts->force_wide != 0;
         depth = opts->depth;
     }
@@ -114,6 +124,13 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
         if (st == SPMM_OK) st = upload(&p->d_wins, h.wins.data(), h.wins.size() * 4, p->device_bytes);
         if (st == SPMM_OK) st = upload(&p->d_items, h.items.data(), h.items.size() * 4, p->device_bytes);
         if (st == SPMM_OK) st = upload(&p->d_rowmap, h.rowmap.data(), h.rowmap.size() * 4, p->device_bytes);
+        if (st == SPMM_OK && h.n_cross_slots > 0) {
+            const size_t slots = (size_t)h.n_cross_slots * CROSS_MAX_TILES;
+            int64_t before = p->device_bytes;
+            st = upload(&p->d_cross_sums, nullptr, slots * (size_t)h.ufi * CROSS_ROW_FLOATS * sizeof(float), p->device_bytes);
+            p->scratch_bytes = p->device_bytes - before;
+            if (st == SPMM_OK) st = upload(&p->d_cross_table, h.cross.data(), h.cross.size() * 4, p->device_bytes);
+        }
         if (st != SPMM_OK) {
             release_device(p);
             delete p;
@@ -170,6 +187,12 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
     a.n_blocks = (int32_t)h.n_blocks;
     a.ldn = N;
     a.col_mask = h.K <= ((int64_t)1 << spmm_fmt::COL_PATTERN_SHIFT) ? spmm_fmt::COL_INDEX_MASK : 0xFFFFFFFFu;
+    a.cross_sums = plan->d_cross_sums;
+    a.cross_table = plan->d_cross_table;
+    a.n_cross_slots = (uint32_t)h.n_cross_slots;
+    a.n_cross = (int32_t)h.n_cross;
+    // the scratch of panels cut across workgroups is sized for CROSS_MAX_TILES column tiles per launch
+    const int32_t max_tiles = h.n_cross_slots > 0 ? CROSS_MAX_TILES : 65535;
     // A 128-column tile of B that exceeds one L2 (4 MiB) while a 64-column tile fits: two
     // narrower tiles read the plan twice but keep their rows of B L2-resident (measured on a
     // 16384-column matrix of 13 M nonzeros: 275 against 295 us).
@@ -198,8 +221,8 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
             n_tiles += 1;  // the narrower last tile runs on the same kernel
             cols = left;
         }
-        if (n_tiles > 65535) {  // grid limit; the loop takes the rest
-            n_tiles = 65535;
+        if (n_tiles > max_tiles) {  // grid limit, or the scratch's; the loop takes the rest
+            n_tiles = max_tiles;
             cols = n_tiles * tile;
         }
         a.B = B ? B + j0 : nullptr;
@@ -244,6 +267,8 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
     out->stream_words = plan->stream_words;
     out->device_bytes = plan->device_bytes;
     out->sorted_rows = h.rowmap.empty() ? 0 : 1;
+    out->n_cross = h.n_cross;
+    out->scratch_bytes = plan->scratch_bytes;
     return SPMM_OK;
 }
 

@@ -95,11 +95,35 @@ enum ItemField {
     IT_RED_ROW = 9,   // ... row of C to write
     IT_WIN0 = 10,     // first window of the group
     IT_NWINS = 11,    // windows of the group (0 for an idle slot)
-    IT_WIN_FIRST = 12 // copy of the first window's entry of the window table (saves a dependent load)
+    IT_WIN_FIRST = 12,// copy of the first window's entry of the window table (saves a dependent load)
+    IT_X_NPARTS = 13, // blocks that share this block's panel (FLAG_CROSS only)
+    IT_X_SLOT0 = 14,  // ... scratch slot of the panel's first block
+    IT_X_PART = 15    // ... this block's place among them
 };
 constexpr int FLAG_SPLIT = 1;  // the group is one piece of a split panel: its tile goes to LDS
 constexpr int FLAG_IDLE = 2;   // no group in this wave slot
 constexpr int FLAG_SYNC = 4;   // the block holds split panels: every wave meets at one barrier
+constexpr int FLAG_CROSS = 8;  // the block holds WAVES_PER_WG pieces (or the last few) of a panel cut into more
+                               // pieces than one block has waves: the blocks' sums meet in scratch memory
+                               // and a second, small launch adds them
+
+// A panel is cut across blocks when it is heavier than both WAVES_PER_WG group budgets
+// and 1 / CROSS_SHARE of all entries (a quarter of a compute unit's share on 256 units):
+// left in one block it would outlast the rest of the launch.  At most MAX_CROSS_PARTS blocks.
+constexpr int CROSS_SHARE = 1024;
+constexpr int MAX_CROSS_PARTS = 64;
+// Floats per tile row of a scratch slot (the widest column tile); a slot holds ufi rows.
+constexpr int CROSS_ROW_FLOATS = 128;
+// Column tiles one launch of a plan with such panels may hold: the scratch is sized for them.
+constexpr int CROSS_MAX_TILES = 4;
+// Table of the panels cut across blocks (`cross`), one entry each: the combine step's input.
+constexpr int CROSS_ENTRY_WORDS = 12;
+enum CrossField {
+    CE_SLOT0 = 0,   // scratch slot of the panel's first block
+    CE_NPARTS = 1,  // blocks of the panel
+    CE_NROWS = 2,   // rows of the panel
+    CE_ROW0 = 4     // CE_ROW0 + r: row of C that row r of the panel is
+};
 
 }  // namespace spmm_fmt
 #endif

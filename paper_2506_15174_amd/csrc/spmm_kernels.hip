@@ -221,7 +221,8 @@ __global__ __launch_bounds__(64 * WAVES_PER_WG, (waves_per_simd(S, UFI))) void
 spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                    const uint32_t *__restrict__ wins_g, const uint32_t *__restrict__ items_g,
                    const uint32_t *__restrict__ rowmap_g, const float *__restrict__ B_all, uint32_t b_bytes_all,
-                   float *__restrict__ C_all, int32_t ldn, int32_t width_all, int32_t tile_cols, uint32_t col_mask)
+                   float *__restrict__ C_all, int32_t ldn, int32_t width_all, int32_t tile_cols, uint32_t col_mask,
+                   float *__restrict__ cross_sums, uint32_t n_cross_slots)
 {
     // blockIdx.y: the column tile this workgroup computes (tiles of tile_cols columns of
     // the width_all columns of this launch; the last one may be narrower).  Workgroups
@@ -432,22 +433,56 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
         // Every wave of a block with split panels arrives here exactly once.
         __syncthreads();
         const uint32_t nseg = it[IT_RED_NSEG];
-        if (nseg != 0 && slice == 0 && active) {
+        const bool adds = nseg != 0 && slice == 0 && active;
+        vec_t sum = Vec<VW>::zero();
+        if (adds) {
             const uint32_t first = it[IT_RED_SLOT0];
             const uint32_t r = it[IT_RED_R];
-            vec_t sum = Vec<VW>::zero();
             for (uint32_t p = 0; p < nseg; ++p)
                 add_to(sum, *reinterpret_cast<const vec_t *>(&lds[first + p][(r * L + sl) * VW]));
-            store_cols(C + (size_t)it[IT_RED_ROW] * (size_t)ldn + sl * VW, sum, valid);
+        }
+        if (!(flags & FLAG_CROSS)) {
+            if (adds) store_cols(C + (size_t)it[IT_RED_ROW] * (size_t)ldn + sl * VW, sum, valid);
+        } else if (adds) {
+            // The panel is cut across several blocks: each parks the sums of its pieces in
+            // its scratch slot; spmm_cross_combine_kernel, enqueued behind this launch, adds the
+            // slots in block order and writes C.
+            const size_t base = (size_t)blockIdx.y * n_cross_slots + it[IT_X_SLOT0] + it[IT_X_PART];
+            float *slot = cross_sums + base * (size_t)(UFI * CROSS_ROW_FLOATS);
+            *reinterpret_cast<vec_t *>(slot + it[IT_RED_R] * (uint32_t)CROSS_ROW_FLOATS + (uint32_t)(sl * VW)) = sum;
         }
     }
+}
+
+// Second step of panels cut across workgroups: block (x, y) adds, for panel x and column
+// tile y of the launch before it, the sums its workgroups parked in their scratch slots, in
+// workgroup order (so the result does not depend on how the launch was scheduled), and
+// writes the panel's rows of C.  Thread t owns row t / 32 of the tile and its columns
+// 4 (t % 32) .. + 3.  The kernel boundary makes the first step's stores visible: no fences,
+// no counters, nothing to clear between launches.
+__global__ __launch_bounds__(256) void
+spmm_cross_combine_kernel(const uint32_t *__restrict__ table, const float *__restrict__ sums, uint32_t n_cross_slots,
+                          int32_t ufi, float *__restrict__ C_all, int32_t ldn, int32_t width_all, int32_t tile_cols)
+{
+    const uint32_t *e = table + (size_t)blockIdx.x * CROSS_ENTRY_WORDS;
+    const uint32_t slot0 = e[CE_SLOT0], nparts = e[CE_NPARTS], nrows = e[CE_NROWS];
+    const uint32_t r = threadIdx.x / 32u;
+    const int32_t c = (int32_t)(threadIdx.x % 32u) * 4;
+    const int32_t col0 = (int32_t)blockIdx.y * tile_cols;
+    const int32_t width = width_all - col0 < tile_cols ? width_all - col0 : tile_cols;
+    if (r >= nrows || c >= width) return;
+    const size_t slot_floats = (size_t)ufi * CROSS_ROW_FLOATS;
+    const float *s = sums + ((size_t)blockIdx.y * n_cross_slots + slot0) * slot_floats + r * (uint32_t)CROSS_ROW_FLOATS + c;
+    f32x4_t total = Vec<4>::zero();
+    for (uint32_t p = 0; p < nparts; ++p) total += *reinterpret_cast<const f32x4_t *>(s + (size_t)p * slot_floats);
+    store_cols(C_all + (size_t)e[CE_ROW0 + r] * (size_t)ldn + col0 + c, total, width - c);
 }
 
 template <int U, int S, int VW, int D, bool WIDE> void launch_instance(const spmm_launch_args &a, void *stream)
 {
     hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE>), dim3((unsigned)a.n_blocks, (unsigned)a.n_tiles),
                        dim3(64 * WAVES_PER_WG), a.lds_pad, (hipStream_t)stream, a.stream, a.wins, a.items, a.rowmap,
-                       a.B, a.b_bytes, a.C, a.ldn, a.width, a.tile_cols, a.col_mask);
+                       a.B, a.b_bytes, a.C, a.ldn, a.width, a.tile_cols, a.col_mask, a.cross_sums, a.n_cross_slots);
 }
 
 // One (height, slices) pair at the pipeline depth asked for.  DMAX is the depth the
@@ -492,6 +527,10 @@ int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int slices, bool wide
     case 1: launch_slices<1, 3, 4, 8>(a, slices, wide, depth, stream); break;
     default: return (int)hipErrorInvalidValue;
     }
+    if (a.n_cross > 0)
+        hipLaunchKernelGGL(spmm_cross_combine_kernel, dim3((unsigned)a.n_cross, (unsigned)a.n_tiles), dim3(256), 0,
+                           (hipStream_t)stream, a.cross_table, a.cross_sums, a.n_cross_slots, (int32_t)ufi, a.C, a.ldn,
+                           a.width, a.tile_cols);
     return (int)hipGetLastError();
 }
 

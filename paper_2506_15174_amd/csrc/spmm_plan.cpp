@@ -112,13 +112,20 @@ int choose_ufi(int64_t M, int64_t K, int64_t nnz, int32_t n_hint)
 // where wide B would take four or more, else single rows.  A tile of B beyond one
 // L2 keeps single rows as above (for more than 64 columns the executor narrows
 // the tile to 64 columns first).  Height 1 means the rows are not sorted at all.
-int choose_ufi_skewed(int64_t K, int64_t nnz, int64_t max_row, int32_t n_hint)
+//
+// When panels may be cut across workgroups (cross_allowed below) a heavy panel is no
+// longer bound to one workgroup and the tail argument falls away: wide B takes eight
+// rows and medium B four (measured on the same matrices with every height forced and the
+// group budget halved: 13 % and 6 % faster in geometric mean than the bound above;
+// narrow B gains nothing from taller panels and keeps the bound).
+int choose_ufi_skewed(int64_t K, int64_t nnz, int64_t max_row, int32_t n_hint, bool cross)
 {
     const bool narrow = n_hint > 0 && n_hint <= 32;
     const bool medium = n_hint > 32 && n_hint <= 64;
     const int64_t l2 = (int64_t)4 << 20;
     const int64_t tile_row_bytes = narrow ? 128 : medium ? 256 : K * 512 > l2 ? 256 : 512;
     if (K * tile_row_bytes > l2) return 1;
+    if (cross && !narrow) return medium ? 4 : 8;
     const int64_t fair = std::max<int64_t>(1, nnz / 256);
     int h = 1;
     while (h < MAX_UFI && 2 * h * max_row <= 2 * fair) h *= 2;
@@ -146,6 +153,20 @@ void choose_group_budget(int64_t M, int64_t nnz, int ufi, int32_t &G_out, int32_
     if (g > 1024) g = 1024;
     G_out = (int32_t)g;
     GP_out = (int32_t)GP;
+}
+
+// Panels may be cut across workgroups (their sums then meet in scratch memory and a second,
+// small launch adds them) when the caller insists (setting > 0), or, by default, when the
+// row lengths are skewed and the matrix holds at least 2^20 entries: on smaller products
+// the second launch costs more than the balance gains (2048 x 2048 Zipf rows: + 3 us on
+// 9 .. 16 us), and matrices of even row lengths have no panel that outlasts the others.
+// Narrow B (hint of 32 columns or fewer) keeps every panel in one workgroup: its products
+// are short and the finer cut lost on most of them (8192 x 8192 Zipf rows: 25 -> 29 us).
+bool cross_allowed(int32_t setting, bool skewed, int64_t nnz, int32_t n_hint)
+{
+    if (setting != 0) return setting > 0;
+    const bool narrow = n_hint > 0 && n_hint <= 32;
+    return skewed && !narrow && nnz >= ((int64_t)1 << 20);
 }
 
 // Row lengths so uneven that sorting the rows pays: the rows longer than four
@@ -252,12 +273,17 @@ struct Emitter {
 // rounded up to a power of two (so that the pieces of several panels fill the
 // eight wave slots of a workgroup exactly), size = ceil(pn / want),
 // nseg = ceil(pn / size); the last piece takes the rest.
+// A panel heavier than both eight budgets and 1 / CROSS_SHARE of all entries (and
+// `cross` permitting) is cut across blocks instead: parts = ceil(pn / that bound), at
+// most MAX_CROSS_PARTS, eight pieces per part, size = ceil(pn / (8 parts)),
+// nseg = ceil(pn / size); its pieces fill blocks of eight in order.
 // Lighter panels are packed greedily: a group closes when the next panel would
 // exceed the budget or the panel cap.
-std::vector<Group> make_groups(const int32_t *row_ptr, int64_t M, int ufi, int64_t G, int64_t GP)
+std::vector<Group> make_groups(const int32_t *row_ptr, int64_t M, int ufi, int64_t G, int64_t GP, bool cross)
 {
     std::vector<Group> groups;
     const int64_t P = (M + ufi - 1) / ufi;
+    const int64_t part_bound = std::max<int64_t>(WAVES_PER_WG * G, (int64_t)row_ptr[M] / CROSS_SHARE);
     bool open = false;
     Group cur{};
     int64_t cur_panels = 0;
@@ -273,6 +299,8 @@ std::vector<Group> make_groups(const int32_t *row_ptr, int64_t M, int ufi, int64
             flush();
             int64_t want = std::min<int64_t>(WAVES_PER_WG, (pn + G - 1) / G);
             while (want & (want - 1)) want += 1;
+            const bool across = cross && pn > part_bound;
+            if (across) want = WAVES_PER_WG * std::min<int64_t>(MAX_CROSS_PARTS, (pn + part_bound - 1) / part_bound);
             const int64_t size = (pn + want - 1) / want;
             const int64_t nseg = (pn + size - 1) / size;
             for (int64_t s = 0; s < nseg; ++s) {
@@ -281,7 +309,7 @@ std::vector<Group> make_groups(const int32_t *row_ptr, int64_t M, int ufi, int64
                 g.row_end = (int32_t)r1;
                 g.nnz_begin = (int32_t)(a + s * size);
                 g.nnz_end = (int32_t)std::min<int64_t>(b, a + (s + 1) * size);
-                g.flags = FLAG_SPLIT;
+                g.flags = across ? FLAG_SPLIT | FLAG_CROSS : FLAG_SPLIT;
                 g.seg = (int32_t)s;
                 g.nseg = (int32_t)nseg;
                 groups.push_back(g);
@@ -366,10 +394,11 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         int ufi = opts.ufi;
         const bool forced_ufi = ufi == 1 || ufi == 2 || ufi == 4 || ufi == 8;
         const bool skewed = skewed_rows(row_ptr, M, nnz);
+        const bool cross = cross_allowed(opts.cross, skewed, nnz, opts.n_hint);
         if (!forced_ufi) {
             // a forced sort asks for the height a sorted matrix would get
             const bool as_sorted = opts.sort_rows > 0 || (opts.sort_rows == 0 && skewed);
-            ufi = as_sorted ? choose_ufi_skewed(K, nnz, max_row, opts.n_hint) : choose_ufi(M, K, nnz, opts.n_hint);
+            ufi = as_sorted ? choose_ufi_skewed(K, nnz, max_row, opts.n_hint, cross) : choose_ufi(M, K, nnz, opts.n_hint);
         }
         // single rows share nothing: sorting them would only scatter the rows of C
         const bool sorted = opts.sort_rows > 0 || (opts.sort_rows == 0 && skewed && ufi > 1);
@@ -394,11 +423,15 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         // ---- 1. group budget and row groups, from the row pointer alone ----------
         int32_t auto_g = 0, auto_gp = 0;
         choose_group_budget(M, nnz, ufi, auto_g, auto_gp);
+        // heavy panels cut as finely as needed: half the budget, so that the launch is made of
+        // lighter pieces throughout (measured with the heights above: stress matrix 162 -> 154 us,
+        // 8192 x 8192 lognormal rows of sigma 1.5 94 -> 81 us at 128 columns, 60 -> 53 us at 64)
+        if (cross) auto_g = std::max<int32_t>(32, auto_g / 2 / 32 * 32);
         out.group_nnz = opts.group_nnz > 0 ? std::max(8, opts.group_nnz) : auto_g;
         out.group_panels = opts.group_panels > 0 ? opts.group_panels : auto_gp;
         const int64_t G = out.group_nnz;
         const int64_t GP = out.group_panels;
-        std::vector<Group> groups = make_groups(plan_ptr, M, ufi, G, GP);
+        std::vector<Group> groups = make_groups(plan_ptr, M, ufi, G, GP, cross);
         out.ufi = ufi;
         const int UFI = ufi;  // panel height of this plan
         const int N_PATTERNS = (1 << UFI) - 1;
@@ -699,7 +732,49 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
             size_t at = 0;
             int used = WAVES_PER_WG, panels = SPLIT_PANELS_PER_WG;  // forces a new block
             for (int64_t head : split_heads) {
-                const int nseg = groups[(size_t)head].nseg;
+                const Group &g0 = groups[(size_t)head];
+                const int nseg = g0.nseg;
+                if (g0.flags & FLAG_CROSS) {
+                    // a panel cut across blocks: its pieces fill blocks of their own, eight at a
+                    // time; after its barrier wave r of every block adds row r of the block's
+                    // pieces into the block's scratch slot, and a second launch adds the slots in order
+                    const int nparts = (nseg + WAVES_PER_WG - 1) / WAVES_PER_WG;
+                    const uint32_t slot0 = (uint32_t)out.n_cross_slots;
+                    for (int part = 0; part < nparts; ++part) {
+                        at = new_block(FLAG_SYNC | FLAG_CROSS);
+                        const int first = part * WAVES_PER_WG, here = std::min(WAVES_PER_WG, nseg - first);
+                        for (int sidx = 0; sidx < here; ++sidx) {
+                            uint32_t *it = &out.items[at + (size_t)sidx * ITEM_WORDS];
+                            place(head + first + sidx, it);
+                            it[IT_FLAGS] |= FLAG_SYNC;
+                            out.n_split += 1;
+                        }
+                        for (int w = 0; w < WAVES_PER_WG; ++w) {
+                            uint32_t *it = &out.items[at + (size_t)w * ITEM_WORDS];
+                            it[IT_X_NPARTS] = (uint32_t)nparts;
+                            it[IT_X_SLOT0] = slot0;
+                            it[IT_X_PART] = (uint32_t)part;
+                            if (w < g0.row_end - g0.row_begin) {
+                                it[IT_RED_NSEG] = (uint32_t)here;
+                                it[IT_RED_SLOT0] = 0u;
+                                it[IT_RED_R] = (uint32_t)w;
+                                it[IT_RED_ROW] = (uint32_t)src(g0.row_begin + w);
+                            }
+                        }
+                    }
+                    const size_t e = out.cross.size();
+                    out.cross.resize(e + CROSS_ENTRY_WORDS, 0u);
+                    out.cross[e + CE_SLOT0] = slot0;
+                    out.cross[e + CE_NPARTS] = (uint32_t)nparts;
+                    out.cross[e + CE_NROWS] = (uint32_t)(g0.row_end - g0.row_begin);
+                    for (int r = 0; r < g0.row_end - g0.row_begin; ++r)
+                        out.cross[e + CE_ROW0 + (size_t)r] = (uint32_t)src(g0.row_begin + r);
+                    out.n_cross += 1;
+                    out.n_cross_slots += nparts;
+                    used = WAVES_PER_WG;  // the next split panel starts a block of its own
+                    panels = SPLIT_PANELS_PER_WG;
+                    continue;
+                }
                 if (used + nseg > WAVES_PER_WG || panels == SPLIT_PANELS_PER_WG) {
                     at = new_block(FLAG_SYNC);
                     used = 0;
@@ -712,7 +787,6 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                     out.n_split += 1;
                 }
                 // after the barrier wave UFI * panels + r adds row r of this panel
-                const Group &g0 = groups[(size_t)head];
                 for (int r = 0; r < g0.row_end - g0.row_begin; ++r) {
                     uint32_t *it = &out.items[at + (size_t)(UFI * panels + r) * ITEM_WORDS];
                     it[IT_RED_NSEG] = (uint32_t)nseg;

@@ -23,6 +23,9 @@ struct HostPlan {
     int64_t n_chunks = 0;      // real chunks (without the padding)
     int64_t n_enum = 0;        // enumerated columns (real column slots)
     int64_t n_split = 0;       // groups that are pieces of split panels
+    int64_t n_cross = 0;       // panels cut across several blocks
+    int64_t n_cross_slots = 0; // blocks of such panels: scratch slots of ufi x CROSS_ROW_FLOATS floats per column tile
+    std::vector<uint32_t> cross; // CROSS_ENTRY_WORDS per such panel (spmm_format.h)
     // Rows sorted by length (skewed matrices): rowmap[i] = row of A and C that the
     // plan's row i stands for.  Empty = the plan's rows are the matrix's rows.
     std::vector<uint32_t> rowmap;
@@ -35,6 +38,7 @@ struct InspectorOptions {
     int32_t n_hint = 0;        // B columns the plan is meant for; 0 = unknown
     int32_t sort_rows = 0;     // 0 = choose; > 0 = sort rows by length; < 0 = keep the row order
     int32_t threads = 0;       // 0 = choose; else host threads of the enumeration (1..64)
+    int32_t cross = 0;         // 0 = panels may be cut across blocks; < 0 = never (at most one block per panel)
 };
 
 // Status codes follow spmm_status_t (0 ok, 1 invalid argument, 2 invalid CSR,

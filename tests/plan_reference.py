@@ -17,14 +17,18 @@ COL_INDEX_MASK = (1 << COL_PATTERN_SHIFT) - 1
 
 
 WAVES_PER_WG = 8
-FLAG_SPLIT, FLAG_IDLE, FLAG_SYNC = 1, 2, 4
+FLAG_SPLIT, FLAG_IDLE, FLAG_SYNC, FLAG_CROSS = 1, 2, 4, 8
+CROSS_SHARE = 1024
+MAX_CROSS_PARTS = 64
 
 
-def _groups_for(rp, M, ufi, group_nnz, group_panels):
+def _groups_for(rp, M, ufi, group_nnz, group_panels, cross=True):
     whole, split = [], []          # split: list of panels, each a list of pieces
     cur = None
     cur_panels = 0
     P = (M + ufi - 1) // ufi
+    # a panel heavier than this (and than the budget of eight groups) is cut across workgroups
+    part_bound = max(WAVES_PER_WG * group_nnz, rp[M] // CROSS_SHARE)
     for p in range(P):
         r0, r1 = p * ufi, min(M, p * ufi + ufi)
         a, b = rp[r0], rp[r1]
@@ -36,9 +40,13 @@ def _groups_for(rp, M, ufi, group_nnz, group_panels):
             want = min(WAVES_PER_WG, -(-pn // group_nnz))
             while want & (want - 1):
                 want += 1
+            across = cross and pn > part_bound
+            if across:
+                want = WAVES_PER_WG * min(MAX_CROSS_PARTS, -(-pn // part_bound))
             size = -(-pn // want)
             nseg = -(-pn // size)
-            split.append([[r0, r1, a + s * size, min(b, a + (s + 1) * size), 1] for s in range(nseg)])
+            flag = FLAG_SPLIT | FLAG_CROSS if across else FLAG_SPLIT
+            split.append([[r0, r1, a + s * size, min(b, a + (s + 1) * size), flag] for s in range(nseg)])
             continue
         if cur is not None and (cur[3] - cur[2] + pn > group_nnz or cur_panels == group_panels):
             whole.append(cur)
@@ -61,6 +69,10 @@ def _blocks_for(split, whole, ufi):
     blocks = -(-len(whole) // WAVES_PER_WG)
     used, panels = WAVES_PER_WG, WAVES_PER_WG // ufi
     for pieces in split:
+        if pieces[0][4] & FLAG_CROSS:
+            blocks += -(-len(pieces) // WAVES_PER_WG)       # blocks of their own, eight pieces each
+            used, panels = WAVES_PER_WG, WAVES_PER_WG // ufi
+            continue
         if used + len(pieces) > WAVES_PER_WG or panels == WAVES_PER_WG // ufi:
             blocks += 1
             used, panels = 0, 0
@@ -104,16 +116,26 @@ def skewed_rows(row_ptr):
     return 4 * heavy >= nnz
 
 
-def choose_ufi_skewed(K, nnz, max_row, n_hint=0):
+def cross_allowed(row_ptr, setting=0, n_hint=0):
+    """Whether panels may be cut across workgroups: the caller's setting, or skewed row
+    lengths, at least 2^20 entries and no hint of 32 columns or fewer."""
+    if setting != 0:
+        return setting > 0
+    return bool(skewed_rows(row_ptr)) and not 0 < n_hint <= 32 and int(row_ptr[-1]) >= 1 << 20
+
+
+def choose_ufi_skewed(K, nnz, max_row, n_hint=0, cross=False):
     """Panel height for rows sorted by length: the largest power of two h <= 8 with
     h * (longest row) <= 2 * (nnz // 256); narrow B takes 2 where that gives 4 or 8,
     else 1; single rows when the tile of B exceeds one L2 (wide tiles narrow to 64
-    columns first)."""
+    columns first).  When panels may be cut across workgroups: 8 for wide, 4 for medium B."""
     narrow, medium = 0 < n_hint <= 32, 32 < n_hint <= 64
     l2 = 4 << 20
     tile_row_bytes = 128 if narrow else 256 if medium else 256 if K * 512 > l2 else 512
     if K * tile_row_bytes > l2:
         return 1
+    if cross and not narrow:
+        return 4 if medium else 8
     fair = max(1, nnz // 256)
     h = 1
     while h < MAX_UFI and 2 * h * max_row <= 2 * fair:
@@ -123,16 +145,16 @@ def choose_ufi_skewed(K, nnz, max_row, n_hint=0):
     return h
 
 
-def choose_schedule(row_ptr, M, K, n_hint=0, ufi=0, sort_rows=0):
-    """(panel height, rows sorted?) as the inspector decides them: `ufi` and
-    `sort_rows` are the caller's settings (0 = choose; sort_rows > 0 sort, < 0 keep)."""
+def choose_schedule(row_ptr, M, K, n_hint=0, ufi=0, sort_rows=0, cross=0):
+    """(panel height, rows sorted?) as the inspector decides them: `ufi`, `sort_rows` and
+    `cross` are the caller's settings (0 = choose; sort_rows > 0 sort, < 0 keep)."""
     lens = np.diff(np.asarray(row_ptr, dtype=np.int64))
     nnz = int(lens.sum())
     skewed = skewed_rows(row_ptr)
     if ufi not in (1, 2, 4, 8):
         as_sorted = sort_rows > 0 or (sort_rows == 0 and skewed)
-        ufi = (choose_ufi_skewed(K, nnz, int(lens.max()) if M else 0, n_hint) if as_sorted
-               else choose_ufi(M, K, nnz, n_hint))
+        ufi = (choose_ufi_skewed(K, nnz, int(lens.max()) if M else 0, n_hint, cross_allowed(row_ptr, cross, n_hint))
+               if as_sorted else choose_ufi(M, K, nnz, n_hint))
     return ufi, bool(sort_rows > 0 or (sort_rows == 0 and skewed and ufi > 1))
 
 
@@ -155,11 +177,11 @@ def choose_group_budget(M, nnz, ufi):
     return min(1024, max(32, g)), GP
 
 
-def derive_groups(row_ptr, M, group_nnz, group_panels, ufi):
+def derive_groups(row_ptr, M, group_nnz, group_panels, ufi, cross=True):
     """(row groups in launch order as an (n, 5) int32 array, workgroups), from
     row_ptr only, for a given panel height, budget and panel cap."""
     rp = [int(x) for x in row_ptr]
-    split, whole = _groups_for(rp, M, ufi, group_nnz, group_panels)
+    split, whole = _groups_for(rp, M, ufi, group_nnz, group_panels, cross)
     blocks = _blocks_for(split, whole, ufi)
     out = [piece for pieces in split for piece in pieces] + whole
     return np.array(out, dtype=np.int32).reshape(-1, 5), blocks
@@ -177,8 +199,30 @@ def check_blocks(items, ufi, rowmap=None):
     plan row when the plan's rows are sorted by length."""
     items = items.reshape(-1, WAVES_PER_WG, ITEM_WORDS)
     to_c = (lambda r: int(rowmap[r])) if rowmap is not None and len(rowmap) else (lambda r: r)
+    expect = None      # (parts, first slot, next part, panel rows) of a panel cut across blocks
+    slots_used = 0
     for blk in items:
         flags = blk[:, 5]
+        crossing = (flags & FLAG_CROSS) != 0
+        assert crossing.all() or not crossing.any(), "a panel cut across blocks fills its blocks alone"
+        if crossing.any():
+            nparts, slot0, part = (int(x) for x in blk[0, 13:16])
+            assert np.all(blk[:, 13] == nparts) and np.all(blk[:, 14] == slot0) and np.all(blk[:, 15] == part)
+            live = blk[(flags & FLAG_IDLE) == 0]
+            assert len(live) >= 1 and len(set(live[:, 0])) == 1 and len(set(live[:, 1])) == 1
+            rows = (int(live[0, 0]), int(live[0, 1]))
+            if expect is None:
+                assert part == 0 and nparts >= 2 and slot0 == slots_used
+                expect = [nparts, slot0, 0, rows]
+            assert [nparts, slot0, part, rows] == expect
+            assert len(live) == WAVES_PER_WG or part == nparts - 1, "only the last block may be short"
+            expect[2] += 1
+            if expect[2] == nparts:
+                slots_used += nparts
+                expect = None
+        else:
+            assert expect is None, "the blocks of a panel cut across blocks are adjacent"
+            assert not blk[:, 13:16].any()
         sync = (flags & FLAG_SYNC) != 0
         assert sync.all() or not sync.any(), "the barrier flag is a property of the block"
         idle = (flags & FLAG_IDLE) != 0
@@ -187,7 +231,7 @@ def check_blocks(items, ufi, rowmap=None):
         if not sync.any():
             assert not is_split.any() and not blk[:, 6].any()
             continue
-        assert not (is_split & idle).any()
+        assert not (is_split & idle).any() and (not crossing.any() or sync.all())
         assert np.all(is_split | idle), "blocks with split panels hold nothing else"
         # every split panel of the block has one adding wave per row, covering
         # exactly the slots of its pieces
@@ -210,6 +254,8 @@ def check_blocks(items, ufi, rowmap=None):
         for w in slots:
             for r in range(int(blk[w, 1])):
                 assert to_c(int(blk[w, 0]) + r) in rows_written
+    assert expect is None
+    return slots_used
 
 
 def walk_chunks(it, hdr, stream, wins):
@@ -316,6 +362,7 @@ def interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap=None, K=0):
     C = np.full((M, N), np.nan, dtype=np.float32)
     B64 = B.astype(np.float64)
     index_mask = 0xFFFFFFFF if K > (1 << COL_PATTERN_SHIFT) else COL_INDEX_MASK
+    parked = {}     # scratch slot -> sums of one block of a panel cut across blocks, per tile row
     for blk in blocks:
         tiles = np.zeros((WAVES_PER_WG, ufi, N), dtype=np.float32)
         for w, it in enumerate(blk):
@@ -352,5 +399,15 @@ def interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap=None, K=0):
                 total = np.zeros(N, dtype=np.float32)
                 for p in range(nseg):
                     total = total + tiles[slot0 + p, r]
-                C[crow] = total
+                if not int(it[5]) & FLAG_CROSS:
+                    C[crow] = total
+                    continue
+                # the block parks its sums; whichever block comes last adds the blocks' sums in block order
+                nparts, xslot0, part = (int(x) for x in it[13:16])
+                parked[(xslot0 + part, r)] = total
+                if part == nparts - 1:
+                    final = np.zeros(N, dtype=np.float32)
+                    for q in range(nparts):
+                        final = final + parked[(xslot0 + q, r)]
+                    C[crow] = final
     return C

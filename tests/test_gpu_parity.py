@@ -284,6 +284,70 @@ def test_pipeline_depth_setting_does_not_change_the_result(torch_gpu, oracle, de
     check(oracle, csr, B, C1)
 
 
+@pytest.mark.parametrize("N", [32, 64, 128, 100, 260, 700])
+@pytest.mark.parametrize("ufi", [1, 2, 4, 8])
+def test_panels_cut_across_workgroups(torch_gpu, oracle, ufi, N):
+    """Dense rows far heavier than the group budget: their panels are cut across several
+    workgroups whose sums meet in the plan's scratch memory (the workgroup that arrives
+    last adds them in workgroup order).  Small integers: bit-exact against the oracle;
+    repeated executes are bit-identical (the arrival counters are back at zero after
+    every launch); N = 700 needs more column tiles than one launch's scratch holds; the
+    same matrix with cross < 0 (every panel inside one workgroup) gives the same C."""
+    rng = np.random.default_rng(600 + ufi)
+    M, K = 61, 2600
+    W = np.where(rng.random((M, K)) < 0.04, rng.integers(-8, 9, (M, K)), 0).astype(np.float32)
+    W[1] = rng.integers(1, 9, K)
+    W[2, ::3] = rng.integers(1, 9, len(W[2, ::3]))
+    W[40] = rng.integers(1, 9, K)
+    W[[7, 8, 9]] = 0
+    csr = gen.csr_from_dense(W)
+    B = rng.integers(-16, 17, (K, N)).astype(np.float32)
+    C_ref, _ = oracle.spmm(csr.row_ptr, csr.col_idx, csr.vals, B)
+    assert np.abs(C_ref).max() < 2 ** 24
+    C, plan = gpu_product(torch_gpu, csr, B, guard_rows=2, group_nnz=64, ufi=ufi, cross=1)
+    info = plan.describe()
+    assert info["n_cross"] >= 1 and info["scratch_bytes"] > 0
+    assert np.array_equal(C.astype(np.float64), C_ref)
+    dB = torch_gpu.from_numpy(B).cuda()
+    for _ in range(3):
+        again = plan.execute(dB)
+        torch_gpu.cuda.synchronize()
+        assert np.array_equal(C, again.cpu().numpy())
+    C1, plan1 = gpu_product(torch_gpu, csr, B, group_nnz=64, ufi=ufi, cross=-1)
+    assert plan1.describe()["n_cross"] == 0 and plan1.describe()["scratch_bytes"] == 0
+    assert np.array_equal(C1.astype(np.float64), C_ref)
+
+
+def test_panels_cut_across_workgroups_in_a_replayed_graph(torch_gpu, oracle):
+    """The arrival counters of panels cut across workgroups are reset by the kernel itself
+    (no clearing call between launches), so a captured execute replays correctly."""
+    torch = torch_gpu
+    csr = heavy_tail(64, 3000, 195)
+    N = 128
+    plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, group_nnz=64, ufi=4, cross=1)
+    assert plan.describe()["n_cross"] > 0
+    B = torch.from_numpy(gen.dense_activations(csr.K, N, 196)).cuda()
+    C = torch.full((csr.M, N), float("nan"), dtype=torch.float32, device="cuda")
+    eager = plan.execute(B).clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        plan.execute(B, C)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.execute(B, C)
+    for replay in range(4):
+        C.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(C, eager), "replay %d differs from the eager result" % replay
+        plan.execute(B)
+        torch.cuda.synchronize()
+    check(oracle, csr, B.cpu().numpy(), C.cpu().numpy())
+
+
 def test_plain_c_client_runs_on_the_device(tmp_path):
     """create -> execute -> destroy from plain C99 (no Python, no torch between the caller
     and the library): the client uploads B, runs the product and compares known elements."""
@@ -366,8 +430,10 @@ def test_stress_config_whole_product_at_full_size(torch_gpu, oracle):
     csr = gen.stress()
     B = gen.activations_for(csr, 128)
     C, plan = gpu_product(torch_gpu, csr, B, n_hint=128)
-    # Zipf rows: the inspector sorts them by length and takes four-row panels
-    assert (plan.describe()["sorted_rows"], plan.describe()["ufi"]) == (1, 4)
+    # Zipf rows: the inspector sorts them by length, takes eight-row panels and cuts the
+    # heavy ones (the dense rows) across workgroups
+    info = plan.describe()
+    assert (info["sorted_rows"], info["ufi"]) == (1, 8) and info["n_cross"] > 50 and info["scratch_bytes"] > 0
     check(oracle, csr, B, C, parallel=True)
     lens = np.diff(csr.row_ptr)
     # every empty row of the full matrix is exactly zero

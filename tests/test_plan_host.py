@@ -17,7 +17,7 @@ import paper_2506_15174_amd as spmm
 from workloads import generators as gen
 
 from plan_reference import (UFK, canonical_csr, choose_group_budget, choose_schedule, choose_ufi,
-                            choose_ufi_skewed, decode_plan, derive_groups, interpret_plan, skewed_rows,
+                            check_blocks, choose_ufi_skewed, cross_allowed, decode_plan, derive_groups, interpret_plan, skewed_rows,
                             sorted_row_order,
                             walk_chunks)
 
@@ -98,7 +98,8 @@ def test_row_groups_match_python_rederivation(name, group_nnz, force_ufi, sort_r
     assert info["group_nnz"] == (group_nnz or auto_g) and info["group_panels"] == auto_gp
     got = plan.get_groups()
     _, plan_ptr = plan_rows(csr, plan)
-    want, blocks = derive_groups(plan_ptr, csr.M, info["group_nnz"], info["group_panels"], UFI)
+    want, blocks = derive_groups(plan_ptr, csr.M, info["group_nnz"], info["group_panels"], UFI,
+                                 cross=cross_allowed(csr.row_ptr))
     assert blocks == info["n_blocks"]
     assert got.shape == want.shape and np.array_equal(got, want)
     assert info["n_groups"] == len(want) and info["n_split"] == int((want[:, 4] & 1).sum())
@@ -200,14 +201,15 @@ def _plan_from_row_lengths(lens, K, **kw):
 # (rows as (count, length) runs, K, hint) -> (ufi, sorted), worked by hand from the
 # rule for skewed matrices in the header of spmm_plan.cpp
 SKEWED_CASES = [
-    # 256 rows of 2048 among 16128 of 60: nnz 1 491 968, mean 91, the long rows hold 35 %:
-    # skewed; fair share 5828: 4 x 2048 <= 11656 < 8 x 2048 -> four rows, sorted
-    (((256, 2048), (16128, 60)), 2048, 128, (4, 1)),
+    # 256 rows of 2048 among 16128 of 60: nnz 1 491 968 (2^20 or more: heavy panels may be cut
+    # across workgroups), mean 91, the long rows hold 35 %: skewed -> eight rows for wide B,
+    # four for medium B, sorted
+    (((256, 2048), (16128, 60)), 2048, 128, (8, 1)),
     (((256, 2048), (16128, 60)), 2048, 64, (4, 1)),
     # narrow B takes two rows where wide B takes four or eight
     (((256, 2048), (16128, 60)), 2048, 32, (2, 1)),
-    # 256 rows of 2048 among 16128 of 20: nnz 846 848, fair share 3308: 2 x 2048 <= 6616 < 4 x 2048
-    # -> two rows; narrow B: single rows, not sorted
+    # 256 rows of 2048 among 16128 of 20: nnz 846 848 (below 2^20: every panel stays inside one
+    # workgroup), fair share 3308: 2 x 2048 <= 6616 < 4 x 2048 -> two rows; narrow B: single rows, not sorted
     (((256, 2048), (16128, 20)), 2048, 128, (2, 1)),
     (((256, 2048), (16128, 20)), 2048, 32, (1, 0)),
     # 64 rows of 4096 among 4032 of 100: skewed (39 %), fair share 2599: 2 x 4096 > 5198: single rows
@@ -241,6 +243,25 @@ def test_schedule_of_skewed_matrices(runs, K, hint, want):
         assert np.all(np.diff(sl) <= 0), "longest rows first"
         same = np.flatnonzero(np.diff(sl) == 0)
         assert np.all(rowmap[same] < rowmap[same + 1]), "equal lengths keep the row order"
+
+
+def test_skewed_schedule_without_cuts_across_workgroups():
+    """cross < 0: a panel stays inside one workgroup, so the height follows the longest row
+    against a compute unit's share (fair share 5828: 4 x 2048 <= 11656 < 8 x 2048 -> four
+    rows) and the group budget is the ordinary one; by default the same matrix takes eight
+    rows and half the budget, its heavy panels cut across workgroups."""
+    lens = np.concatenate([np.full(256, 2048), np.full(16128, 60)])
+    lens = lens[np.random.default_rng(5).permutation(len(lens))]
+    row_ptr, plan = _plan_from_row_lengths(lens, 2048, n_hint=128, cross=-1)
+    info = plan.describe()
+    assert (info["ufi"], info["sorted_rows"], info["n_cross"]) == (4, 1, 0)
+    assert choose_schedule(row_ptr, len(lens), 2048, 128, cross=-1) == (4, True)
+    assert info["group_nnz"] == choose_group_budget(len(lens), int(row_ptr[-1]), 4)[0]
+    _, plan = _plan_from_row_lengths(lens, 2048, n_hint=128)
+    info = plan.describe()
+    assert (info["ufi"], info["sorted_rows"]) == (8, 1) and info["n_cross"] == 32   # 256 rows of 2048 in 32 panels
+    g8 = choose_group_budget(len(lens), int(row_ptr[-1]), 8)[0]
+    assert info["group_nnz"] == max(32, g8 // 2 // 32 * 32)
 
 
 def test_sorting_can_be_forced_and_forbidden():
@@ -481,7 +502,8 @@ def test_random_matrices_and_settings_round_trip(seed):
     want_ufi, want_sorted = choose_schedule(csr.row_ptr, M, K, hint, ufi, sort_rows)
     assert (info["ufi"], info["sorted_rows"]) == (want_ufi, int(want_sorted))
     rowmap, plan_ptr = plan_rows(csr, plan)
-    want, blocks = derive_groups(plan_ptr, M, info["group_nnz"], info["group_panels"], info["ufi"])
+    want, blocks = derive_groups(plan_ptr, M, info["group_nnz"], info["group_panels"], info["ufi"],
+                                 cross=cross_allowed(csr.row_ptr))
     assert np.array_equal(plan.get_groups(), want) and blocks == info["n_blocks"]
     items, hdr, stream, wins = arrays(plan)
     rows, cc, bits = decode_plan(items, hdr, stream, wins, info["ufi"], rowmap)
@@ -494,6 +516,46 @@ def test_random_matrices_and_settings_round_trip(seed):
     dense = np.zeros((M, K), dtype=np.float64)
     np.add.at(dense, (np.repeat(np.arange(M), np.diff(csr.row_ptr)), csr.col_idx), csr.vals.astype(np.float64))
     assert np.array_equal(C.astype(np.float64), dense @ B.astype(np.float64))
+
+
+@pytest.mark.parametrize("ufi", [1, 2, 4, 8])
+def test_heavy_panels_are_cut_across_blocks(ufi):
+    """A panel heavier than eight group budgets and than 1/1024 of all entries is cut
+    into more pieces than a block has waves: its pieces fill blocks of their own, eight
+    each (the last may be short), every block gets a scratch slot, and the chunk arrays
+    still evaluate to the exact product.  With the setting cross < 0 the same matrix
+    keeps every panel in one block and needs no scratch."""
+    rng = np.random.default_rng(50 + ufi)
+    M, K = 37, 3000
+    W = np.where(rng.random((M, K)) < 0.03, rng.integers(-8, 9, (M, K)), 0).astype(np.float32)
+    W[2] = rng.integers(1, 9, K)
+    W[3, ::2] = rng.integers(1, 9, K // 2)
+    W[20] = rng.integers(1, 9, K)
+    csr = gen.csr_from_dense(W)
+    B = rng.integers(-4, 5, (K, 5)).astype(np.float32)
+    dense = W.astype(np.float64) @ B.astype(np.float64)
+    assert not cross_allowed(csr.row_ptr) and cross_allowed(csr.row_ptr, 1)    # a small matrix: only on request
+    for cross in (1, 0, -1):
+        plan = host_plan(csr, ufi=ufi, group_nnz=64, cross=cross)
+        info = plan.describe()
+        groups = plan.get_groups()
+        rowmap, plan_ptr = plan_rows(csr, plan)     # tall panels of this matrix sort the rows by length
+        want, blocks = derive_groups(plan_ptr, M, info["group_nnz"], info["group_panels"], ufi, cross=cross > 0)
+        assert np.array_equal(groups, want) and blocks == info["n_blocks"]
+        items, hdr, stream, wins = arrays(plan)
+        slots = check_blocks(items, ufi, rowmap)
+        if cross <= 0:
+            assert info["n_cross"] == 0 and slots == 0 and not (groups[:, 4] & 8).any()
+            assert max(np.bincount(groups[groups[:, 4] != 0, 0])) <= 8
+        else:
+            assert info["n_cross"] >= 1 and slots >= 2 * info["n_cross"]
+            heavy = groups[(groups[:, 4] & 8) != 0]
+            assert len(heavy) > 8 * info["n_cross"] and np.all(heavy[:, 4] == 9)
+            # pieces of one budget or less: 8 budgets = 512 entries per block at most
+            assert np.all(heavy[:, 3] - heavy[:, 2] <= 64)
+        assert info["scratch_bytes"] == 0      # host-only plans own no device memory
+        C = interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap)
+        assert np.array_equal(C.astype(np.float64), dense)
 
 
 @pytest.mark.parametrize("K", [(1 << 24) - 1, 1 << 24, (1 << 24) + 1, (1 << 24) + 77])
