@@ -143,7 +143,9 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
  * Asynchronous: kernels are enqueued on `stream` and the call returns.  It
  * allocates nothing and does not synchronise.  The plan is read-only during
  * execution (pieces of a split panel meet in on-chip memory, not in the plan),
- * so any number of executes of one plan may be in flight on any streams.
+ * so any number of executes of one plan may be in flight on any streams -- unless the
+ * plan holds panels cut across workgroups (info.n_cross > 0): their sums meet in scratch
+ * memory of the plan, so at most one execute of such a plan may be in flight at a time.
  * Results are bit-identical from run to run.  B and C must be 4-byte aligned.
  * Every N runs on the kernels that handle four columns per lane (the last lane of
  * a row stores only the columns that exist; rows that are not 16-byte aligned cost
@@ -152,6 +154,26 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
  */
 spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N,
                            float *C, void *stream);
+
+/*
+ * spmm_execute for callers that cannot tolerate any device allocation behind the
+ * product, not even the plan's own: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation calls.  Same arguments, same result bit for bit.
+ * The sums of panels cut across workgroups (info.n_cross > 0) go to a scratch array that
+ * is part of the library's code object (6 MiB per device, held until the process ends)
+ * instead of the plan's scratch memory; plans without such panels run exactly as
+ * spmm_execute.  The call allocates and frees nothing; the first call on a device (or
+ * the creation of a plan with cut panels on it) asks the runtime for the array's address.
+ *
+ * One column tile of a launch needs 512 * ufi bytes per workgroup of a cut panel; the
+ * call packs as many column tiles into a launch as the array holds and returns
+ * SPMM_ERR_UNSUPPORTED, enqueuing nothing, when a single tile does not fit.
+ * All plans and all callers on one device share the array, which keeps the last call's
+ * content (every launch overwrites what it reads, nothing needs clearing): calls that
+ * overlap in time on one device race, also on different streams and for different plans.
+ */
+spmm_status_t spmm_execute_static(const spmm_plan_t *plan, const float *B, int32_t N,
+                                  float *C, void *stream);
 
 /* Frees the plan and its device memory.  NULL is a no-op returning SPMM_OK. */
 spmm_status_t spmm_plan_destroy(spmm_plan_t *plan);

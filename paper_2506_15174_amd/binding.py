@@ -21,7 +21,7 @@ SPMM_ERR_UNSUPPORTED = 5
 
 ARRAY_HDR, ARRAY_STREAM, ARRAY_WINS, ARRAY_ITEMS, ARRAY_ROWMAP = 0, 1, 2, 3, 4
 
-EXPORTS = ("spmm_plan_create", "spmm_plan_create_ex", "spmm_execute",
+EXPORTS = ("spmm_plan_create", "spmm_plan_create_ex", "spmm_execute", "spmm_execute_static",
            "spmm_plan_destroy", "spmm_plan_describe", "spmm_plan_get_groups",
            "spmm_plan_get_array", "spmm_status_string")
 
@@ -80,6 +80,8 @@ def load():
                                         ctypes.POINTER(Options)]
     lib.spmm_execute.restype = ctypes.c_int
     lib.spmm_execute.argtypes = [vp, vp, i32, vp, vp]
+    lib.spmm_execute_static.restype = ctypes.c_int
+    lib.spmm_execute_static.argtypes = [vp, vp, i32, vp, vp]
     lib.spmm_plan_destroy.restype = ctypes.c_int
     lib.spmm_plan_destroy.argtypes = [vp]
     lib.spmm_plan_describe.restype = ctypes.c_int
@@ -146,6 +148,12 @@ class Plan:
         st = _lib.spmm_execute(self._h, B_ptr, N, C_ptr, stream_ptr)
         if st != SPMM_OK:
             raise SpmmError(st, "spmm_execute")
+
+    def execute_static_raw(self, B_ptr, N, C_ptr, stream_ptr=None):
+        """spmm_execute_static with raw device addresses (ints)."""
+        st = _lib.spmm_execute_static(self._h, B_ptr, N, C_ptr, stream_ptr)
+        if st != SPMM_OK:
+            raise SpmmError(st, "spmm_execute_static")
 
     def execute(self, B, C=None, stream=None):
         """spmm_execute on torch tensors (device memory and stream plumbing only).

@@ -130,6 +130,11 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
             st = upload(&p->d_cross_sums, nullptr, slots * (size_t)h.ufi * CROSS_ROW_FLOATS * sizeof(float), p->device_bytes);
             p->scratch_bytes = p->device_bytes - before;
             if (st == SPMM_OK) st = upload(&p->d_cross_table, h.cross.data(), h.cross.size() * 4, p->device_bytes);
+            // set-up for spmm_execute_static: this device's address of the static scratch is looked up here,
+            // once, so that the entry point itself finds it ready (a failure only matters to that entry point)
+            float *unused = nullptr;
+            size_t unused_bytes = 0;
+            if (spmm_static_scratch(&unused, &unused_bytes) != 0) (void)hipGetLastError();
         }
         if (st != SPMM_OK) {
             release_device(p);
@@ -157,7 +162,12 @@ spmm_status_t spmm_plan_create(spmm_plan_t **plan, int64_t M, int64_t K, const i
     return spmm_plan_create_ex(plan, M, K, row_ptr, col_idx, vals, nullptr);
 }
 
-spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, float *C, void *stream)
+namespace {
+
+// cross_sums: scratch for the sums of panels cut across workgroups, with room for
+// cross_tiles column tiles of one launch (unused by plans without such panels)
+spmm_status_t execute_with(const spmm_plan_t *plan, const float *B, int32_t N, float *C, void *stream,
+                           float *cross_sums, int32_t cross_tiles)
 {
     if (!plan || N < 1) return SPMM_ERR_INVALID_ARG;
     if (!plan->on_device) return SPMM_ERR_INVALID_ARG;
@@ -187,12 +197,12 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
     a.n_blocks = (int32_t)h.n_blocks;
     a.ldn = N;
     a.col_mask = h.K <= ((int64_t)1 << spmm_fmt::COL_PATTERN_SHIFT) ? spmm_fmt::COL_INDEX_MASK : 0xFFFFFFFFu;
-    a.cross_sums = plan->d_cross_sums;
+    a.cross_sums = cross_sums;
     a.cross_table = plan->d_cross_table;
     a.n_cross_slots = (uint32_t)h.n_cross_slots;
     a.n_cross = (int32_t)h.n_cross;
-    // the scratch of panels cut across workgroups is sized for CROSS_MAX_TILES column tiles per launch
-    const int32_t max_tiles = h.n_cross_slots > 0 ? CROSS_MAX_TILES : 65535;
+    // the scratch of panels cut across workgroups holds so many column tiles of one launch
+    const int32_t max_tiles = h.n_cross_slots > 0 ? cross_tiles : 65535;
     // A 128-column tile of B that exceeds one L2 (4 MiB) while a 64-column tile fits: two
     // narrower tiles read the plan twice but keep their rows of B L2-resident (measured on a
     // 16384-column matrix of 13 M nonzeros: 275 against 295 us).
@@ -237,6 +247,31 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, f
         j0 += cols;
     }
     return SPMM_OK;
+}
+
+}  // namespace
+
+spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N, float *C, void *stream)
+{
+    return execute_with(plan, B, N, C, stream, plan ? plan->d_cross_sums : nullptr, CROSS_MAX_TILES);
+}
+
+spmm_status_t spmm_execute_static(const spmm_plan_t *plan, const float *B, int32_t N, float *C, void *stream)
+{
+    if (!plan) return SPMM_ERR_INVALID_ARG;
+    const HostPlan &h = plan->host;
+    if (h.n_cross_slots == 0 || !plan->on_device) return execute_with(plan, B, N, C, stream, nullptr, 0);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return hip_fail();
+    if (dev != plan->device) return SPMM_ERR_INVALID_ARG;
+    float *sums = nullptr;
+    size_t bytes = 0;
+    if (spmm_static_scratch(&sums, &bytes) != 0) return hip_fail();
+    // one column tile of a launch needs a slot of ufi x CROSS_ROW_FLOATS floats per workgroup of a cut panel
+    const size_t per_tile = (size_t)h.n_cross_slots * (size_t)h.ufi * CROSS_ROW_FLOATS * sizeof(float);
+    if (per_tile > bytes) return SPMM_ERR_UNSUPPORTED;
+    const size_t tiles = bytes / per_tile;
+    return execute_with(plan, B, N, C, stream, sums, (int32_t)(tiles < 65535 ? tiles : 65535));
 }
 
 spmm_status_t spmm_plan_destroy(spmm_plan_t *plan)

@@ -3,6 +3,7 @@
 #ifndef SPMM_KERNELS_H
 #define SPMM_KERNELS_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 struct spmm_launch_args {
@@ -34,6 +35,15 @@ struct spmm_launch_args {
 // addressing of B.  depth = chunks of B rows in flight (0 or anything deeper than the
 // instance's tuned depth = the tuned depth).  Returns the hipError_t of the launch as int.
 int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int slices, bool wide, int depth, void *stream);
+
+// Size of the library's statically allocated device scratch (one copy per device, held
+// until the process ends).
+#define SPMM_STATIC_SCRATCH_BYTES ((size_t)6 << 20)
+
+// The current device's copy of that scratch: *ptr = its device address, *bytes = its size.
+// The first call on a device asks the runtime for the address (no allocation: the array is
+// part of the loaded code object); later calls return the kept value.  Returns a hipError_t.
+int spmm_static_scratch(float **ptr, size_t *bytes);
 
 // The pipeline depth an instance is tuned for.
 int spmm_default_depth(int ufi, int slices);

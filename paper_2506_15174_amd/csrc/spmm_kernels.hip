@@ -36,6 +36,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "spmm_format.h"
 #include "spmm_kernels.h"
 
@@ -532,6 +534,36 @@ int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int slices, bool wide
                            (hipStream_t)stream, a.cross_table, a.cross_sums, a.n_cross_slots, (int32_t)ufi, a.C, a.ldn,
                            a.width, a.tile_cols);
     return (int)hipGetLastError();
+}
+
+// Scratch memory that exists without any allocation call: a device array of the library's
+// code object, for callers of spmm_execute_static.  In host code the array's name is only a
+// handle for the runtime; its address on each device is asked for once and kept.
+namespace {
+static __device__ __align__(256) float scratch[SPMM_STATIC_SCRATCH_BYTES / sizeof(float)];
+constexpr int MAX_DEVICES = 64;
+float *scratch_on_device[MAX_DEVICES];
+std::mutex scratch_lock;
+}  // namespace
+
+int spmm_static_scratch(float **ptr, size_t *bytes)
+{
+    *ptr = nullptr;
+    *bytes = 0;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= MAX_DEVICES) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(scratch_lock);
+    if (!scratch_on_device[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // this device's copy of the array
+        if (e != hipSuccess || !p) return e != hipSuccess ? (int)e : (int)hipErrorInvalidSymbol;
+        scratch_on_device[dev] = static_cast<float *>(p);
+    }
+    *ptr = scratch_on_device[dev];
+    *bytes = SPMM_STATIC_SCRATCH_BYTES;
+    return 0;
 }
 
 int spmm_default_depth(int ufi, int slices)
