@@ -395,17 +395,20 @@ def run_ablation(args):
     """The ingredients of the method switched on one by one on 30 sweep matrices (paper
     Section 4.3, Figure 7: baseline -> + enumeration -> + coarsening), as geometric-mean
     GFLOP/s per column count:
-      rows        one wave per row, rows never cut (the paper's Figure 1a mapping with
-                  this kernel's chunked B loads)
+      rows        one wave per row, rows never cut, no B row requested before the
+                  previous chunk is multiplied (the paper's Figure 1a mapping with this
+                  kernel's chunked B loads)
       +balance    nnz-balanced row groups: heavy rows cut into pieces that meet in LDS
       +enumerate  panels of 2, 4 or 8 rows enumerated by nonzero pattern, height by the
-                  schedule rule (the full method)"""
+                  schedule rule; still one chunk at a time (pipeline depth 1)
+      +coarsen    the full method: the chunks of B rows of the next D - 1 steps in flight
+                  while one is multiplied (the paper's unroll(k, UFk), Section 3.3.2)"""
     import torch
     import paper_2506_15174_amd as spmm
     from workloads import generators as gen
     torch.cuda.set_device(0)
     cols = (32, 64, 128)
-    rungs = ("rows", "+balance", "+enumerate")
+    rungs = ("rows", "+balance", "+enumerate", "+coarsen")
     pts = []
     t_start = time.perf_counter()
     for entry in _ladder_matrices(gen):
@@ -415,11 +418,12 @@ def run_ablation(args):
         for N in cols:
             B = torch.from_numpy(gen.activations_for(csr, N)).cuda()
             C = torch.empty((csr.M, N), dtype=torch.float32, device="cuda")
-            plans = {"rows": spmm.plan_create(*a, ufi=1, group_nnz=1 << 30, group_panels=1),
-                     "+balance": spmm.plan_create(*a, ufi=1, n_hint=N),
-                     "+enumerate": spmm.plan_create(*a, n_hint=N)}
+            plans = {"rows": spmm.plan_create(*a, ufi=1, group_nnz=1 << 30, group_panels=1, depth=1),
+                     "+balance": spmm.plan_create(*a, ufi=1, n_hint=N, depth=1),
+                     "+enumerate": spmm.plan_create(*a, n_hint=N, depth=1),
+                     "+coarsen": spmm.plan_create(*a, n_hint=N)}
             row = {"M": csr.M, "K": csr.K, "sparsity": entry["sparsity"], "N": N,
-                   "ufi": plans["+enumerate"].describe()["ufi"]}
+                   "ufi": plans["+coarsen"].describe()["ufi"]}
             for r in rungs:
                 us = _time_plan(torch, plans[r], B, C, N)
                 row[r + "_us"] = round(us, 3)
@@ -432,8 +436,10 @@ def run_ablation(args):
         sel = [p for p in pts if p["N"] == N]
         summary[str(N)] = {r: round(_geomean([p[r + "_gflops"] for p in sel]), 1) for r in rungs}
         summary[str(N)]["speedup_full_over_rows"] = round(
-            _geomean([p["rows_us"] / p["+enumerate_us"] for p in sel]), 3)
-    full = [p["+enumerate_gflops"] for p in pts]
+            _geomean([p["rows_us"] / p["+coarsen_us"] for p in sel]), 3)
+        summary[str(N)]["speedup_coarsen_over_enumerate"] = round(
+            _geomean([p["+enumerate_us"] / p["+coarsen_us"] for p in sel]), 3)
+    full = [p["+coarsen_gflops"] for p in pts]
     print(json.dumps({"metric": "fp32 CSR SpMM GFLOP/s (2*nnz*bCols), geomean per rung", "value": round(_geomean(full), 2),
                       "unit": "GFLOP/s", "n_gpus": 1, "higher_is_better": True, "dtype": "f32", "data": "synthetic",
                       "config": {"workload": "ablation ladder on 30 sweep matrices (M, K >= 1024) x bCols 32/64/128",

@@ -40,7 +40,9 @@ typedef enum {
 typedef struct {
     int64_t M, K, nnz;
     int32_t ufi;           /* rows per panel: height of the register tile (the paper's UFi): 8, 4, 2 or 1 */
-    int32_t ufk;           /* enumerated columns in flight per wave (the paper's UFk) */
+    int32_t ufk;           /* enumerated columns per chunk, the unit a wave requests and multiplies at
+                              a time (the paper's UFk): 8, or 16 / 32 / 64 in plans made for B of at
+                              most 32 / 16 / 8 columns */
     int32_t group_nnz;     /* nonzero budget of one row group (one wave's work item) */
     int32_t group_panels;  /* most panels a row group may hold */
     int64_t n_groups;      /* row groups = wave-level work items, in launch order */
@@ -86,6 +88,12 @@ typedef struct {
                               any number of executes of the plan may overlap); > 0 always; 0: when the
                               row lengths are skewed (see sort_rows), A holds 2^20 entries or more and
                               n_hint is 0 or above 32.  Such a plan also halves its group budget. */
+    int32_t ufk;           /* force the enumerated columns per chunk: 8, 16, 32 or 64 (0 = choose from
+                              n_hint: 8 for more than 32 columns or unknown, else 16 / 32 / 64 for up to
+                              32 / 16 / 8 columns; always 8 for more than 2^24 columns of A and with
+                              force_wide).  A plan with wider chunks computes every N on column tiles
+                              of 32 / 16 / 8 (or 4) columns and cannot address a B beyond 4 GiB
+                              (spmm_execute then returns SPMM_ERR_UNSUPPORTED). */
 } spmm_options_t;
 
 /*

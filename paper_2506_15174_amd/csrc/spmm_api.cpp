@@ -101,7 +101,10 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
         io.sort_rows = opts->sort_rows;
         io.threads = opts->threads;
         io.cross = opts->cross;
+        if (opts->ufk != 0 && !valid_ufk(opts->ufk)) return SPMM_ERR_INVALID_ARG;
+        io.ufk = opts->ufk;
         force_wide = opts->force_wide != 0;
+        if (force_wide) io.ufk = UFK;  // the 64-bit addressing kernels read chunks of 8 columns
         depth = opts->depth;
     }
     spmm_plan *p = new (std::nothrow) spmm_plan();
@@ -212,7 +215,13 @@ spmm_status_t execute_with(const spmm_plan_t *plan, const float *B, int32_t N, f
     a.lds_pad = narrow_tiles ? 24u << 10 : 0u;
     // Column tiles of one width share a launch (its workgroups start tile by tile, so a
     // tile begins while the previous one drains); a narrower rest takes a launch of its own.
+    // Plans made for narrow B (chunks wider than 8 columns) run every N on their own narrow tiles.
+    if (h.ufk != UFK && wide) return SPMM_ERR_UNSUPPORTED;
     auto tile_for = [&](int32_t left, int &slices) -> int32_t {
+        if (h.ufk != UFK) {
+            slices = h.ufk == 16 ? 8 : h.ufk == 32 ? 16 : left > 4 ? 32 : 64;
+            return 256 / slices;
+        }
         if (!quads) {
             slices = 1;
             return 64;
@@ -242,7 +251,7 @@ spmm_status_t execute_with(const spmm_plan_t *plan, const float *B, int32_t N, f
         a.n_tiles = n_tiles;
         const uint64_t skipped = (uint64_t)j0 * 4u;
         a.b_bytes = wide || b_total <= skipped ? 0u : (uint32_t)(b_total - skipped);
-        const int e = spmm_launch_chunks(a, h.ufi, slices, wide, plan->depth, stream);
+        const int e = spmm_launch_chunks(a, h.ufi, h.ufk, slices, wide, plan->depth, stream);
         if (e != 0) return SPMM_ERR_HIP;
         j0 += cols;
     }
@@ -291,7 +300,7 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
     out->K = h.K;
     out->nnz = h.nnz;
     out->ufi = h.ufi;
-    out->ufk = UFK;
+    out->ufk = h.ufk;
     out->group_nnz = h.group_nnz;
     out->group_panels = h.group_panels;
     out->n_groups = (int64_t)(h.groups.size() / 5);

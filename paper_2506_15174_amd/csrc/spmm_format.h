@@ -23,49 +23,59 @@ namespace spmm_fmt {
 // 8, 4, 2 or 1; a panel of u rows has 2^u - 1 nonzero patterns (paper Section 2).
 constexpr int MAX_UFI = 8;
 
-// Enumerated columns per chunk (the paper's UFk).
+// Enumerated columns per chunk (the paper's UFk): a property of the plan.  8 for B of more
+// than 32 columns (or unknown width); plans made for narrower B take wider chunks, so that a
+// wave cut into more slices (16 bytes of a B row need only one lane per four columns) still
+// hands every slice two column slots per chunk: 16 for up to 32 columns of B, 32 for up to
+// 16, 64 for up to 8.
 constexpr int UFK = 8;
+constexpr int MAX_UFK = 64;
+constexpr bool valid_ufk(int u) { return u == 8 || u == 16 || u == 32 || u == 64; }
 
 // A chunk is described by
 //
 //   header     one word:  bits 0..7   pattern (rows of the panel that own a value in
 //                                     every column of the chunk), 0 only for the
 //                                     single chunk of a panel without nonzeros
-//                         bits 8..11  count of real columns, 0..UFK
-//                         bit  12     last chunk of its panel (write the tile)
-//   columns    UFK column words (slots >= count repeat a valid column of the chunk,
+//                         bits 8..14  count of real columns, 0..ufk
+//                         bit  15     last chunk of its panel (write the tile)
+//   columns    ufk column words (slots >= count repeat a valid column of the chunk,
 //              or 0, and carry zero values).  Bits 0..23 hold the column index.  The
 //              leftovers of several patterns may share a chunk; its header then holds
 //              the union of their patterns and a slot whose own pattern is smaller
 //              keeps it in bits 24..31 (0 = the slot has the chunk's pattern).  Plans
 //              of matrices with more than 2^24 columns never share chunks and use all
 //              32 bits for the index.
-//   values     for every set row of the pattern in ascending row order UFK value
+//   values     for every set row of the pattern in ascending row order ufk value
 //              words (float bits, value of that row in column slot u; zero in
 //              unused slots and in slots whose own pattern lacks the row)
 //
 // The chunks of a row group are cut into *windows*, the unit a wave stages through
-// LDS: as many consecutive chunks as fit WIN_WORDS words.  `stream` holds the
+// LDS: as many consecutive chunks as fit win_words(ufk) words.  `stream` holds the
 // windows back to back, each laid out as
 //   [ headers of its chunks, zero-padded to a multiple of 8 words ]
-//   [ columns of its chunks, UFK words each ]
+//   [ columns of its chunks, ufk words each ]
 //   [ values of its chunks, back to back ]
 // so a chunk's header and columns sit at fixed strides and only its value offset
-// is a running sum (UFK * popcount(pattern) per chunk).
+// is a running sum (ufk * popcount(pattern) per chunk).
 //   wins[i]    one word per window: bits 0..15 chunks, bits 16..31 words
 //   hdr[c]     host-side copy of all headers in launch order (introspection only)
 constexpr uint32_t HDR_PATTERN_MASK = 0xFFu;
 constexpr int HDR_COUNT_SHIFT = 8;
-constexpr uint32_t HDR_COUNT_MASK = 0xFu;
-constexpr uint32_t HDR_END_PANEL = 1u << 12;
+constexpr uint32_t HDR_COUNT_MASK = 0x7Fu;
+constexpr uint32_t HDR_END_PANEL = 1u << 15;
 constexpr int COL_PATTERN_SHIFT = 24;
 constexpr uint32_t COL_INDEX_MASK = (1u << COL_PATTERN_SHIFT) - 1u;
 
-// Words of LDS one wave owns (its window; later its partial tile).
+// Words of LDS one wave owns (its window; later its partial tile): 1024 for chunks of 8 or
+// 16 columns, 2048 for wider chunks (a chunk of 64 columns of an eight-row panel is 577 words).
 constexpr int WIN_WORDS = 1024;
+constexpr int MAX_WIN_WORDS = 2048;
+constexpr int win_words(int ufk) { return ufk >= 32 ? MAX_WIN_WORDS : WIN_WORDS; }
 // Deepest software pipeline of any kernel instance: column slots of up to this
 // many chunks past a window's last chunk are read (and never used).
 constexpr int LOOKAHEAD = 8;
+constexpr int lookahead(int ufk) { return ufk > 8 ? 4 : LOOKAHEAD; }
 
 // Headers (all zero) appended after the last real chunk so that the kernels'
 // look-ahead never leaves the array.

@@ -34,7 +34,9 @@ struct spmm_launch_args {
 // columns; slices = 1: one column per lane, tile of up to 64 columns.  wide = 64-bit
 // addressing of B.  depth = chunks of B rows in flight (0 or anything deeper than the
 // instance's tuned depth = the tuned depth).  Returns the hipError_t of the launch as int.
-int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int slices, bool wide, int depth, void *stream);
+// ufk = columns per chunk of the plan: 8, or 16 / 32 / 64 with slices = 8 / 16 / 32 or 64 (tiles
+// of 32 / 16 / 8 or 4 columns; 32-bit addressing and the tuned depth only).
+int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int ufk, int slices, bool wide, int depth, void *stream);
 
 // Size of the library's statically allocated device scratch (one copy per device, held
 // until the process ends).

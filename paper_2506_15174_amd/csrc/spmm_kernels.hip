@@ -16,7 +16,7 @@
 //     when a panel ends (the warp-level reduction of Section 3.3.2).
 //   * The UFI x 4 accumulators of a panel stay in VGPRs across all chunks of the
 //     panel (the paper's register tile, Listing 6).
-//   * A chunk is UFK = 8 enumerated columns of one nonzero pattern (or leftovers
+//   * A chunk is UFKT = 8 (16, 32, 64 in plans made for narrow B) enumerated columns of one nonzero pattern (or leftovers
 //     of several patterns under the union of their patterns, with zeros where a
 //     column lacks a row).  Its column indices and values are staged through LDS,
 //     a window of the group's stream at a time, with coalesced 16-byte loads (the
@@ -199,14 +199,15 @@ template <int Q> __device__ __forceinline__ void lds_read(uint32_t (&out)[Q], co
 // blocks start at `at`: the block index is the number of pattern rows below r.
 // Clamped to `limit` so that the request stays inside the wave's window for rows
 // the pattern does not hold.
-__device__ __forceinline__ uint32_t value_block(uint32_t at, uint32_t pattern, int r, uint32_t limit)
+template <int UFKT> __device__ __forceinline__ uint32_t value_block(uint32_t at, uint32_t pattern, int r, uint32_t limit)
 {
-    const uint32_t w = at + (uint32_t)UFK * (uint32_t)__builtin_popcount(pattern & ((1u << r) - 1u));
+    const uint32_t w = at + (uint32_t)UFKT * (uint32_t)__builtin_popcount(pattern & ((1u << r) - 1u));
     return w < limit ? w : limit;
 }
 
 // UFI   rows per panel (1, 2, 4, 8): height of the register tile
-// S     slices per wave (1, 2, 4, 8); a slice has 64 / S lanes and UFK / S column slots per chunk
+// S     slices per wave (1, 2, 4, 8; 16, 32, 64 for narrow B); a slice has 64 / S lanes and UFKT / S column slots per chunk
+// UFKT  enumerated columns per chunk of the plan (8; 16, 32, 64 in plans made for narrow B)
 // VW    columns per lane (4 with 16-byte loads; 1 for the generic path, S == 1 only)
 // D     chunks of B rows in flight per wave
 // WIDE  64-bit addressing of B
@@ -216,10 +217,15 @@ __device__ __forceinline__ uint32_t value_block(uint32_t at, uint32_t pattern, i
 // it: 8 (64 VGPRs) with eight slices, 6 (80 VGPRs) with four, 4 (128 VGPRs)
 // with two.  The eight-row tile alone is 32 registers: 4 waves whatever the slices
 // (sized for 6, the eight-slice instance spilled 68 registers and ran 10-28 % slower).
-constexpr int waves_per_simd(int S, int UFI) { return UFI > 4 ? 4 : S >= 8 ? 8 : S >= 4 ? 6 : 4; }
+// Wider chunks (UFKT > 8) give a slice two column slots per chunk: budgets as for four slices of
+// an 8-column chunk; windows of 2048 words (UFKT >= 32) cap a compute unit at two workgroups.
+constexpr int waves_per_simd(int S, int UFI, int UFKT)
+{
+    return UFKT >= 32 ? 4 : UFI > 4 ? 4 : UFKT / S >= 2 && S >= 4 ? 6 : S >= 8 ? 8 : S >= 4 ? 6 : 4;
+}
 
-template <int UFI, int S, int VW, int D, bool WIDE>
-__global__ __launch_bounds__(64 * WAVES_PER_WG, (waves_per_simd(S, UFI))) void
+template <int UFI, int S, int VW, int D, bool WIDE, int UFKT = UFK>
+__global__ __launch_bounds__(64 * WAVES_PER_WG, (waves_per_simd(S, UFI, UFKT))) void
 spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                    const uint32_t *__restrict__ wins_g, const uint32_t *__restrict__ items_g,
                    const uint32_t *__restrict__ rowmap_g, const float *__restrict__ B_all, uint32_t b_bytes_all,
@@ -238,12 +244,13 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
     typedef typename Vec<VW>::type vec_t;
     typedef typename BSource<WIDE>::off_t off_t;
     constexpr int L = 64 / S;    // lanes per slice
-    constexpr int Q = UFK / S;   // column slots per slice and chunk
-    static_assert(UFK % S == 0 && VW * L * UFI * 4 <= WIN_WORDS * 4, "tile must fit the wave's window");
-    static_assert(D <= LOOKAHEAD, "the inspector keeps LOOKAHEAD chunks of column slots inside every window");
+    constexpr int Q = UFKT / S;  // column slots per slice and chunk
+    constexpr int WINW = win_words(UFKT);
+    static_assert(UFKT % S == 0 && VW * L * UFI * 4 <= WINW * 4, "tile must fit the wave's window");
+    static_assert(D <= lookahead(UFKT), "the inspector keeps so many chunks of column slots inside every window");
 
     // Per wave: the staged window of its stream; later the partial tile of a split panel.
-    __shared__ __attribute__((aligned(16))) uint32_t lds[WAVES_PER_WG][WIN_WORDS];
+    __shared__ __attribute__((aligned(16))) uint32_t lds[WAVES_PER_WG][WINW];
 
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
@@ -296,23 +303,23 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
             // ---- pipeline over the window's chunks.  Window layout: headers
-            //      (padded to 8 words), UFK column words per chunk, then the value
+            //      (padded to 8 words), UFKT column words per chunk, then the value
             //      blocks back to back.
             const uint32_t cols_base = ((wc + 7u) & ~7u) + slot0;
-            uint32_t at_val = ((wc + 7u) & ~7u) + wc * (uint32_t)UFK + slot0;  // values of the chunk multiplied next
+            uint32_t at_val = ((wc + 7u) & ~7u) + wc * (uint32_t)UFKT + slot0;  // values of the chunk multiplied next
             vec_t b[D][Q];
             off_t voff[Q];
 #pragma unroll
             for (int j = 0; j < D - 1; ++j) {
                 uint32_t cv[Q];
-                lds_read<Q>(cv, win, cols_base + (uint32_t)(j * UFK));
+                lds_read<Q>(cv, win, cols_base + (uint32_t)(j * UFKT));
                 const uint32_t ld_eff = (uint32_t)j < wc ? ld_bytes : 0u;
 #pragma unroll
                 for (int q = 0; q < Q; ++q) src.load(b[j][q], BSource<WIDE>::offset(col_index(cv[q]), ld_eff, lane_off));
             }
             {
                 uint32_t cv[Q];
-                lds_read<Q>(cv, win, cols_base + (uint32_t)((D - 1) * UFK));
+                lds_read<Q>(cv, win, cols_base + (uint32_t)((D - 1) * UFKT));
                 const uint32_t ld_eff = (uint32_t)(D - 1) < wc ? ld_bytes : 0u;
 #pragma unroll
                 for (int q = 0; q < Q; ++q) voff[q] = BSource<WIDE>::offset(col_index(cv[q]), ld_eff, lane_off);
@@ -320,7 +327,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
             // last word a slice may start a value read at (blocks are requested for
             // every row of the tile; those of rows outside the pattern are clamped
             // into the window and never used)
-            const uint32_t val_limit = (uint32_t)(WIN_WORDS - UFK) + slot0;
+            const uint32_t val_limit = (uint32_t)(WINW - UFKT) + slot0;
             uint32_t h_next = win[0];  // header of the chunk multiplied in the next step (same in all lanes)
             uint32_t c = 0;
             bool more = true;
@@ -333,7 +340,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                     // columns of chunk c+D for the next step; a chunk past the window's
                     // end reads row 0 through a zero pitch (its columns are never used)
                     uint32_t cv[Q];
-                    lds_read<Q>(cv, win, cols_base + (c + (uint32_t)D) * (uint32_t)UFK);
+                    lds_read<Q>(cv, win, cols_base + (c + (uint32_t)D) * (uint32_t)UFKT);
                     const uint32_t ld_next = c + (uint32_t)D < wc ? ld_bytes : 0u;
                     const uint32_t h_now = __builtin_amdgcn_readfirstlane(h_next);
                     h_next = win[c + 1];
@@ -347,8 +354,8 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                         // are never used), so the LDS latency hides behind it
                         uint32_t a[UFI][Q];
 #pragma unroll
-                        for (int r = 0; r < UFI; ++r) lds_read<Q>(a[r], win, value_block(at_val, pattern, r, val_limit));
-                        at_val += (uint32_t)UFK * (uint32_t)__builtin_popcount(pattern);
+                        for (int r = 0; r < UFI; ++r) lds_read<Q>(a[r], win, value_block<UFKT>(at_val, pattern, r, val_limit));
+                        at_val += (uint32_t)UFKT * (uint32_t)__builtin_popcount(pattern);
                         wait_for<(D - 1) * Q>(b[s]);
 #pragma unroll
                         for (int r = 0; r < UFI; ++r) {
@@ -368,7 +375,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                                 lds_read<Q>(a, win, at_val);
 #pragma unroll
                                 for (int q = 0; q < Q; ++q) fma_acc(acc[r], __uint_as_float(a[q]), b[s][q]);
-                                at_val += (uint32_t)UFK;
+                                at_val += (uint32_t)UFKT;
                             }
                         }
                     }
@@ -389,6 +396,18 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                         if constexpr (S >= 8) {
 #pragma unroll
                             for (int r = 0; r < UFI; ++r) add_across<8>(acc[r]);
+                        }
+                        if constexpr (S >= 16) {
+#pragma unroll
+                            for (int r = 0; r < UFI; ++r) add_across<4>(acc[r]);
+                        }
+                        if constexpr (S >= 32) {
+#pragma unroll
+                            for (int r = 0; r < UFI; ++r) add_across<2>(acc[r]);
+                        }
+                        if constexpr (S >= 64) {
+#pragma unroll
+                            for (int r = 0; r < UFI; ++r) add_across<1>(acc[r]);
                         }
                         const uint32_t rows_here = rows_left < (uint32_t)UFI ? rows_left : (uint32_t)UFI;
                         if (slice == 0) {
@@ -480,9 +499,9 @@ spmm_cross_combine_kernel(const uint32_t *__restrict__ table, const float *__res
     store_cols(C_all + (size_t)e[CE_ROW0 + r] * (size_t)ldn + col0 + c, total, width - c);
 }
 
-template <int U, int S, int VW, int D, bool WIDE> void launch_instance(const spmm_launch_args &a, void *stream)
+template <int U, int S, int VW, int D, bool WIDE, int UFKT = UFK> void launch_instance(const spmm_launch_args &a, void *stream)
 {
-    hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE>), dim3((unsigned)a.n_blocks, (unsigned)a.n_tiles),
+    hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE, UFKT>), dim3((unsigned)a.n_blocks, (unsigned)a.n_tiles),
                        dim3(64 * WAVES_PER_WG), a.lds_pad, (hipStream_t)stream, a.stream, a.wins, a.items, a.rowmap,
                        a.B, a.b_bytes, a.C, a.ldn, a.width, a.tile_cols, a.col_mask, a.cross_sums, a.n_cross_slots);
 }
@@ -515,13 +534,39 @@ template <int U, int D2, int D4, int D8> void launch_slices(const spmm_launch_ar
     }
 }
 
+// Plans made for narrow B (chunks of 16, 32 or 64 columns): one instance per height and chunk
+// width pair, at the tuned depth, 32-bit addressing only.  slices: 8 (tile of 32 columns,
+// chunks of 16), 16 (16 columns, chunks of 32), 32 or 64 (8 or 4 columns, chunks of 64).
+template <int U, int D> bool launch_narrow(const spmm_launch_args &a, int ufk, int slices, void *stream)
+{
+    if (ufk == 16 && slices == 8) launch_instance<U, 8, 4, D, false, 16>(a, stream);
+    else if (ufk == 32 && slices == 16) launch_instance<U, 16, 4, D, false, 32>(a, stream);
+    else if (ufk == 64 && slices == 32) launch_instance<U, 32, 4, D, false, 64>(a, stream);
+    else if (ufk == 64 && slices == 64) launch_instance<U, 64, 4, (D > 4 ? 4 : D), false, 64>(a, stream);
+    else return false;
+    return true;
+}
+
 }  // namespace
 
 // The depth table (instances per height: 2, 4, 8 slices): kept in step with
 // spmm_default_depth below.
-int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int slices, bool wide, int depth, void *stream)
+int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int ufk, int slices, bool wide, int depth, void *stream)
 {
     if (a.n_blocks <= 0 || a.n_tiles <= 0) return 0;
+    if (ufk != UFK) {
+        bool ok = !wide;
+        if (ok) {
+            switch (ufi) {
+            case 8: ok = launch_narrow<8, 4>(a, ufk, slices, stream); break;
+            case 4: ok = launch_narrow<4, 3>(a, ufk, slices, stream); break;
+            case 2: ok = launch_narrow<2, 4>(a, ufk, slices, stream); break;
+            case 1: ok = launch_narrow<1, 4>(a, ufk, slices, stream); break;
+            default: ok = false;
+            }
+        }
+        if (!ok) return (int)hipErrorInvalidValue;
+    } else
     switch (ufi) {
     case 8: launch_slices<8, 2, 4, 4>(a, slices, wide, depth, stream); break;
     case 4: launch_slices<4, 3, 3, 4>(a, slices, wide, depth, stream); break;

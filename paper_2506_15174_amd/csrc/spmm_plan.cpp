@@ -133,6 +133,19 @@ int choose_ufi_skewed(int64_t K, int64_t nnz, int64_t max_row, int32_t n_hint, b
     return h;
 }
 
+// Columns per chunk.  A slice of a wave (the lanes that share one row of B, four columns
+// per lane) should own two column slots of every chunk: with one slot per slice the fixed
+// work per chunk (header, row branches, offsets) outweighs its multiply-adds.  B of up to 32
+// columns runs on 8 slices (16 columns per chunk), up to 16 columns on 16 slices (32), up to
+// 8 columns on 32 slices (64).  Matrices of more than 2^24 columns keep 8: their column
+// words hold no slot pattern and their B needs 64-bit addressing, which only the kernels for
+// chunks of 8 have.
+int choose_ufk(int64_t K, int32_t n_hint)
+{
+    if (K > ((int64_t)1 << COL_PATTERN_SHIFT) || n_hint <= 0 || n_hint > 32) return 8;
+    return n_hint > 16 ? 16 : n_hint > 8 ? 32 : 64;
+}
+
 // Nonzero budget G of a row group and the cap GP on the panels one group packs.
 // P panels of mean weight `mean`:
 //   * fewer than 4096 panels: a typical panel is cut into ppt = min(8, ceil(8192 / P))
@@ -183,11 +196,12 @@ bool skewed_rows(const int32_t *row_ptr, int64_t M, int64_t nnz)
 }
 
 struct Emitter {
-    // creation order: one header per chunk, UFK column slots per chunk, and the
-    // chunks' value blocks back to back (UFK words per set pattern row)
+    // creation order: one header per chunk, ufk column slots per chunk, and the
+    // chunks' value blocks back to back (ufk words per set pattern row)
     std::vector<uint32_t> hdr, cols, vals;
     int64_t n_enum = 0;
     int ufi = MAX_UFI;
+    int UFK = spmm_fmt::UFK;      // columns per chunk of this plan
     bool merge = true;            // leftovers of different patterns may share a chunk
     std::vector<Entry> leftovers; // scratch of panel()
 
@@ -223,7 +237,7 @@ struct Emitter {
 
     // Emits the chunks of one panel (or one piece of a panel) whose entries are
     // ordered so that equal patterns are adjacent: first the full chunks of every
-    // pattern, then the leftovers (fewer than UFK entries per pattern), packed UFK
+    // pattern, then the leftovers (fewer than ufk entries per pattern), packed ufk
     // at a time in pattern order.  A leftover chunk costs one step of the kernel
     // whatever it holds, so sharing it between patterns saves both B loads and
     // multiply slots: the paper's compaction of rarely used enumerated blocks
@@ -433,7 +447,10 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         const int64_t GP = out.group_panels;
         std::vector<Group> groups = make_groups(plan_ptr, M, ufi, G, GP, cross);
         out.ufi = ufi;
+        out.ufk = valid_ufk(opts.ufk) && K <= ((int64_t)1 << COL_PATTERN_SHIFT) ? opts.ufk : choose_ufk(K, opts.n_hint);
         const int UFI = ufi;  // panel height of this plan
+        const int UFK = out.ufk;  // columns per chunk of this plan (shadows the default)
+        const int WINW = win_words(UFK), LOOK = lookahead(UFK);
         const int N_PATTERNS = (1 << UFI) - 1;
         const int SPLIT_PANELS_PER_WG = WAVES_PER_WG / UFI;
         const int64_t n_groups = (int64_t)groups.size();
@@ -577,6 +594,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         std::vector<Emitter> parts(n_ranges);
         for (size_t t = 0; t < n_ranges; ++t) {
             parts[t].ufi = UFI;
+            parts[t].UFK = UFK;
             parts[t].merge = merge_leftovers;
             const int64_t share = cuts[t + 1] > cuts[t] ? (int64_t)groups[(size_t)cuts[t + 1] - 1].nnz_end -
                                                               groups[(size_t)cuts[t]].nnz_begin
@@ -677,7 +695,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                     const int64_t words = hdr_w + (wc + 1) * UFK + vw + add;
                     // the kernels read column slots up to LOOKAHEAD chunks past the last
                     // one (values never used): those reads must stay inside the window
-                    if (words > WIN_WORDS || hdr_w + (wc + 1 + LOOKAHEAD) * UFK > WIN_WORDS) break;
+                    if (words > WINW || hdr_w + (wc + 1 + LOOK) * UFK > WINW) break;
                     wc += 1;
                     vw += add;
                 }

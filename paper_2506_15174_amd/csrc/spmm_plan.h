@@ -9,6 +9,7 @@
 struct HostPlan {
     int64_t M = 0, K = 0, nnz = 0;
     int32_t ufi = 0;           // rows per panel (8, 4, 2 or 1)
+    int32_t ufk = 8;           // enumerated columns per chunk (8, 16, 32 or 64)
     int32_t group_nnz = 0;     // nonzero budget per row group
     int32_t group_panels = 0;  // panel cap per row group
 
@@ -38,7 +39,8 @@ struct InspectorOptions {
     int32_t n_hint = 0;        // B columns the plan is meant for; 0 = unknown
     int32_t sort_rows = 0;     // 0 = choose; > 0 = sort rows by length; < 0 = keep the row order
     int32_t threads = 0;       // 0 = choose; else host threads of the enumeration (1..64)
-    int32_t cross = 0;         // 0 = panels may be cut across blocks; < 0 = never (at most one block per panel)
+    int32_t cross = 0;         // 0 = choose whether panels may be cut across blocks; < 0 = never; > 0 = always
+    int32_t ufk = 0;           // 0 = choose; else columns per chunk: 8, 16, 32 or 64
 };
 
 // Status codes follow spmm_status_t (0 ok, 1 invalid argument, 2 invalid CSR,

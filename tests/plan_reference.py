@@ -258,10 +258,20 @@ def check_blocks(items, ufi, rowmap=None):
     return slots_used
 
 
-def walk_chunks(it, hdr, stream, wins):
+def win_words(ufk):
+    return 2048 if ufk >= 32 else WIN_WORDS
+
+
+def lookahead(ufk):
+    return 4 if ufk > 8 else LOOKAHEAD
+
+
+def walk_chunks(it, hdr, stream, wins, ufk=UFK):
     """Yields (header word, column slots, [value block per set row]) for every chunk
     of one wave slot, following the windows and checking the window table and the
-    host-side header copy."""
+    host-side header copy.  ufk: columns per chunk of the plan."""
+    UFK = ufk
+    WIN_WORDS, LOOKAHEAD = win_words(ufk), lookahead(ufk)
     row0, nrows, chunk0, nchunks, stream0, flags = (int(x) for x in it[:6])
     win0, nwins = int(it[10]), int(it[11])
     assert int(it[12]) == (int(wins[win0]) if nwins else 0), "descriptor's copy of the first window entry"
@@ -269,7 +279,7 @@ def walk_chunks(it, hdr, stream, wins):
     c = chunk0
     for w in range(win0, win0 + nwins):
         wc, ww = int(wins[w]) & 0xFFFF, int(wins[w]) >> 16
-        assert 1 <= wc and ww <= WIN_WORDS and ww % UFK == 0
+        assert 1 <= wc and ww <= WIN_WORDS and ww % 8 == 0
         assert -(-wc // 8) * 8 + (wc + LOOKAHEAD) * UFK <= WIN_WORDS, "look-ahead column reads leave the window"
         hdr_words = -(-wc // 8) * 8
         assert not stream[at + wc:at + hdr_words].any()
@@ -289,7 +299,7 @@ def walk_chunks(it, hdr, stream, wins):
     assert c == chunk0 + nchunks
 
 
-def decode_plan(items, hdr, stream, wins, ufi, rowmap=None, K=0):
+def decode_plan(items, hdr, stream, wins, ufi, rowmap=None, K=0, ufk=UFK):
     """Chunk arrays -> (row, col, value bits) arrays in the order the kernel
     consumes them.  Also checks the structural invariants of the format and
     raises AssertionError on any violation.  K: columns of the matrix; beyond 2^24
@@ -297,6 +307,7 @@ def decode_plan(items, hdr, stream, wins, ufi, rowmap=None, K=0):
     check_blocks(items, ufi, rowmap)
     wide_cols = K > (1 << COL_PATTERN_SHIFT)
     index_mask = 0xFFFFFFFF if wide_cols else COL_INDEX_MASK
+    UFK = ufk
     to_c = (lambda r: int(rowmap[r])) if rowmap is not None and len(rowmap) else (lambda r: r)
     items = items.reshape(-1, ITEM_WORDS)
     out_rows, out_cols, out_bits = [], [], []
@@ -307,9 +318,9 @@ def decode_plan(items, hdr, stream, wins, ufi, rowmap=None, K=0):
             continue
         row = row0
         rows_left = nrows
-        for h, cc, blocks in walk_chunks(it, hdr, stream, wins):
-            pattern, count, end = h & 255, (h >> 8) & 15, (h >> 12) & 1
-            assert h >> 13 == 0 and count <= UFK
+        for h, cc, blocks in walk_chunks(it, hdr, stream, wins, ufk):
+            pattern, count, end = h & 255, (h >> 8) & 127, (h >> 15) & 1
+            assert h >> 16 == 0 and count <= UFK
             assert (count == 0) == (pattern == 0)
             if count == 0:
                 assert end, "an empty chunk is the only chunk of an empty panel"
@@ -351,7 +362,7 @@ def decode_plan(items, hdr, stream, wins, ufi, rowmap=None, K=0):
             np.array(out_bits, dtype=np.uint32))
 
 
-def interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap=None, K=0):
+def interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap=None, K=0, ufk=UFK):
     """Evaluates C from the chunk arrays in float32, block by block, chunk by
     chunk, FMA by FMA (row blocks in ascending row, slots in ascending order;
     pieces of a split panel added in slot order by the wave slot the table names).
@@ -371,15 +382,15 @@ def interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap=None, K=0):
                 continue
             acc = np.zeros((ufi, N), dtype=np.float32)
             row, rows_left = row0, nrows
-            for h, cc, vblocks in walk_chunks(it, hdr, stream, wins):
-                pattern, end = h & 255, (h >> 12) & 1
+            for h, cc, vblocks in walk_chunks(it, hdr, stream, wins, ufk):
+                pattern, end = h & 255, (h >> 15) & 1
                 t = 0
                 for r in range(ufi):
                     if not (pattern >> r) & 1:
                         continue
                     fv = vblocks[t].view(np.float32)
                     t += 1
-                    for u in range(UFK):
+                    for u in range(ufk):
                         a = np.float64(fv[u])
                         # fused multiply-add: exact product and sum in double, one rounding
                         acc[r] = (a * B64[int(cc[u]) & index_mask] + acc[r].astype(np.float64)).astype(np.float32)

@@ -270,6 +270,46 @@ def test_every_kernel_instance_is_bit_exact_on_integer_data(torch_gpu, oracle, u
     assert np.array_equal(C.astype(np.float64), C_ref)
 
 
+NARROW_INSTANCES = [(ufi, ufk, N) for ufi in (1, 2, 4, 8) for ufk, N in ((16, 32), (32, 16), (64, 8), (64, 4))]
+
+
+@pytest.mark.parametrize("ufi,ufk,N", NARROW_INSTANCES,
+                         ids=["UFI%d-UFK%d-S%d" % (u, k, 256 // n) for u, k, n in NARROW_INSTANCES])
+def test_every_narrow_b_kernel_instance_is_bit_exact_on_integer_data(torch_gpu, oracle, ufi, ufk, N):
+    """The instances for plans made for narrow B: chunks of 16 / 32 / 64 enumerated columns
+    on waves cut into 8 / 16 / 32 or 64 slices (tiles of 32 / 16 / 8 / 4 columns).  Same
+    demands as above: integer data, bit-exact, groups much longer than the pipeline."""
+    rng = np.random.default_rng(7000 + 100 * ufi + ufk + N)
+    M, K = 67, 4000
+    W = np.where(rng.random((M, K)) < 0.3, rng.integers(-8, 9, (M, K)), 0).astype(np.float32)
+    W[5] = rng.integers(1, 9, K)
+    W[[9, 10, 11, 12, 13, 14, 15, 16]] = 0
+    csr = gen.csr_from_dense(W)
+    B = rng.integers(-16, 17, (K, N)).astype(np.float32)
+    C, plan = gpu_product(torch_gpu, csr, B, guard_rows=2, group_nnz=1024, ufi=ufi, ufk=ufk)
+    info = plan.describe()
+    assert (info["ufi"], info["ufk"]) == (ufi, ufk) and info["n_split"] > 0
+    assert info["n_chunks"] > 6 * info["n_groups"] > 0
+    C_ref, _ = oracle.spmm(csr.row_ptr, csr.col_idx, csr.vals, B)
+    assert np.abs(C_ref).max() < 2 ** 24
+    assert np.array_equal(C.astype(np.float64), C_ref)
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 8, 12, 16, 17, 31, 32, 33, 70, 130])
+@pytest.mark.parametrize("hint", [4, 8, 16, 32])
+def test_plans_made_for_narrow_b_compute_every_width(torch_gpu, oracle, hint, N):
+    """A plan created with a narrow hint (chunks of 64 / 64 / 32 / 16 columns for hints of
+    4 / 8 / 16 / 32 columns) stays valid for every N: wider B runs as several of the plan's
+    narrow column tiles, the last one masked.  Ragged rows, dense rows (split panels, and
+    with cross = 1 panels cut across workgroups), empty rows, M % 8 != 0."""
+    csr = heavy_tail(39, 1500, 140 + hint)
+    B = gen.dense_activations(csr.K, N, 150 + N)
+    for ufi, cross in ((0, 0), (4, 1), (8, 0)):
+        C, plan = gpu_product(torch_gpu, csr, B, guard_rows=3, group_nnz=96, ufi=ufi, n_hint=hint, cross=cross)
+        assert plan.describe()["ufk"] == {4: 64, 8: 64, 16: 32, 32: 16}[hint]
+        check(oracle, csr, B, C)
+
+
 @pytest.mark.parametrize("depth", [1, 2, 3, 4, 8])
 def test_pipeline_depth_setting_does_not_change_the_result(torch_gpu, oracle, depth):
     """The depth of the software pipeline (spmm_options_t.depth) only changes when a B

@@ -315,7 +315,7 @@ def test_format_round_trip_is_bit_exact(name, group_nnz, force_ufi, sort_rows):
     assert np.array_equal(cc[order], want_cols)
     assert np.array_equal(bits[order], want_bits)
     info = plan.describe()
-    counts = (hdr[:info["n_chunks"]] >> 8) & 15
+    counts = (hdr[:info["n_chunks"]] >> 8) & 127
     assert int(counts.sum()) == info["n_enum"]
     assert len(hdr) >= info["n_chunks"] + 10 and not hdr[info["n_chunks"]:].any()
     pc = np.array([bin(int(h) & 255).count("1") for h in hdr[:info["n_chunks"]]])
@@ -325,7 +325,7 @@ def test_format_round_trip_is_bit_exact(name, group_nnz, force_ufi, sort_rows):
 def slot_patterns(h, cols):
     """(own pattern, column index) of the real slots of a chunk: a slot's pattern is
     the top byte of its column word, or the chunk's when that byte is 0."""
-    return [((int(c) >> 24) or (int(h) & 255), int(c) & 0xFFFFFF) for c in cols[:(int(h) >> 8) & 15]]
+    return [((int(c) >> 24) or (int(h) & 255), int(c) & 0xFFFFFF) for c in cols[:(int(h) >> 8) & 127]]
 
 
 def test_leftovers_of_different_patterns_share_chunks():
@@ -343,9 +343,9 @@ def test_leftovers_of_different_patterns_share_chunks():
     assert info["n_chunks"] == 2 and info["n_enum"] == 15
     chunks = [c for it in items.reshape(-1, 16) if not int(it[5]) & 2 for c in walk_chunks(it, hdr, stream, wins)]
     (h0, c0, v0), (h1, c1, v1) = chunks
-    assert h0 & 255 == 0b0001 and (h0 >> 8) & 15 == 8 and not (h0 >> 12) & 1
+    assert h0 & 255 == 0b0001 and (h0 >> 8) & 127 == 8 and not (h0 >> 15) & 1
     assert [x for _, x in slot_patterns(h0, c0)] == list(range(8)) and all(int(c) >> 24 == 0 for c in c0)
-    assert h1 & 255 == 0b1111 and (h1 >> 8) & 15 == 7 and (h1 >> 12) & 1
+    assert h1 & 255 == 0b1111 and (h1 >> 8) & 127 == 7 and (h1 >> 15) & 1
     assert slot_patterns(h1, c1) == [(1, 8), (1, 9), (6, 10), (6, 11), (6, 12), (8, 13), (8, 14)]
     # four value blocks (rows 0..3); a slot holds zeros in the rows it lacks
     f = [b.view(np.float32) for b in v1]
@@ -373,7 +373,7 @@ def test_unsorted_and_duplicate_columns_are_canonicalised():
     for it in items.reshape(-1, 16):
         if not int(it[5]) & 2:
             for h, cols, _ in walk_chunks(it, hdr, stream, wins):
-                slots += [int(c) & 0xFFFFFF for c in cols[:(h >> 8) & 15]]
+                slots += [int(c) & 0xFFFFFF for c in cols[:(h >> 8) & 127]]
     assert slots.count(7) == 2 and slots.count(2) == 2
     # within a row, duplicates keep their stored order (3 after 1 for column 7 of row 0)
     B = np.eye(8, dtype=np.float32)
@@ -496,9 +496,11 @@ def test_random_matrices_and_settings_round_trip(seed):
     ufi = int(rng.choice([0, 1, 2, 4, 8]))
     group_nnz = int(rng.choice([0, 8, 40, 300]))
     sort_rows = int(rng.choice([-1, 0, 1]))
-    hint = int(rng.choice([0, 32, 64, 128]))
-    plan = host_plan(csr, group_nnz=group_nnz, ufi=ufi, sort_rows=sort_rows, n_hint=hint)
+    hint = int(rng.choice([0, 4, 8, 16, 32, 64, 128]))
+    ufk = int(rng.choice([0, 0, 8, 16, 32, 64]))
+    plan = host_plan(csr, group_nnz=group_nnz, ufi=ufi, sort_rows=sort_rows, n_hint=hint, ufk=ufk)
     info = plan.describe()
+    assert info["ufk"] == (ufk or (8 if hint == 0 or hint > 32 else 16 if hint > 16 else 32 if hint > 8 else 64))
     want_ufi, want_sorted = choose_schedule(csr.row_ptr, M, K, hint, ufi, sort_rows)
     assert (info["ufi"], info["sorted_rows"]) == (want_ufi, int(want_sorted))
     rowmap, plan_ptr = plan_rows(csr, plan)
@@ -506,13 +508,13 @@ def test_random_matrices_and_settings_round_trip(seed):
                                  cross=cross_allowed(csr.row_ptr))
     assert np.array_equal(plan.get_groups(), want) and blocks == info["n_blocks"]
     items, hdr, stream, wins = arrays(plan)
-    rows, cc, bits = decode_plan(items, hdr, stream, wins, info["ufi"], rowmap)
+    rows, cc, bits = decode_plan(items, hdr, stream, wins, info["ufi"], rowmap, ufk=info["ufk"])
     # the same multiset of (row, column, value): values of a column stored twice in a row keep their order
     want_rows, want_cols, want_bits = canonical_csr(csr.row_ptr, csr.col_idx, csr.vals)
     got = sorted(zip(rows.tolist(), cc.tolist(), bits.tolist()))
     assert got == sorted(zip(want_rows.tolist(), want_cols.tolist(), want_bits.tolist()))
     B = rng.integers(-4, 5, (K, 3)).astype(np.float32)
-    C = interpret_plan(items, hdr, stream, wins, B, M, info["ufi"], rowmap)
+    C = interpret_plan(items, hdr, stream, wins, B, M, info["ufi"], rowmap, ufk=info["ufk"])
     dense = np.zeros((M, K), dtype=np.float64)
     np.add.at(dense, (np.repeat(np.arange(M), np.diff(csr.row_ptr)), csr.col_idx), csr.vals.astype(np.float64))
     assert np.array_equal(C.astype(np.float64), dense @ B.astype(np.float64))
@@ -596,7 +598,7 @@ def test_column_words_at_and_beyond_the_24_bit_boundary(K, ufi):
     for it in items.reshape(-1, 16):
         if not int(it[5]) & 2:
             for h, cw, _ in walk_chunks(it, hdr, stream, wins):
-                col_words += [int(w) for w in cw[:(h >> 8) & 15]]
+                col_words += [int(w) for w in cw[:(h >> 8) & 127]]
     tagged = [w for w in col_words if w >> 24]
     if K > (1 << 24):
         # all index: any top byte is part of a column number of 2^24 or more
