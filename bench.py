@@ -477,9 +477,9 @@ def run_tune(args):
             auto.destroy()
             best = None
             for ufi in (1, 2, 4, 8):
-                g0 = spmm.plan_create(*a, ufi=ufi, host_only=True).describe()["group_nnz"]
+                g0 = spmm.plan_create(*a, ufi=ufi, n_hint=N, host_only=True).describe()["group_nnz"]
                 for g in sorted({max(32, g0 // 2), g0, min(1024, g0 * 2)}):
-                    plan = spmm.plan_create(*a, ufi=ufi, group_nnz=g)
+                    plan = spmm.plan_create(*a, ufi=ufi, group_nnz=g, n_hint=N)
                     us = _time_plan(torch, plan, B, C, N, reps=5)
                     plan.destroy()
                     if best is None or us < best[0]:

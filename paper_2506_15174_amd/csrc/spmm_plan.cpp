@@ -60,9 +60,12 @@ struct Entry {
 //     rows on with row >= 1024 (16384 x 16384 at 90 %: 434 against 521 us; at
 //     98 %, row 327, single rows win 118 against 159 us);
 //   * narrow B (hint <= 32 columns): one wave load already covers eight enumerated
-//     columns, so tall panels save few loads and pay with a longer dependent chain
-//     per chunk: four rows only from 4096 rows on with row >= 1024; two rows for
-//     512 .. 4095 rows with row >= 256; else single rows;
+//     columns, so tall panels save fewer loads: from 4096 rows on eight rows with
+//     row >= 768 and four with row >= 384 in rows at least an eighth full (chunks of 16
+//     columns, two per slice: 4096 x 4096
+//     at 50 % 27.7 against 32.3 us with four rows, 4096 x 1024 at 50 % 10.2 with four rows
+//     against 12.7 us with single rows); two rows for 512 .. 4095 rows with row >= 256;
+//     else single rows;
 //   * medium B (hint 33 .. 64): eight rows from 4096 rows on with row >= 256; two
 //     rows for 512 .. 4095 rows with row >= 64; else single rows;
 //   * wide or unknown B: eight rows from 4096 rows on with row >= 192; for 1024 ..
@@ -86,7 +89,7 @@ int choose_ufi(int64_t M, int64_t K, int64_t nnz, int32_t n_hint)
         return 1;
     }
     if (narrow) {
-        if (M >= 4096) return row >= 1024 ? 4 : 1;
+        if (M >= 4096) return row >= 768 ? 8 : row >= 384 && 8 * row >= K ? 4 : 1;
         if (M >= 512) return row >= 256 ? 2 : 1;
         return 1;
     }
@@ -154,13 +157,20 @@ int choose_ufk(int64_t K, int32_t n_hint)
 //     ceil(P / 8192) of them (at most 16) share a wave.
 // G = ceil(5 mean GP / (4 ppt)), rounded up to a multiple of 32 inside [32, 1024];
 // the quarter of headroom keeps panels near the mean on the typical piece count.
-void choose_group_budget(int64_t M, int64_t nnz, int ufi, int32_t &G_out, int32_t &GP_out)
+// Single rows of a matrix of 1024 .. 2047 rows meant for B of at most 64 columns are not cut
+// below 256 entries (rows shorter than that stay whole): such products take 3 to 5 us, and
+// waves of 32 to 64 entries cost them 10 to 20 % in start-up (every wave first fetches its
+// descriptor, its first window and its first rows of B) and in workgroups to dispatch.
+// Wider B and matrices of fewer rows need the finer cut to occupy the chip.
+void choose_group_budget(int64_t M, int64_t nnz, int ufi, int32_t n_hint, int32_t &G_out, int32_t &GP_out)
 {
     const int64_t P = std::max<int64_t>(1, (M + ufi - 1) / ufi);
     const int64_t mean = (nnz + P - 1) / P;
     const int64_t ppt = P < 4096 ? std::min<int64_t>(8, (8192 + P - 1) / P) : 1;
     const int64_t GP = std::min<int64_t>(16, std::max<int64_t>(1, (P + 8191) / 8192));
     int64_t g = (5 * mean * GP + 4 * ppt - 1) / (4 * ppt);
+    if (ufi == 1 && M >= 1024 && M < 2048 && n_hint > 0 && n_hint <= 64)
+        g = std::max<int64_t>(g, std::min<int64_t>((5 * mean + 3) / 4, 256));
     g = (g + 31) / 32 * 32;
     if (g < 32) g = 32;
     if (g > 1024) g = 1024;
@@ -436,7 +446,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         const int32_t *plan_ptr = sorted ? sorted_ptr.data() : row_ptr;
         // ---- 1. group budget and row groups, from the row pointer alone ----------
         int32_t auto_g = 0, auto_gp = 0;
-        choose_group_budget(M, nnz, ufi, auto_g, auto_gp);
+        choose_group_budget(M, nnz, ufi, opts.n_hint, auto_g, auto_gp);
         // heavy panels cut as finely as needed: half the budget, so that the launch is made of
         // lighter pieces throughout (measured with the heights above: stress matrix 162 -> 154 us,
         // 8192 x 8192 lognormal rows of sigma 1.5 94 -> 81 us at 128 columns, 60 -> 53 us at 64)

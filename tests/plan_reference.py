@@ -92,7 +92,7 @@ def choose_ufi(M, K, nnz, n_hint=0):
         return 8 if (wide_tiles and M >= 4096 and row >= 1024) else 1
     if narrow:
         if M >= 4096:
-            return 4 if row >= 1024 else 1
+            return 8 if row >= 768 else 4 if (row >= 384 and 8 * row >= K) else 1
         return 2 if (M >= 512 and row >= 256) else 1
     if medium:
         if M >= 4096:
@@ -166,13 +166,15 @@ def sorted_row_order(row_ptr):
     return order, np.concatenate(([0], np.cumsum(lens[order])))
 
 
-def choose_group_budget(M, nnz, ufi):
+def choose_group_budget(M, nnz, ufi, n_hint=0):
     """(nonzero budget, panel cap) of a row group for panels of `ufi` rows."""
     P = max(1, -(-M // ufi))
     mean = -(-nnz // P)
     ppt = min(8, -(-8192 // P)) if P < 4096 else 1
     GP = min(16, max(1, -(-P // 8192)))
     g = -(-(5 * mean * GP) // (4 * ppt))
+    if ufi == 1 and 1024 <= M < 2048 and 0 < n_hint <= 64:   # single rows of small matrices for narrow B: not cut below 256 entries
+        g = max(g, min(-(-(5 * mean) // 4), 256))
     g = -(-g // 32) * 32
     return min(1024, max(32, g)), GP
 

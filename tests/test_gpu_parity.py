@@ -480,11 +480,11 @@ def test_stress_config_whole_product_at_full_size(torch_gpu, oracle):
     assert not C[lens == 0].any()
 
 
-@pytest.mark.parametrize("N,want_ufi", [(128, 8), (64, 8), (32, 4)])
+@pytest.mark.parametrize("N,want_ufi", [(128, 8), (64, 8), (32, 8)])
 def test_largest_sweep_entry_whole_product_at_full_size(torch_gpu, oracle, N, want_ufi):
     """The largest matrix of the sweep (8192 x 8192, half of the entries kept) in the
-    launch configuration the benchmark times: eight-row panels for 64 and 128 columns,
-    four-row panels for 32; every element against the oracle, with guard rows around C."""
+    launch configuration the benchmark times (eight-row panels at every width, chunks of 16
+    columns for 32 columns of B); every element against the oracle, with guard rows around C."""
     entry = [e for e in gen.sweep_entries() if e["M"] == 8192 and e["sparsity"] == 0.5][0]
     csr = gen.sweep_matrix(entry)
     B = gen.activations_for(csr, N)

@@ -146,19 +146,26 @@ SCHEDULE_CASES = [
     ((512, 2048, 410, 32), (2, 160, 1)),
     # ... but rows of 200 stay single: 512 panels of 200 -> 8 pieces -> ceil(5*200/32) = 32
     ((512, 2048, 200, 32), (1, 32, 1)),
+    # 1024 single rows of 100 for narrow B are not cut: 125 -> 128; for wide B 8 pieces -> 16 -> 32
+    ((1024, 1024, 100, 32), (1, 128, 1)),
+    ((1024, 1024, 30, 128), (1, 32, 1)),
+    # ... and rows of 400 for 64 columns (2 rows from rows of 64 on) are unaffected: 512 panels of 800 -> 125 -> 128
+    ((1024, 4096, 400, 64), (2, 128, 1)),
     # 4096 x 1024 at 50 %, wide B: 8 rows; 512 panels of 4096 -> 8 pieces -> 640
     ((4096, 1024, 512, 128), (8, 640, 1)),
-    # narrow B, rows of 512 < 1024: single rows; 4096 whole rows -> 640
-    ((4096, 1024, 512, 32), (1, 640, 1)),
+    # narrow B, 384 <= rows of 512 < 768, half full: four rows; 1024 panels of 2048 -> 8 pieces -> 5*2048/32 = 320
+    ((4096, 1024, 512, 32), (4, 320, 1)),
+    # ... rows of 400 in 4096 columns are less than an eighth full: single rows
+    ((4096, 4096, 400, 32), (1, 512, 1)),
     # rows of 52 < 192: single rows; 4096 whole rows of 52 -> 65 -> 96
     ((4096, 1024, 52, 0), (1, 96, 1)),
     # 256 rows: too few panels for tall ones; 256 rows of 128 -> 8 pieces -> 20 -> 32
     ((256, 256, 128, 128), (1, 32, 1)),
     # 32768 single rows: 4 panels share a wave, budget 5*8*4/4 = 40 -> 64
     ((32768, 1024, 8, 0), (1, 64, 4)),
-    # 8192 x 8192 at 50 %, narrow B: rows of 4096 >= 1024 -> 4 rows; 2048 panels -> 4 pieces, capped
-    ((8192, 8192, 4096, 32), (4, 1024, 1)),
-    # ... medium and wide B: 8 rows; 1024 panels -> 8 pieces, capped
+    # 8192 x 8192 at 50 %, narrow B: rows of 4096 >= 768 -> 8 rows; 1024 panels -> 8 pieces, capped
+    ((8192, 8192, 4096, 32), (8, 1024, 1)),
+    # ... medium and wide B: 8 rows as well
     ((8192, 8192, 4096, 64), (8, 1024, 1)),
     ((8192, 8192, 4096, 128), (8, 1024, 1)),
     # 64 columns of B: 8 rows from 4096 rows on when rows hold 256 or more
@@ -186,7 +193,7 @@ def test_schedule_constants_rule(case, want):
     assert (info["ufi"], info["group_nnz"], info["group_panels"]) == want
     nnz = M * per_row
     ufi = choose_ufi(M, K, nnz, hint)
-    assert (ufi,) + choose_group_budget(M, nnz, ufi) == want
+    assert (ufi,) + choose_group_budget(M, nnz, ufi, hint) == want
 
 
 def _plan_from_row_lengths(lens, K, **kw):
