@@ -188,12 +188,17 @@ def tiles_of_64(N, K):
     return N > 64 and K * 512 > 4 << 20 and K * 256 <= 4 << 20
 
 
-def kernel_shape(N, ufi, K=0):
+def kernel_shape(N, ufi, K=0, ufk=8):
     """Template arguments of the instance spmm_execute launches for a tile of N columns
-    (N a multiple of 4, at most 128) of a plan with panels of `ufi` rows: slices per
-    wave, floats per lane, pipeline depth (the table of spmm_launch_chunks).  When 128
-    columns of B exceed one L2 and 64 fit (8192 < K <= 16384) the product runs as two
-    tiles of 64 columns."""
+    (N a multiple of 4, at most 128) of a plan with panels of `ufi` rows and chunks of
+    `ufk` columns: slices per wave, floats per lane, pipeline depth (the tables of
+    spmm_launch_chunks).  When 128 columns of B exceed one L2 and 64 fit
+    (8192 < K <= 16384) the product runs as two tiles of 64 columns.  Plans made for
+    narrow B (ufk 16 / 32 / 64) run on 8 / 16 / 32 or 64 slices."""
+    if ufk != 8:
+        S = {16: 8, 32: 16}.get(ufk, 64 if N <= 4 else 32)
+        depth = {8: 4, 4: 3, 2: 4, 1: 4}[ufi]
+        return "S=%d,VW=4,D=%d,UFK=%d" % (S, depth, ufk)
     depth = {8: (2, 4, 4), 4: (3, 3, 4), 2: (3, 4, 6), 1: (3, 4, 8)}[ufi]
     if tiles_of_64(N, K):
         return "S=4,VW=4,D=%d, tiles of 64 columns" % depth[1]
@@ -447,6 +452,14 @@ def run_ablation(args):
                       "summary": summary, "points": pts}))
 
 
+# Shapes the schedule rule was not fitted on (the rule's thresholds come from the sweep's 30
+# larger matrices): the tuning run reports the rule's loss on these separately.
+HELD_OUT = [dict(M=2048, K=8192, sparsity=0.7, seed=7001), dict(M=2048, K=8192, sparsity=0.95, seed=7002),
+            dict(M=3072, K=768, sparsity=0.5, seed=7003), dict(M=3072, K=768, sparsity=0.9, seed=7004),
+            dict(M=6144, K=1536, sparsity=0.8, seed=7005), dict(M=2048, K=2048, sparsity=0.6, seed=7006),
+            dict(M=768, K=3072, sparsity=0.8, seed=7007), dict(M=12288, K=3072, sparsity=0.9, seed=7008)]
+
+
 def run_tune(args):
     """Offline tuning run (paper Section 3.5): every panel height and three group budgets
     forced on each of the 30 larger sweep matrices per column count; reports what the
@@ -460,8 +473,9 @@ def run_tune(args):
     cols = (32, 64, 128)
     pts = []
     t_start = time.perf_counter()
-    for entry in _ladder_matrices(gen):
-        csr = gen.sweep_matrix(entry)
+    entries = [dict(e, heldout=False) for e in _ladder_matrices(gen)] + [dict(e, heldout=True) for e in HELD_OUT]
+    for entry in entries:
+        csr = gen.magnitude_pruned(entry["M"], entry["K"], entry["sparsity"], entry["seed"])
         nnz = int(csr.row_ptr[-1])
         a = (csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals)
         for N in cols:
@@ -470,7 +484,8 @@ def run_tune(args):
             auto = spmm.plan_create(*a, n_hint=N)
             ai = auto.describe()
             _time_plan(torch, auto, B, C, N, reps=3)          # clocks up before the first figure
-            row = {"M": csr.M, "K": csr.K, "sparsity": entry["sparsity"], "N": N, "rule_ufi": ai["ufi"],
+            row = {"M": csr.M, "K": csr.K, "sparsity": entry["sparsity"], "N": N, "heldout": entry["heldout"],
+                   "rule_ufi": ai["ufi"],
                    "rule_group_nnz": ai["group_nnz"], "rule_us": round(_time_plan(torch, auto, B, C, N), 3),
                    "plan_bytes_over_csr": round(ai["device_bytes"] / (8.0 * nnz + 4 * (csr.M + 1)), 3),
                    "plan_bytes_over_dense": round(ai["device_bytes"] / (4.0 * csr.M * csr.K), 3)}
@@ -488,11 +503,14 @@ def run_tune(args):
                        rule_over_best=round(row["rule_us"] / best[0], 3))
             pts.append(row)
             print(json.dumps(row), file=sys.stderr, flush=True)
-    summary = {str(N): {"geomean_rule_over_best": round(_geomean([p["rule_over_best"] for p in pts if p["N"] == N]), 3),
-                        "worst": max(p["rule_over_best"] for p in pts if p["N"] == N)} for N in cols}
+    def loss(sel):
+        return {str(N): {"geomean_rule_over_best": round(_geomean([p["rule_over_best"] for p in sel if p["N"] == N]), 3),
+                         "worst": max(p["rule_over_best"] for p in sel if p["N"] == N)} for N in cols}
+    summary = loss([p for p in pts if not p["heldout"]])
+    summary_heldout = loss([p for p in pts if p["heldout"]])
     size = {}
-    for sp in sorted({p["sparsity"] for p in pts}):
-        sel = [p for p in pts if p["sparsity"] == sp and p["N"] == 128]
+    for sp in sorted({p["sparsity"] for p in pts if not p["heldout"]}):
+        sel = [p for p in pts if p["sparsity"] == sp and p["N"] == 128 and not p["heldout"]]
         size[str(sp)] = {"plan_over_csr": round(_geomean([p["plan_bytes_over_csr"] for p in sel]), 3),
                          "plan_over_dense": round(_geomean([p["plan_bytes_over_dense"] for p in sel]), 3)}
     print(json.dumps({"metric": "time of the rule's plan / time of the best forced plan (geomean)",
@@ -500,10 +518,11 @@ def run_tune(args):
                       "higher_is_better": False, "dtype": "f32", "data": "synthetic",
                       "config": {"workload": "tuning run on 30 sweep matrices (M, K >= 1024) x bCols 32/64/128",
                                  "wall_s": round(time.perf_counter() - t_start, 1)},
-                      "summary": summary, "plan_size_by_sparsity_bcols128": size, "points": pts}))
+                      "summary": summary, "summary_heldout": summary_heldout,
+                      "plan_size_by_sparsity_bcols128": size, "points": pts}))
 
 
-def kernel_report(torch, csr, plan, info, B, C, N, workload_key, samples=20):
+def kernel_report(torch, csr, plan, info, B, C, N, workload_key, samples=20, plan_kw=None):
     """Roofline block of one launch: algorithmic bytes over the launch's average duration
     (HIP events on the launch stream) against the HBM peak, the rate of wave-wide loads of
     B rows against the measured gather ceiling, the share of the fp32 vector peak."""
@@ -513,7 +532,7 @@ def kernel_report(torch, csr, plan, info, B, C, N, workload_key, samples=20):
     achieved = bmin / (avg_ms * 1e-3) / 1e9
     kernel_tflops = 2.0 * nnz * N / (avg_ms * 1e-3) / 1e12
     traffic, prov = measured_traffic(workload_key, N)
-    shape = kernel_shape(N, info["ufi"], csr.K)
+    shape = kernel_shape(N, info["ufi"], csr.K, info["ufk"])
     roofline = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic, "traffic_source": prov,
                 "kernel": "spmm_chunks_kernel<UFI=%d,%s> (bCols %d)" % (info["ufi"], shape, N),
@@ -521,16 +540,30 @@ def kernel_report(torch, csr, plan, info, B, C, N, workload_key, samples=20):
                 "avg_launch_us": round(avg_ms * 1e3, 3), "median_launch_us": round(med_ms * 1e3, 3),
                 "launches_per_execute": 1, "algorithmic_bytes": bmin, "kernel_tflops": round(kernel_tflops, 3),
                 "frac_of_fp32_valu_peak": round(kernel_tflops / FP32_VALU_PEAK_TFLOPS, 5)}
-    # On-chip gather: each chunk of 8 enumerated columns costs 8 / S wave-wide loads of B
+    # On-chip gather: each chunk of ufk enumerated columns costs ufk / S wave-wide loads of B
     # rows (S rows of B per load); the ceiling is the rate the gather microbenchmark
     # reaches on distinct rows of an L2-resident B.
-    S = {"S=2": 2, "S=4": 4, "S=8": 8}[shape[:3]]
-    tiles = 2 if tiles_of_64(N, csr.K) else 1
-    wave_loads = info["n_chunks"] * 8 // S * tiles
+    S = int(shape.split(",")[0][2:])
+    tiles = 2 if (info["ufk"] == 8 and tiles_of_64(N, csr.K)) else 1
+    wave_loads = info["n_chunks"] * info["ufk"] // S * tiles
     roofline["gather"] = {"wave_loads_per_launch": wave_loads,
                           "g_wave_loads_per_s": round(wave_loads / (avg_ms * 1e-3) / 1e9, 2),
                           "measured_ceiling": GATHER_CEILING_GWLS,
                           "frac": round(wave_loads / (avg_ms * 1e-3) / 1e9 / GATHER_CEILING_GWLS, 4)}
+    # The ceiling of the plan's own index stream: the same plan as a measuring plan, whose
+    # launches request and await every B row as the product does and skip the multiply-adds.
+    try:
+        import paper_2506_15174_amd as spmm
+        kw = dict(plan_kw if plan_kw is not None else {"n_hint": N})
+        probe = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, probe=True, **kw)
+        scratch_c = torch.empty_like(C)
+        p_avg, _ = time_execute(torch, probe, B, scratch_c, N, samples=samples)
+        probe.destroy()
+        roofline["gather"].update({"loads_only_us": round(p_avg * 1e3, 3),
+                                   "loads_only_over_product": round(p_avg / avg_ms, 4)})
+    except Exception as exc:   # a measuring plan is refused for 64-bit addressing and chunks wider than 16
+        roofline["gather"]["loads_only_us"] = None
+        roofline["gather"]["loads_only_note"] = repr(exc)
     return roofline
 
 
@@ -655,7 +688,11 @@ def run_headline(args):
                                  "hipsparse_best_us": stress_base.get("hipsparse_best_us"),
                                  "rocblas_sgemm_us": stress_base.get("rocblas_sgemm_us")},
                       "wall_s": round(time.perf_counter() - t_start, 1)},
-           "roofline": roofline, "cpu_baseline": cpu, "summary": summary, "points": points}
+           "roofline": roofline, "cpu_baseline": cpu, "summary": summary}
+    if args.points_file:
+        with open(args.points_file, "w") as f:
+            json.dump(points, f)
+    # the per-point figures went to stderr as they were measured; the line stays short
     print(json.dumps(out))
 
 
@@ -705,7 +742,8 @@ def run_single(args):
     # dominant kernel: the widest column count; one launch per execute there (column tiles
     # of one width share a launch)
     Nd = max(cols)
-    roofline = kernel_report(torch, csr, plans[Nd], infos[Nd], Bs[Nd], Cs[Nd], Nd, args.workload)
+    roofline = kernel_report(torch, csr, plans[Nd], infos[Nd], Bs[Nd], Cs[Nd], Nd, args.workload,
+                             plan_kw=dict(n_hint=Nd, ufi=args.ufi))
 
     per_cols = {}
     for N in cols:
@@ -758,6 +796,7 @@ def main():
     ap.add_argument("--ufi", type=int, default=0, help="single workloads: force the rows per panel (1, 2, 4, 8)")
     ap.add_argument("--depth", type=int, default=0,
                     help="single workloads: chunks of B rows in flight per wave (1, 2, 3, 4, 8; 0 = tuned)")
+    ap.add_argument("--points-file", default="", help="headline: also write the per-point figures to this JSON file")
     ap.add_argument("--no-baselines", action="store_true")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-cold", action="store_true",

@@ -94,6 +94,12 @@ typedef struct {
                               force_wide).  A plan with wider chunks computes every N on column tiles
                               of 32 / 16 / 8 (or 4) columns and cannot address a B beyond 4 GiB
                               (spmm_execute then returns SPMM_ERR_UNSUPPORTED). */
+    int32_t probe;         /* nonzero: a measuring plan.  spmm_execute requests and awaits every row
+                              of B exactly as the product does but skips the multiply-adds, and C
+                              becomes all zeros: the time of such an execute is the on-chip gather
+                              ceiling of this plan's own index stream.  Not combinable with
+                              force_wide, depth or chunks wider than 16 columns (SPMM_ERR_INVALID_ARG);
+                              a B that needs 64-bit addressing is refused (SPMM_ERR_UNSUPPORTED). */
 } spmm_options_t;
 
 /*

@@ -46,7 +46,7 @@ class Options(ctypes.Structure):
                 ("host_only", ctypes.c_int32), ("ufi", ctypes.c_int32),
                 ("n_hint", ctypes.c_int32), ("sort_rows", ctypes.c_int32),
                 ("force_wide", ctypes.c_int32), ("threads", ctypes.c_int32), ("depth", ctypes.c_int32),
-                ("cross", ctypes.c_int32), ("ufk", ctypes.c_int32)]
+                ("cross", ctypes.c_int32), ("ufk", ctypes.c_int32), ("probe", ctypes.c_int32)]
 
 
 class SpmmError(RuntimeError):
@@ -191,7 +191,7 @@ class Plan:
 
 
 def plan_create(M, K, row_ptr, col_idx, vals, group_nnz=0, group_panels=0, host_only=False, ufi=0,
-                n_hint=0, sort_rows=0, force_wide=False, threads=0, depth=0, cross=0, ufk=0):
+                n_hint=0, sort_rows=0, force_wide=False, threads=0, depth=0, cross=0, ufk=0, probe=False):
     """spmm_plan_create / spmm_plan_create_ex on numpy host arrays."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
@@ -199,9 +199,9 @@ def plan_create(M, K, row_ptr, col_idx, vals, group_nnz=0, group_panels=0, host_
     handle = ctypes.c_void_p()
     lib = load()
     if group_nnz or group_panels or host_only or ufi or n_hint or sort_rows or force_wide or threads or depth \
-            or cross or ufk:
+            or cross or ufk or probe:
         opts = Options(int(group_nnz), int(group_panels), 1 if host_only else 0, int(ufi), int(n_hint),
-                       int(sort_rows), 1 if force_wide else 0, int(threads), int(depth), int(cross), int(ufk))
+                       int(sort_rows), 1 if force_wide else 0, int(threads), int(depth), int(cross), int(ufk), 1 if probe else 0)
         st = lib.spmm_plan_create_ex(ctypes.byref(handle), int(M), int(K), _ptr(row_ptr),
                                      _ptr(col_idx), _ptr(vals), ctypes.byref(opts))
     else:

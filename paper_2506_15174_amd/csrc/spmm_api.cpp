@@ -29,6 +29,7 @@ struct spmm_plan {
     int64_t stream_words = 0;  // length of host.stream at creation (a device plan drops its host mirror)
     bool force_wide = false;  // spmm_options_t.force_wide: 64-bit addressing kernels also on small inputs
     int depth = 0;            // spmm_options_t.depth: pipeline depth asked for (0 = per-instance default)
+    bool probe = false;       // spmm_options_t.probe: loads-only launches (measurement)
 };
 
 namespace {
@@ -83,7 +84,7 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
     if (!plan) return SPMM_ERR_INVALID_ARG;
     *plan = nullptr;
     InspectorOptions io;
-    bool host_only = false, force_wide = false;
+    bool host_only = false, force_wide = false, probe = false;
     int depth = 0;
     if (opts) {
         if (opts->group_nnz < 0 || opts->group_panels < 0 || opts->n_hint < 0) return SPMM_ERR_INVALID_ARG;
@@ -106,6 +107,8 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
         force_wide = opts->force_wide != 0;
         if (force_wide) io.ufk = UFK;  // the 64-bit addressing kernels read chunks of 8 columns
         depth = opts->depth;
+        probe = opts->probe != 0;
+        if (probe && (force_wide || depth != 0 || (io.ufk != 0 && io.ufk > 16))) return SPMM_ERR_INVALID_ARG;
     }
     spmm_plan *p = new (std::nothrow) spmm_plan();
     if (!p) return SPMM_ERR_ALLOC;
@@ -116,6 +119,7 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
     }
     p->force_wide = force_wide;
     p->depth = depth;
+    p->probe = probe;
     if (!host_only) {
         if (hipGetDevice(&p->device) != hipSuccess) {
             delete p;
@@ -204,6 +208,8 @@ spmm_status_t execute_with(const spmm_plan_t *plan, const float *B, int32_t N, f
     a.cross_table = plan->d_cross_table;
     a.n_cross_slots = (uint32_t)h.n_cross_slots;
     a.n_cross = (int32_t)h.n_cross;
+    a.probe = plan->probe;
+    if (plan->probe && (wide || h.ufk > 16)) return SPMM_ERR_UNSUPPORTED;
     // the scratch of panels cut across workgroups holds so many column tiles of one launch
     const int32_t max_tiles = h.n_cross_slots > 0 ? cross_tiles : 65535;
     // A 128-column tile of B that exceeds one L2 (4 MiB) while a 64-column tile fits: two

@@ -21,6 +21,7 @@ struct spmm_launch_args {
     int32_t n_tiles;        // column tiles of this launch (grid y)
     uint32_t col_mask;      // bits of a column word that hold the column index
     uint32_t lds_pad = 0;   // extra LDS bytes per workgroup (never touched): caps the workgroups per CU
+    bool probe = false;     // launch the loads-only instance (32-bit addressing, tuned depth, chunks of 8 or 16)
     // Panels cut across workgroups (plans with n_cross > 0; else unused):
     float *cross_sums = nullptr;          // DEVICE n_tiles x n_cross_slots slots of ufi x 128 floats (scratch)
     const uint32_t *cross_table = nullptr;// DEVICE one entry per such panel: slots and rows of C

@@ -224,7 +224,10 @@ constexpr int waves_per_simd(int S, int UFI, int UFKT)
     return UFKT >= 32 ? 4 : UFI > 4 ? 4 : UFKT / S >= 2 && S >= 4 ? 6 : S >= 8 ? 8 : S >= 4 ? 6 : 4;
 }
 
-template <int UFI, int S, int VW, int D, bool WIDE, int UFKT = UFK>
+// PROBE instances request and await every B row exactly as the product does but skip the
+// value reads and the multiply-adds (C becomes all zeros): the time of such a launch is the
+// on-chip gather ceiling of the plan's own index stream.
+template <int UFI, int S, int VW, int D, bool WIDE, int UFKT = UFK, bool PROBE = false>
 __global__ __launch_bounds__(64 * WAVES_PER_WG, (waves_per_simd(S, UFI, UFKT))) void
 spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                    const uint32_t *__restrict__ wins_g, const uint32_t *__restrict__ items_g,
@@ -348,7 +351,9 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                     // the enumerated block of chunk c (paper Listing 7); its B rows are
                     // older than the (D - 1) * Q loads issued since
                     const uint32_t pattern = h_now & HDR_PATTERN_MASK;
-                    if constexpr (S <= 2 && UFI <= 4) {
+                    if constexpr (PROBE) {
+                        wait_for<(D - 1) * Q>(b[s]);
+                    } else if constexpr (S <= 2 && UFI <= 4) {
                         // wide slices: request the value blocks of all UFI rows before
                         // the wait for the B rows (blocks of rows outside the pattern
                         // are never used), so the LDS latency hides behind it
@@ -499,9 +504,10 @@ spmm_cross_combine_kernel(const uint32_t *__restrict__ table, const float *__res
     store_cols(C_all + (size_t)e[CE_ROW0 + r] * (size_t)ldn + col0 + c, total, width - c);
 }
 
-template <int U, int S, int VW, int D, bool WIDE, int UFKT = UFK> void launch_instance(const spmm_launch_args &a, void *stream)
+template <int U, int S, int VW, int D, bool WIDE, int UFKT = UFK, bool PROBE = false>
+void launch_instance(const spmm_launch_args &a, void *stream)
 {
-    hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE, UFKT>), dim3((unsigned)a.n_blocks, (unsigned)a.n_tiles),
+    hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE, UFKT, PROBE>), dim3((unsigned)a.n_blocks, (unsigned)a.n_tiles),
                        dim3(64 * WAVES_PER_WG), a.lds_pad, (hipStream_t)stream, a.stream, a.wins, a.items, a.rowmap,
                        a.B, a.b_bytes, a.C, a.ldn, a.width, a.tile_cols, a.col_mask, a.cross_sums, a.n_cross_slots);
 }
@@ -513,6 +519,7 @@ template <int U, int S, int VW, int D, bool WIDE, int UFKT = UFK> void launch_in
 template <int U, int S, int VW, int DMAX, bool WIDE> void launch_depth(const spmm_launch_args &a, int depth, void *stream)
 {
     if constexpr (!WIDE) {
+        if (a.probe) return launch_instance<U, S, VW, DMAX, WIDE, UFK, true>(a, stream);
         if (depth == 1 && DMAX > 1) return launch_instance<U, S, VW, 1, WIDE>(a, stream);
         if (depth == 2 && DMAX > 2) return launch_instance<U, S, VW, 2, WIDE>(a, stream);
         if (depth == 3 && DMAX > 3) return launch_instance<U, S, VW, (DMAX > 3 ? 3 : DMAX), WIDE>(a, stream);
@@ -539,7 +546,8 @@ template <int U, int D2, int D4, int D8> void launch_slices(const spmm_launch_ar
 // chunks of 16), 16 (16 columns, chunks of 32), 32 or 64 (8 or 4 columns, chunks of 64).
 template <int U, int D> bool launch_narrow(const spmm_launch_args &a, int ufk, int slices, void *stream)
 {
-    if (ufk == 16 && slices == 8) launch_instance<U, 8, 4, D, false, 16>(a, stream);
+    if (a.probe && ufk == 16 && slices == 8) launch_instance<U, 8, 4, D, false, 16, true>(a, stream);
+    else if (ufk == 16 && slices == 8) launch_instance<U, 8, 4, D, false, 16>(a, stream);
     else if (ufk == 32 && slices == 16) launch_instance<U, 16, 4, D, false, 32>(a, stream);
     else if (ufk == 64 && slices == 32) launch_instance<U, 32, 4, D, false, 64>(a, stream);
     else if (ufk == 64 && slices == 64) launch_instance<U, 64, 4, (D > 4 ? 4 : D), false, 64>(a, stream);

@@ -27,6 +27,14 @@ def test_kernel_label_follows_the_launch_table():
         assert bench.kernel_shape(32, ufi) == "S=8,VW=4,D=%d" % d8
         # 128 columns of a 16384-row B exceed one L2, 64 fit: tiles of 64
         assert bench.kernel_shape(128, ufi, 16384).startswith("S=4,VW=4,D=%d" % d4)
+    # plans made for narrow B: chunks of 16 / 32 / 64 columns on 8 / 16 / 32 or 64 slices, depth by height
+    narrow = {int(u): int(d) for u, d in re.findall(r"case (\d): ok = launch_narrow<\d, (\d)>\(", src)}
+    assert sorted(narrow) == [1, 2, 4, 8]
+    for ufi, d in narrow.items():
+        assert bench.kernel_shape(32, ufi, ufk=16) == "S=8,VW=4,D=%d,UFK=16" % d
+        assert bench.kernel_shape(16, ufi, ufk=32) == "S=16,VW=4,D=%d,UFK=32" % d
+        assert bench.kernel_shape(8, ufi, ufk=64) == "S=32,VW=4,D=%d,UFK=64" % d
+        assert bench.kernel_shape(4, ufi, ufk=64) == "S=64,VW=4,D=%d,UFK=64" % d
     assert bench.tiles_of_64(128, 16384) and not bench.tiles_of_64(128, 8192)
     assert not bench.tiles_of_64(64, 16384) and not bench.tiles_of_64(128, 16385)
     # the executor's own condition, as written in its source

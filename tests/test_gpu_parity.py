@@ -388,6 +388,21 @@ def test_panels_cut_across_workgroups_in_a_replayed_graph(torch_gpu, oracle):
     check(oracle, csr, B.cpu().numpy(), C.cpu().numpy())
 
 
+def test_measuring_plans_load_everything_and_multiply_nothing(torch_gpu):
+    """probe = 1: the launches request every row of B as the product does and skip the
+    multiply-adds, so C is all zeros (never NaN: every element is still written); the
+    setting is refused together with forced 64-bit addressing, a depth or chunks wider than 16."""
+    csr = heavy_tail(70, 1800, 171)
+    for N, kw in ((128, dict(ufi=8)), (64, dict(ufi=4, cross=1, group_nnz=64)), (32, dict(n_hint=32, ufi=2)), (100, dict())):
+        B = gen.dense_activations(csr.K, N, 172)
+        C, plan = gpu_product(torch_gpu, csr, B, guard_rows=2, probe=True, **kw)
+        assert not C.any() and not np.isnan(C).any()
+    for bad in (dict(force_wide=True), dict(depth=2), dict(ufk=32)):
+        with pytest.raises(spmm.SpmmError) as err:
+            spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, probe=True, **bad)
+        assert err.value.status == spmm.SPMM_ERR_INVALID_ARG
+
+
 def test_plain_c_client_runs_on_the_device(tmp_path):
     """create -> execute -> destroy from plain C99 (no Python, no torch between the caller
     and the library): the client uploads B, runs the product and compares known elements."""
