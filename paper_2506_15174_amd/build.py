@@ -38,12 +38,41 @@ def is_stale():
 
 def _run(cmd, verbose):
     res = subprocess.run(cmd, capture_output=True, text=True)
-    noise = "is not a recognized feature for this target"
-    err = "\n".join(ln for ln in res.stderr.splitlines() if noise not in ln)
+    noise = ("is not a recognized feature for this target", "-Rpass-analysis=kernel-resource-usage")
+    import re
+    err = "\n".join(ln for ln in res.stderr.splitlines()
+                    if not any(n in ln for n in noise) and not re.match(r"^\s*(\d+)?\s*\|", ln))
     if verbose and err:
         print(err)
     if res.returncode != 0:
         raise RuntimeError("%s failed:\n%s" % (cmd[0], err))
+    return res.stderr
+
+
+def check_no_spills(remarks):
+    """The kernels issue their loads of B rows from inline assembly and await them later
+    (an explicit s_waitcnt): a register the compiler spills or copies in between would
+    carry stale data.  No instance may therefore use scratch memory at all: the compiler's
+    resource remarks (-Rpass-analysis=kernel-resource-usage) must report zero spilled
+    VGPRs and SGPRs and a zero scratch size for every kernel.  Returns the number of
+    kernels checked; raises with the offenders otherwise."""
+    import re
+    name, bad, seen = None, [], 0
+    for ln in remarks.splitlines():
+        m = re.search(r"Function Name: (\S+)", ln)
+        if m:
+            name = m.group(1)
+            seen += 1
+            continue
+        m = re.search(r"(VGPRs Spill|SGPRs Spill|ScratchSize \[bytes/lane\]): (\d+)", ln)
+        if m and name and int(m.group(2)) != 0:
+            bad.append("%s: %s = %s" % (name, m.group(1), m.group(2)))
+    if seen == 0:
+        raise RuntimeError("the compiler printed no resource remarks: the spill check did not run")
+    if bad:
+        raise RuntimeError("kernel instances use scratch memory (give them a larger register budget "
+                           "or a shallower pipeline):\n  " + "\n  ".join(bad))
+    return seen
 
 
 def build(verbose=False):
@@ -64,10 +93,15 @@ def build(verbose=False):
         if s.endswith(".hip"):
             cmd = [hipcc, "--offload-arch=gfx950",
                    # packed-fp32 forms are kept out of the generated code on purpose
-                   "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+                   "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                   "-Rpass-analysis=kernel-resource-usage"]
         else:
             cmd = [hipcc, "-x", "c++"]
-        _run(cmd + common + ["-c", os.path.join(CSRC, s), "-o", obj], verbose)
+        remarks = _run(cmd + common + ["-c", os.path.join(CSRC, s), "-o", obj], verbose)
+        if s.endswith(".hip"):
+            n = check_no_spills(remarks)
+            if verbose:
+                print("%s: %d kernel instances, none uses scratch memory" % (s, n))
         objects.append(obj)
     _run([hipcc, "-shared", "-fPIC"] + objects +
          ["-L", os.path.join(ROCM, "lib"), "-lamdhip64", "-pthread", "-o", LIB_PATH], verbose)

@@ -219,16 +219,21 @@ template <int UFKT> __device__ __forceinline__ uint32_t value_block(uint32_t at,
 // (sized for 6, the eight-slice instance spilled 68 registers and ran 10-28 % slower).
 // Wider chunks (UFKT > 8) give a slice two column slots per chunk: budgets as for four slices of
 // an 8-column chunk; windows of 2048 words (UFKT >= 32) cap a compute unit at two workgroups.
-constexpr int waves_per_simd(int S, int UFI, int UFKT)
+// Every budget is one the instance fits without spilling (the build checks it): a spilled
+// register could be the destination of a B row still in flight.  Four-row panels on eight
+// slices take 67 to 73 registers (6 waves); 64-bit addressing costs a register more per column
+// slot, so those instances get the budget of two waves fewer.
+constexpr int waves_per_simd(int S, int UFI, int UFKT, bool WIDE)
 {
-    return UFKT >= 32 ? 4 : UFI > 4 ? 4 : UFKT / S >= 2 && S >= 4 ? 6 : S >= 8 ? 8 : S >= 4 ? 6 : 4;
+    const int narrow = UFKT >= 32 ? 4 : UFI > 4 ? 4 : UFKT / S >= 2 && S >= 4 ? 6 : S >= 8 ? (UFI == 4 ? 6 : 8) : S >= 4 ? 6 : 4;
+    return WIDE ? (narrow > 4 ? narrow - 2 : 2) : narrow;
 }
 
 // PROBE instances request and await every B row exactly as the product does but skip the
 // value reads and the multiply-adds (C becomes all zeros): the time of such a launch is the
 // on-chip gather ceiling of the plan's own index stream.
 template <int UFI, int S, int VW, int D, bool WIDE, int UFKT = UFK, bool PROBE = false>
-__global__ __launch_bounds__(64 * WAVES_PER_WG, (waves_per_simd(S, UFI, UFKT))) void
+__global__ __launch_bounds__(64 * WAVES_PER_WG, (waves_per_simd(S, UFI, UFKT, WIDE))) void
 spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                    const uint32_t *__restrict__ wins_g, const uint32_t *__restrict__ items_g,
                    const uint32_t *__restrict__ rowmap_g, const float *__restrict__ B_all, uint32_t b_bytes_all,
@@ -415,25 +420,32 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                             for (int r = 0; r < UFI; ++r) add_across<1>(acc[r]);
                         }
                         const uint32_t rows_here = rows_left < (uint32_t)UFI ? rows_left : (uint32_t)UFI;
-                        if (slice == 0) {
+                        // The lane's place in its slice is worked out afresh here (an opaque lane
+                        // count the compiler cannot hoist), so that no lane constant but the byte
+                        // offset of the loads stays in a register across the chunk loop.
+                        int lane_now;
+                        asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_now));
+                        const int sl_now = lane_now % L;
+                        const int valid_now = width - sl_now * VW;
+                        if (lane_now < L) {   // slice 0 holds the sums
                             if (flags & FLAG_SPLIT) {
                                 // the window is dead by now (a piece ends with its panel)
 #pragma unroll
                                 for (int r = 0; r < UFI; ++r)
-                                    *reinterpret_cast<vec_t *>(win + (r * L + sl) * VW) = acc[r];
-                            } else if (active) {
+                                    *reinterpret_cast<vec_t *>(win + (r * L + sl_now) * VW) = acc[r];
+                            } else if (valid_now > 0) {
                                 if (rowmap_g) {
                                     // rows sorted by length: the plan's row `row + r` is another row of C
                                     cword_t *map = (cword_t *)(rowmap_g) + row;
 #pragma unroll
                                     for (int r = 0; r < UFI; ++r)
                                         if ((uint32_t)r < rows_here)
-                                            store_cols(C + (size_t)map[r] * (size_t)ldn + sl * VW, acc[r], valid);
+                                            store_cols(C + (size_t)map[r] * (size_t)ldn + sl_now * VW, acc[r], valid_now);
                                 } else {
-                                    float *c_panel = C + (size_t)row * (size_t)ldn + sl * VW;
+                                    float *c_panel = C + (size_t)row * (size_t)ldn + sl_now * VW;
 #pragma unroll
                                     for (int r = 0; r < UFI; ++r)
-                                        if ((uint32_t)r < rows_here) store_cols(c_panel + (size_t)r * ldn, acc[r], valid);
+                                        if ((uint32_t)r < rows_here) store_cols(c_panel + (size_t)r * ldn, acc[r], valid_now);
                                 }
                             }
                         }

@@ -47,3 +47,22 @@ def test_more_than_one_gpu_is_refused_with_a_message():
                        text=True, timeout=120)
     assert r.returncode != 0
     assert "one GPU" in (r.stdout + r.stderr)
+
+
+def test_build_refuses_kernel_instances_that_spill():
+    """The build parses the compiler's resource remarks and fails when any kernel instance
+    uses scratch memory (a spilled register could be an in-flight load destination)."""
+    import pytest
+    from paper_2506_15174_amd import build
+    ok = ("remark: k.hip:1:1: Function Name: kernel_a [-Rpass-analysis=kernel-resource-usage]\n"
+          "remark: k.hip:1:1:     VGPRs: 64 [-Rpass-analysis=kernel-resource-usage]\n"
+          "remark: k.hip:1:1:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]\n"
+          "remark: k.hip:1:1:     SGPRs Spill: 0 [-Rpass-analysis=kernel-resource-usage]\n"
+          "remark: k.hip:1:1:     VGPRs Spill: 0 [-Rpass-analysis=kernel-resource-usage]\n")
+    assert build.check_no_spills(ok) == 1
+    with pytest.raises(RuntimeError, match="kernel_a: VGPRs Spill = 3"):
+        build.check_no_spills(ok.replace("VGPRs Spill: 0", "VGPRs Spill: 3"))
+    with pytest.raises(RuntimeError, match="ScratchSize"):
+        build.check_no_spills(ok.replace("lane]: 0", "lane]: 16"))
+    with pytest.raises(RuntimeError, match="no resource remarks"):
+        build.check_no_spills("")
