@@ -95,6 +95,71 @@ template <int MASK> __device__ __forceinline__ void add_across(f32x4_t &a)
     a[3] += __shfl_xor(a[3], MASK);
 }
 
+// In-place addition of the slices' partial tiles across lanes.  A wave of S slices holds,
+// per tile row, four accumulators x0 .. x3 per lane (columns 4 sl + v of the tile, sl the
+// lane's place inside its slice of 64 / S lanes); the sum over the slices of column
+// 4 sl + v is wanted.  Slices are lane groups, so the sum runs over the lane bits above the
+// slice width:
+//   * bits inside a row of 16 lanes (8 and more slices): x += x rotated by 8 (4, 2, 1)
+//     lanes within the row, one DPP add per stage and register; every lane of a residue
+//     class then holds the class's sum;
+//   * bit 4 (four and more slices): the row swap (odd rows of one register against even
+//     rows of another) followed by one add turns two registers into one whose lane rows
+//     hold [a0 + a1, b0 + b1, a2 + a3, b2 + b3];
+//   * bit 5: the half swap (upper half of one register against the lower half of another)
+//     and one add turn two registers into one holding [a_lo + a_hi | b_lo + b_hi].
+// Two registers become one per swap stage, so the adds halve from stage to stage and no
+// stage needs a temporary per accumulator: the exchange through __shfl_xor cost 16 to 35
+// registers on top of the tile and the B rows in flight, which is what capped the pipeline
+// depth of the tall-panel instances.
+// Result: four and more slices: `lo` of lane l is the sum of column 4 sl + l / 16 (sl = l % L
+// for the lanes with l % 16 < L); two slices: `lo`, `hi` of lane l are the sums of columns
+// 4 (l % 32) + 2 (l / 32) and the next one.
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_unaligned_t __attribute__((ext_vector_type(2), aligned(4)));
+__device__ __forceinline__ float swap32_add(float a, float b)
+{
+    const u32x2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float swap16_add(float a, float b)
+{
+    const u32x2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+template <int ROR> __device__ __forceinline__ float ror_add(float a)
+{
+    return a + __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(a), 0x120 | ROR, 0xF, 0xF, false));
+}
+template <int S> __device__ __forceinline__ void fold_row(const f32x4_t &x, float &lo, float &hi)
+{
+    float x0 = x[0], x1 = x[1], x2 = x[2], x3 = x[3];
+    if constexpr (S >= 8) { x0 = ror_add<8>(x0); x1 = ror_add<8>(x1); x2 = ror_add<8>(x2); x3 = ror_add<8>(x3); }
+    if constexpr (S >= 16) { x0 = ror_add<4>(x0); x1 = ror_add<4>(x1); x2 = ror_add<4>(x2); x3 = ror_add<4>(x3); }
+    if constexpr (S >= 32) { x0 = ror_add<2>(x0); x1 = ror_add<2>(x1); x2 = ror_add<2>(x2); x3 = ror_add<2>(x3); }
+    if constexpr (S >= 64) { x0 = ror_add<1>(x0); x1 = ror_add<1>(x1); x2 = ror_add<1>(x2); x3 = ror_add<1>(x3); }
+    if constexpr (S >= 4) {
+        const float a = swap16_add(x0, x1);   // lane rows: [x0, x1, x0, x1] summed over the row pairs
+        const float b = swap16_add(x2, x3);   //            [x2, x3, x2, x3]
+        lo = swap32_add(a, b);                // lane rows: [x0, x1 | x2, x3] summed over all slices
+        hi = 0.0f;
+    } else {
+        lo = swap32_add(x0, x2);              // halves: [x0 | x2]
+        hi = swap32_add(x1, x3);              //         [x1 | x3]
+    }
+}
+// Tile column whose sum lane l holds after fold_row, and whether lane l is the one that stores it.
+template <int S> __device__ __forceinline__ int fold_col(int l)
+{
+    if constexpr (S >= 4) return 4 * (l % (64 / S)) + l / 16;
+    else return 4 * (l % 32) + 2 * (l / 32);
+}
+template <int S> __device__ __forceinline__ bool fold_owner(int l)
+{
+    if constexpr (S > 4) return (l % 16) < 64 / S;
+    else return true;
+}
+
 // Source of B rows.  Narrow: a raw buffer descriptor over the column tile's
 // bytes (hardware range check, 32-bit per-lane byte offset).  Wide: plain 64-bit
 // addressing for B beyond the narrow limits.
@@ -394,37 +459,43 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                     for (int q = 0; q < Q; ++q) voff[q] = BSource<WIDE>::offset(col_index(cv[q]), ld_next, lane_off);
 
                     if (__builtin_expect((h_now & HDR_END_PANEL) != 0, 0)) {
-                        // add the slices' partial tiles across lanes
-                        if constexpr (S >= 2) {
-#pragma unroll
-                            for (int r = 0; r < UFI; ++r) add_across<32>(acc[r]);
-                        }
-                        if constexpr (S >= 4) {
-#pragma unroll
-                            for (int r = 0; r < UFI; ++r) add_across<16>(acc[r]);
-                        }
-                        if constexpr (S >= 8) {
-#pragma unroll
-                            for (int r = 0; r < UFI; ++r) add_across<8>(acc[r]);
-                        }
-                        if constexpr (S >= 16) {
-#pragma unroll
-                            for (int r = 0; r < UFI; ++r) add_across<4>(acc[r]);
-                        }
-                        if constexpr (S >= 32) {
-#pragma unroll
-                            for (int r = 0; r < UFI; ++r) add_across<2>(acc[r]);
-                        }
-                        if constexpr (S >= 64) {
-#pragma unroll
-                            for (int r = 0; r < UFI; ++r) add_across<1>(acc[r]);
-                        }
                         const uint32_t rows_here = rows_left < (uint32_t)UFI ? rows_left : (uint32_t)UFI;
-                        // The lane's place in its slice is worked out afresh here (an opaque lane
+                        // The lane's place in the wave is worked out afresh here (an opaque lane
                         // count the compiler cannot hoist), so that no lane constant but the byte
                         // offset of the loads stays in a register across the chunk loop.
                         int lane_now;
                         asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_now));
+                        if constexpr (VW == 4 && S >= 2) {
+                            // The slices' partial tiles are added across lanes in place (fold_row):
+                            // afterwards lane l holds, per tile row, the sum of column fold_col(l)
+                            // (two adjacent columns when the wave has two slices).
+                            const int col = fold_col<S>(lane_now);
+                            const bool owner = fold_owner<S>(lane_now);
+                            cword_t *map = rowmap_g ? (cword_t *)(rowmap_g) + row : nullptr;
+#pragma unroll
+                            for (int r = 0; r < UFI; ++r) {
+                                float lo, hi;
+                                fold_row<S>(acc[r], lo, hi);
+                                if (flags & FLAG_SPLIT) {
+                                    // the window is dead by now (a piece ends with its panel)
+                                    if (owner) {
+                                        if constexpr (S == 2) *reinterpret_cast<float2 *>(win + r * L * VW + col) = float2{lo, hi};
+                                        else win[r * L * VW + col] = __float_as_uint(lo);
+                                    }
+                                } else if ((uint32_t)r < rows_here && owner && col < width) {
+                                    // rows sorted by length: the plan's row `row + r` is another row of C
+                                    const size_t c_row = map ? (size_t)map[r] : (size_t)row + (size_t)r;
+                                    float *dst = C + c_row * (size_t)ldn + col;
+                                    if constexpr (S == 2) {
+                                        if (col + 1 < width) *reinterpret_cast<f32x2_unaligned_t *>(dst) = f32x2_unaligned_t{lo, hi};
+                                        else *dst = lo;
+                                    } else {
+                                        *dst = lo;
+                                    }
+                                }
+                            }
+                        } else {
+                        // one column per lane, one slice: nothing to add across lanes
                         const int sl_now = lane_now % L;
                         const int valid_now = width - sl_now * VW;
                         if (lane_now < L) {   // slice 0 holds the sums
@@ -448,6 +519,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                                         if ((uint32_t)r < rows_here) store_cols(c_panel + (size_t)r * ldn, acc[r], valid_now);
                                 }
                             }
+                        }
                         }
                         row += rows_here;
                         rows_left -= rows_here;
