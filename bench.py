@@ -199,7 +199,7 @@ def kernel_shape(N, ufi, K=0, ufk=8):
         S = {16: 8, 32: 16}.get(ufk, 64 if N <= 4 else 32)
         depth = {8: 4, 4: 3, 2: 4, 1: 4}[ufi]
         return "S=%d,VW=4,D=%d,UFK=%d" % (S, depth, ufk)
-    depth = {8: (2, 4, 4), 4: (3, 3, 4), 2: (3, 4, 6), 1: (3, 4, 8)}[ufi]
+    depth = {8: (2, 3, 4), 4: (2, 3, 4), 2: (2, 2, 6), 1: (2, 2, 8)}[ufi]
     if tiles_of_64(N, K):
         return "S=4,VW=4,D=%d, tiles of 64 columns" % depth[1]
     if N > 64:

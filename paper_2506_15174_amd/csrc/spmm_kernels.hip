@@ -282,15 +282,27 @@ template <int UFKT> __device__ __forceinline__ uint32_t value_block(uint32_t at,
 // it: 8 (64 VGPRs) with eight slices, 6 (80 VGPRs) with four, 4 (128 VGPRs)
 // with two.  The eight-row tile alone is 32 registers: 4 waves whatever the slices
 // (sized for 6, the eight-slice instance spilled 68 registers and ran 10-28 % slower).
-// Wider chunks (UFKT > 8) give a slice two column slots per chunk: budgets as for four slices of
-// an 8-column chunk; windows of 2048 words (UFKT >= 32) cap a compute unit at two workgroups.
+// Waves per SIMD an instance is compiled for (its register budget: 512 / waves).  Measured on
+// the pruned-layer shapes with every depth forced: past two or three chunks in flight a deeper
+// pipeline buys nothing (the memory path, not the number of requests a wave has outstanding,
+// paces the gather), while every further resident wave hides more of the chunk's dependent
+// chain (header, row branches, value reads).  So each instance takes the shallowest pipeline
+// that keeps the loads flowing and the occupancy its tile allows: eight-row tiles 4 waves
+// (6 on four slices), four-row tiles 4 waves on two slices and 8 otherwise, shorter tiles 6 to
+// 8.  Wider chunks (UFKT > 8) give a slice two column slots per chunk: 6 waves (4 with eight
+// rows); windows of 2048 words (UFKT >= 32) cap a compute unit at two workgroups.
 // Every budget is one the instance fits without spilling (the build checks it): a spilled
-// register could be the destination of a B row still in flight.  Four-row panels on eight
-// slices take 67 to 73 registers (6 waves); 64-bit addressing costs a register more per column
-// slot, so those instances get the budget of two waves fewer.
+// register could be the destination of a B row still in flight.  64-bit addressing costs a
+// register more per column slot, so those instances get the budget of two waves fewer.
 constexpr int waves_per_simd(int S, int UFI, int UFKT, bool WIDE)
 {
-    const int narrow = UFKT >= 32 ? 4 : UFI > 4 ? 4 : UFKT / S >= 2 && S >= 4 ? 6 : S >= 8 ? (UFI == 4 ? 6 : 8) : S >= 4 ? 6 : 4;
+    const int narrow = UFKT >= 32  ? 4
+                       : UFKT == 16 ? (UFI > 4 ? 4 : 6)
+                       : S == 1     ? 4
+                       : UFI == 8   ? (S == 2 ? 4 : 6)
+                       : UFI == 4   ? (S == 2 ? 4 : 8)
+                       : UFI == 2   ? (S == 2 ? 6 : 8)
+                                    : 8;
     return WIDE ? (narrow > 4 ? narrow - 2 : 2) : narrow;
 }
 
@@ -612,9 +624,9 @@ template <int U, int S, int VW, int DMAX, bool WIDE> void launch_depth(const spm
     launch_instance<U, S, VW, DMAX, WIDE>(a, stream);
 }
 
-// Pipeline depths per height (D2, D4, D8 for 2, 4, 8 slices): as deep as the VGPRs of a
-// wave allow.  The eight-row tile holds 32 accumulators, which leaves room for fewer B
-// rows in flight.
+// Pipeline depths per height (D2, D4, D8 for 2, 4, 8 slices): the shallowest that keeps the
+// loads flowing (see waves_per_simd); one column slot per slice (8 slices) needs more chunks
+// in flight for the same number of requests.
 template <int U, int D2, int D4, int D8> void launch_slices(const spmm_launch_args &a, int slices, bool wide, int depth, void *stream)
 {
     switch (slices) {
@@ -632,8 +644,8 @@ template <int U, int D> bool launch_narrow(const spmm_launch_args &a, int ufk, i
 {
     if (a.probe && ufk == 16 && slices == 8) launch_instance<U, 8, 4, D, false, 16, true>(a, stream);
     else if (ufk == 16 && slices == 8) launch_instance<U, 8, 4, D, false, 16>(a, stream);
-    else if (ufk == 32 && slices == 16) launch_instance<U, 16, 4, D, false, 32>(a, stream);
-    else if (ufk == 64 && slices == 32) launch_instance<U, 32, 4, D, false, 64>(a, stream);
+    else if (ufk == 32 && slices == 16) launch_instance<U, 16, 4, (D > 4 ? 4 : D), false, 32>(a, stream);
+    else if (ufk == 64 && slices == 32) launch_instance<U, 32, 4, (D > 4 ? 4 : D), false, 64>(a, stream);
     else if (ufk == 64 && slices == 64) launch_instance<U, 64, 4, (D > 4 ? 4 : D), false, 64>(a, stream);
     else return false;
     return true;
@@ -660,10 +672,10 @@ int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int ufk, int slices, 
         if (!ok) return (int)hipErrorInvalidValue;
     } else
     switch (ufi) {
-    case 8: launch_slices<8, 2, 4, 4>(a, slices, wide, depth, stream); break;
-    case 4: launch_slices<4, 3, 3, 4>(a, slices, wide, depth, stream); break;
-    case 2: launch_slices<2, 3, 4, 6>(a, slices, wide, depth, stream); break;
-    case 1: launch_slices<1, 3, 4, 8>(a, slices, wide, depth, stream); break;
+    case 8: launch_slices<8, 2, 3, 4>(a, slices, wide, depth, stream); break;
+    case 4: launch_slices<4, 2, 3, 4>(a, slices, wide, depth, stream); break;
+    case 2: launch_slices<2, 2, 2, 6>(a, slices, wide, depth, stream); break;
+    case 1: launch_slices<1, 2, 2, 8>(a, slices, wide, depth, stream); break;
     default: return (int)hipErrorInvalidValue;
     }
     if (a.n_cross > 0)
@@ -705,7 +717,7 @@ int spmm_static_scratch(float **ptr, size_t *bytes)
 
 int spmm_default_depth(int ufi, int slices)
 {
-    static const int table[4][3] = {{3, 4, 8}, {3, 4, 6}, {3, 3, 4}, {2, 4, 4}};  // rows: height 1, 2, 4, 8
+    static const int table[4][3] = {{2, 2, 8}, {2, 2, 6}, {2, 3, 4}, {2, 3, 4}};  // rows: height 1, 2, 4, 8
     const int u = ufi == 8 ? 3 : ufi == 4 ? 2 : ufi == 2 ? 1 : 0;
     return slices == 2 ? table[u][0] : slices == 4 ? table[u][1] : slices == 8 ? table[u][2] : 3;
 }
