@@ -189,6 +189,13 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N,
 spmm_status_t spmm_execute_static(const spmm_plan_t *plan, const float *B, int32_t N,
                                   float *C, void *stream);
 
+/*
+ * The calls below manage and describe a plan.  The paper defines no counterpart for them
+ * (its transformed matrix lives as long as the generated program and is never inspected):
+ * they exist for ownership (destroy), for the bit-exact re-derivation of the row groups and
+ * the format round trip in the tests (describe, get_groups, get_array) and for messages.
+ */
+
 /* Frees the plan and its device memory.  NULL is a no-op returning SPMM_OK. */
 spmm_status_t spmm_plan_destroy(spmm_plan_t *plan);
 
@@ -204,7 +211,8 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
  *                        group of whole panels this equals the range
  *                        ptr[row_begin] .. ptr[row_end] of the row pointer of the
  *                        plan's row order (row_ptr itself unless rows are sorted)
- *   flags                bit 0: the group is one piece of a split panel
+ *   flags                bit 0: the group is one piece of a split panel; bit 3: of a panel
+ *                        cut into more pieces than a workgroup has waves (info.n_cross)
  * Order: pieces of split panels first (heaviest panel first, pieces in order),
  * then groups of whole panels (heaviest first); ties keep row order.
  *   out  HOST int32[5 * cap];  cap must be >= info.n_groups.
@@ -218,10 +226,10 @@ spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_
  * call returns SPMM_ERR_INVALID_ARG.  Layouts are those the kernels read:
  *   SPMM_ARRAY_HDR     one word per chunk, launch order (host-side copy): bits 0-7
  *                      pattern (panel rows that own a value in some column of the
- *                      chunk), bits 8-11 number of real columns, bit 12 last chunk
- *                      of its panel
+ *                      chunk), bits 8-14 number of real columns (at most info.ufk),
+ *                      bit 15 last chunk of its panel
  *   SPMM_ARRAY_WINS    one word per LDS staging window of a group: bits 0-15 chunks,
- *                      bits 16-31 words (at most 1024)
+ *                      bits 16-31 words (at most 1024; 2048 when info.ufk is 32 or 64)
  *   SPMM_ARRAY_STREAM  the windows back to back, each as: the headers of its chunks
  *                      (zero-padded to a multiple of 8 words); ufk column words per
  *                      chunk (bits 0-23 the column index, unused slots repeat a real
@@ -233,19 +241,28 @@ spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_
  *   SPMM_ARRAY_ITEMS   16 words per wave slot, 8 slots per workgroup, launch order:
  *                      first row, rows, first chunk, chunks, first record word, flags
  *                      (1 piece of a split panel, 2 idle slot, 4 workgroup with split
- *                      panels), the slot's share of the split-panel sums (pieces to
- *                      add, first piece's slot, tile row, row of C), first window,
- *                      windows, a copy of the first window's SPMM_ARRAY_WINS entry
+ *                      panels, 8 workgroup of a panel cut across workgroups), the
+ *                      slot's share of the split-panel sums (pieces to add, first
+ *                      piece's slot, tile row, row of C), first window, windows, a copy
+ *                      of the first window's SPMM_ARRAY_WINS entry, and for a panel cut
+ *                      across workgroups the number of its workgroups, the scratch slot
+ *                      of its first one and this workgroup's place among them
  *                      (rows are rows of the plan, except the row of C, which is
  *                      always a row of the matrix)
  *   SPMM_ARRAY_ROWMAP  M words when info.sorted_rows is set, else none: the row of
  *                      A and C that each row of the plan stands for (rows by
  *                      decreasing length, equal lengths in ascending row order)
+ *   SPMM_ARRAY_CROSS   12 words per panel cut across workgroups (info.n_cross entries, in the
+ *                      order their workgroups are launched): first scratch slot, workgroups,
+ *                      rows of the panel, one unused word, then the row of C of each of the
+ *                      panel's rows (8 words, unused ones 0): the input of the launch that
+ *                      adds the workgroups' sums
  *   out   HOST, cap_words 32-bit words of room; *n_words (may be NULL) receives the
  *         array's length.  out == NULL only queries the length.  A too small
  *         cap_words copies nothing and returns SPMM_ERR_INVALID_ARG.
  */
-enum { SPMM_ARRAY_HDR = 0, SPMM_ARRAY_STREAM = 1, SPMM_ARRAY_WINS = 2, SPMM_ARRAY_ITEMS = 3, SPMM_ARRAY_ROWMAP = 4 };
+enum { SPMM_ARRAY_HDR = 0, SPMM_ARRAY_STREAM = 1, SPMM_ARRAY_WINS = 2, SPMM_ARRAY_ITEMS = 3, SPMM_ARRAY_ROWMAP = 4,
+       SPMM_ARRAY_CROSS = 5 };
 spmm_status_t spmm_plan_get_array(const spmm_plan_t *plan, int32_t which,
                                   uint32_t *out, int64_t cap_words, int64_t *n_words);
 

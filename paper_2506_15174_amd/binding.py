@@ -19,7 +19,7 @@ SPMM_ERR_ALLOC = 3
 SPMM_ERR_HIP = 4
 SPMM_ERR_UNSUPPORTED = 5
 
-ARRAY_HDR, ARRAY_STREAM, ARRAY_WINS, ARRAY_ITEMS, ARRAY_ROWMAP = 0, 1, 2, 3, 4
+ARRAY_HDR, ARRAY_STREAM, ARRAY_WINS, ARRAY_ITEMS, ARRAY_ROWMAP, ARRAY_CROSS = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ("spmm_plan_create", "spmm_plan_create_ex", "spmm_execute", "spmm_execute_static",
            "spmm_plan_destroy", "spmm_plan_describe", "spmm_plan_get_groups",

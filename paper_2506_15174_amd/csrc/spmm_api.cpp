@@ -353,6 +353,7 @@ spmm_status_t spmm_plan_get_array(const spmm_plan_t *plan, int32_t which, uint32
     case SPMM_ARRAY_STREAM: v = &h.stream; break;
     case SPMM_ARRAY_WINS: v = &h.wins; break;
     case SPMM_ARRAY_ITEMS: v = &h.items; break;
+    case SPMM_ARRAY_CROSS: v = &h.cross; break;
     default: return SPMM_ERR_INVALID_ARG;
     }
     if (n_words) *n_words = (int64_t)v->size();

@@ -283,7 +283,7 @@ def test_sorting_can_be_forced_and_forbidden():
     _, plan = _plan_from_row_lengths(lens, 400, sort_rows=-1, ufi=2)
     assert plan.describe()["sorted_rows"] == 0 and len(plan.get_array(spmm.ARRAY_ROWMAP)) == 0
     with pytest.raises(spmm.SpmmError):
-        plan.get_array(5)
+        plan.get_array(6)
 
 
 def test_empty_matrix_schedule():
@@ -563,6 +563,19 @@ def test_heavy_panels_are_cut_across_blocks(ufi):
             # pieces of one budget or less: 8 budgets = 512 entries per block at most
             assert np.all(heavy[:, 3] - heavy[:, 2] <= 64)
         assert info["scratch_bytes"] == 0      # host-only plans own no device memory
+        # the table the adding launch reads: one entry per cut panel, in the order of its workgroups
+        table = plan.get_array(spmm.ARRAY_CROSS).reshape(-1, 12)
+        assert len(table) == info["n_cross"]
+        firsts = [blk for blk in items.reshape(-1, 8, 16) if int(blk[0, 5]) & 8 and int(blk[0, 15]) == 0]
+        assert len(firsts) == len(table)
+        for entry, blk in zip(table, firsts):
+            live = blk[(blk[:, 5] & 2) == 0]
+            rows_of_panel = int(live[0, 1])
+            assert (int(entry[0]), int(entry[1]), int(entry[2]), int(entry[3])) == \
+                (int(blk[0, 14]), int(blk[0, 13]), rows_of_panel, 0)
+            want_rows = [int(rowmap[int(live[0, 0]) + r]) if rowmap is not None else int(live[0, 0]) + r
+                         for r in range(rows_of_panel)]
+            assert entry[4:4 + rows_of_panel].tolist() == want_rows and not entry[4 + rows_of_panel:].any()
         C = interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap)
         assert np.array_equal(C.astype(np.float64), dense)
 
