@@ -553,6 +553,8 @@ def kernel_report(torch, csr, plan, info, B, C, N, workload_key, samples=20, pla
     # The ceiling of the plan's own index stream: the same plan as a measuring plan, whose
     # launches request and await every B row as the product does and skip the multiply-adds.
     try:
+        if plan_kw is False:
+            raise RuntimeError("not measured: the plan forces a pipeline depth")
         import paper_2506_15174_amd as spmm
         kw = dict(plan_kw if plan_kw is not None else {"n_hint": N})
         probe = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, probe=True, **kw)
@@ -710,7 +712,7 @@ def run_single(args):
     # one plan per column count: the schedule constants are chosen per bCols, as the
     # paper's tuner does (Section 3.5)
     plans = {N: spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, n_hint=N, ufi=args.ufi,
-                                 depth=args.depth) for N in cols}
+                                 depth=args.depth, ufk=args.ufk) for N in cols}
     plan_s = (time.perf_counter() - t0) / len(cols)
     infos = {N: plans[N].describe() for N in cols}
 
@@ -743,7 +745,7 @@ def run_single(args):
     # of one width share a launch)
     Nd = max(cols)
     roofline = kernel_report(torch, csr, plans[Nd], infos[Nd], Bs[Nd], Cs[Nd], Nd, args.workload,
-                             plan_kw=dict(n_hint=Nd, ufi=args.ufi))
+                             plan_kw=dict(n_hint=Nd, ufi=args.ufi, ufk=args.ufk) if args.depth == 0 else False)
 
     per_cols = {}
     for N in cols:
@@ -794,6 +796,8 @@ def main():
     ap.add_argument("--bcols", type=int, default=128, help="--workload matrix: columns of B")
     ap.add_argument("--seed", type=int, default=11, help="--workload matrix: generator seed")
     ap.add_argument("--ufi", type=int, default=0, help="single workloads: force the rows per panel (1, 2, 4, 8)")
+    ap.add_argument("--ufk", type=int, default=0,
+                    help="single workloads: force the enumerated columns per chunk (8, 16, 32, 64)")
     ap.add_argument("--depth", type=int, default=0,
                     help="single workloads: chunks of B rows in flight per wave (1, 2, 3, 4, 8; 0 = tuned)")
     ap.add_argument("--points-file", default="", help="headline: also write the per-point figures to this JSON file")
