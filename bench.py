@@ -597,7 +597,7 @@ def cpu_baseline(csr, cols, gen, skip=False):
 
 
 PLAN_KEYS = ("ufi", "ufk", "group_nnz", "group_panels", "n_groups", "n_blocks", "n_split", "n_enum", "n_chunks",
-             "device_bytes", "sorted_rows")
+             "device_bytes", "sorted_rows", "n_cross", "scratch_bytes")
 
 
 def run_headline(args):
