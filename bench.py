@@ -188,22 +188,23 @@ def tiles_of_64(N, K):
     return N > 64 and K * 512 > 4 << 20 and K * 256 <= 4 << 20
 
 
-def kernel_shape(N, ufi, K=0, ufk=8):
+def kernel_shape(N, ufi, K=0, ufk=8, k_slices=1):
     """Template arguments of the instance spmm_execute launches for a tile of N columns
     (N a multiple of 4, at most 128) of a plan with panels of `ufi` rows and chunks of
     `ufk` columns: slices per wave, floats per lane, pipeline depth (the tables of
     spmm_launch_chunks).  When 128 columns of B exceed one L2 and 64 fit
-    (8192 < K <= 16384) the product runs as two tiles of 64 columns.  Plans made for
-    narrow B (ufk 16 / 32 / 64) run on 8 / 16 / 32 or 64 slices."""
+    (8192 < K <= 16384) the product runs as two tiles of 64 columns, unless the plan is cut
+    into column ranges (k_slices > 1), which runs full tiles.  Plans made for narrow B (ufk
+    16 / 32 / 64) run on 8 / 16 / 32 or 64 slices."""
     if ufk != 8:
         S = {16: 8, 32: 16}.get(ufk, 64 if N <= 4 else 32)
         depth = {8: 4, 4: 3, 2: 4, 1: 4}[ufi]
         return "S=%d,VW=4,D=%d,UFK=%d" % (S, depth, ufk)
     depth = {8: (2, 3, 4), 4: (2, 3, 4), 2: (2, 2, 6), 1: (2, 2, 8)}[ufi]
-    if tiles_of_64(N, K):
+    if k_slices == 1 and tiles_of_64(N, K):
         return "S=4,VW=4,D=%d, tiles of 64 columns" % depth[1]
     if N > 64:
-        return "S=2,VW=4,D=%d" % depth[0]
+        return "S=2,VW=4,D=%d%s" % (depth[0], ", %d column ranges" % k_slices if k_slices > 1 else "")
     if N > 32:
         return "S=4,VW=4,D=%d" % depth[1]
     return "S=8,VW=4,D=%d" % depth[2]
@@ -532,19 +533,19 @@ def kernel_report(torch, csr, plan, info, B, C, N, workload_key, samples=20, pla
     achieved = bmin / (avg_ms * 1e-3) / 1e9
     kernel_tflops = 2.0 * nnz * N / (avg_ms * 1e-3) / 1e12
     traffic, prov = measured_traffic(workload_key, N)
-    shape = kernel_shape(N, info["ufi"], csr.K, info["ufk"])
+    shape = kernel_shape(N, info["ufi"], csr.K, info["ufk"], info["k_slices"])
     roofline = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic, "traffic_source": prov,
                 "kernel": "spmm_chunks_kernel<UFI=%d,%s> (bCols %d)" % (info["ufi"], shape, N),
                 "cache_state": "hot",
                 "avg_launch_us": round(avg_ms * 1e3, 3), "median_launch_us": round(med_ms * 1e3, 3),
-                "launches_per_execute": 1, "algorithmic_bytes": bmin, "kernel_tflops": round(kernel_tflops, 3),
+                "launches_per_execute": 1 + (info["n_cross"] > 0) + (info["k_slices"] > 1), "algorithmic_bytes": bmin, "kernel_tflops": round(kernel_tflops, 3),
                 "frac_of_fp32_valu_peak": round(kernel_tflops / FP32_VALU_PEAK_TFLOPS, 5)}
     # On-chip gather: each chunk of ufk enumerated columns costs ufk / S wave-wide loads of B
     # rows (S rows of B per load); the ceiling is the rate the gather microbenchmark
     # reaches on distinct rows of an L2-resident B.
     S = int(shape.split(",")[0][2:])
-    tiles = 2 if (info["ufk"] == 8 and tiles_of_64(N, csr.K)) else 1
+    tiles = 2 if (info["ufk"] == 8 and info["k_slices"] == 1 and tiles_of_64(N, csr.K)) else 1
     wave_loads = info["n_chunks"] * info["ufk"] // S * tiles
     roofline["gather"] = {"wave_loads_per_launch": wave_loads,
                           "g_wave_loads_per_s": round(wave_loads / (avg_ms * 1e-3) / 1e9, 2),
@@ -597,7 +598,7 @@ def cpu_baseline(csr, cols, gen, skip=False):
 
 
 PLAN_KEYS = ("ufi", "ufk", "group_nnz", "group_panels", "n_groups", "n_blocks", "n_split", "n_enum", "n_chunks",
-             "device_bytes", "sorted_rows", "n_cross", "scratch_bytes")
+             "device_bytes", "sorted_rows", "n_cross", "scratch_bytes", "k_slices")
 
 
 def run_headline(args):
@@ -712,7 +713,7 @@ def run_single(args):
     # one plan per column count: the schedule constants are chosen per bCols, as the
     # paper's tuner does (Section 3.5)
     plans = {N: spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, n_hint=N, ufi=args.ufi,
-                                 depth=args.depth, ufk=args.ufk) for N in cols}
+                                 depth=args.depth, ufk=args.ufk, kslices=args.kslices) for N in cols}
     plan_s = (time.perf_counter() - t0) / len(cols)
     infos = {N: plans[N].describe() for N in cols}
 
@@ -745,7 +746,7 @@ def run_single(args):
     # of one width share a launch)
     Nd = max(cols)
     roofline = kernel_report(torch, csr, plans[Nd], infos[Nd], Bs[Nd], Cs[Nd], Nd, args.workload,
-                             plan_kw=dict(n_hint=Nd, ufi=args.ufi, ufk=args.ufk) if args.depth == 0 else False)
+                             plan_kw=dict(n_hint=Nd, ufi=args.ufi, ufk=args.ufk, kslices=args.kslices) if args.depth == 0 else False)
 
     per_cols = {}
     for N in cols:
@@ -796,6 +797,8 @@ def main():
     ap.add_argument("--bcols", type=int, default=128, help="--workload matrix: columns of B")
     ap.add_argument("--seed", type=int, default=11, help="--workload matrix: generator seed")
     ap.add_argument("--ufi", type=int, default=0, help="single workloads: force the rows per panel (1, 2, 4, 8)")
+    ap.add_argument("--kslices", type=int, default=0,
+                    help="single workloads: cut the plan into so many column ranges (1 = never, 0 = the rule)")
     ap.add_argument("--ufk", type=int, default=0,
                     help="single workloads: force the enumerated columns per chunk (8, 16, 32, 64)")
     ap.add_argument("--depth", type=int, default=0,

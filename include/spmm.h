@@ -56,7 +56,15 @@ typedef struct {
                               (SPMM_ARRAY_ROWMAP gives the order); 0: the plan's rows are the matrix's */
     int64_t n_cross;       /* panels cut into more pieces than one workgroup has waves: their
                               workgroups' sums meet in scratch memory of the plan */
-    int64_t scratch_bytes; /* that scratch memory (part of device_bytes); 0 when n_cross is 0 */
+    int64_t scratch_bytes; /* scratch memory of the plan that executes write (part of device_bytes): the
+                              sums of panels cut across workgroups and of plans cut along K; 0 when
+                              n_cross is 0 and k_slices is 1 */
+    int64_t k_slices;      /* 1, or the number of column ranges of A (2, 4 or 8) the plan is cut into:
+                              the plan then has k_slices * slice_rows rows, row s * slice_rows + i
+                              holding the entries of row i whose columns lie in range s */
+    int64_t slice_rows;    /* rows per range of such a plan: M rounded up to a multiple of 8 (M when
+                              k_slices is 1) */
+    int64_t slice_cols;    /* columns per range: ceil(K / k_slices) */
 } spmm_plan_info_t;
 
 /* Optional inspector settings; zero in a field means "let the inspector choose". */
@@ -100,6 +108,19 @@ typedef struct {
                               ceiling of this plan's own index stream.  Not combinable with
                               force_wide, depth or chunks wider than 16 columns (SPMM_ERR_INVALID_ARG);
                               a B that needs 64-bit addressing is refused (SPMM_ERR_UNSUPPORTED). */
+    int32_t kslices;       /* cut the plan along K: 2, 4 or 8 column ranges; 1 = never; 0 = choose.
+                              Every workgroup then works on one range and workgroup b of the launch
+                              on range b mod kslices, so that each of the GPU's eight L2 caches (one
+                              per XCD, workgroups are dealt to the XCDs in turn) holds the rows of B of
+                              one range only; the ranges' sums of C meet in scratch memory of the plan
+                              (kslices * slice_rows * 128 floats) and a last, small launch adds them
+                              in range order.  Chosen (0) when a column tile of B is larger than one
+                              L2 (more than 8192 columns of A at more than 64 columns of B or an
+                              unknown number, more than 16384 at 33 to 64), A holds 2^20 entries or
+                              more and its rows at least 32 entries per range on average, and when
+                              the tile is exactly one L2 and the rows hold 1024 entries or more; never for
+                              plans with chunks wider than 8 (SPMM_ERR_INVALID_ARG if both are forced).
+                              At most one execute of such a plan may be in flight at a time. */
 } spmm_options_t;
 
 /*
@@ -159,7 +180,9 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K,
  * execution (pieces of a split panel meet in on-chip memory, not in the plan),
  * so any number of executes of one plan may be in flight on any streams -- unless the
  * plan holds panels cut across workgroups (info.n_cross > 0): their sums meet in scratch
- * memory of the plan, so at most one execute of such a plan may be in flight at a time.
+ * memory of the plan, so at most one execute of such a plan may be in flight at a time;
+ * the same holds for a plan cut along K (info.k_slices > 1), whose ranges' sums meet in
+ * scratch memory of the plan and are added by a last launch, 128 columns at a time.
  * Results are bit-identical from run to run.  B and C must be 4-byte aligned.
  * Every N runs on the kernels that handle four columns per lane (the last lane of
  * a row stores only the columns that exist; rows that are not 16-byte aligned cost
@@ -181,7 +204,8 @@ spmm_status_t spmm_execute(const spmm_plan_t *plan, const float *B, int32_t N,
  *
  * One column tile of a launch needs 512 * ufi bytes per workgroup of a cut panel; the
  * call packs as many column tiles into a launch as the array holds and returns
- * SPMM_ERR_UNSUPPORTED, enqueuing nothing, when a single tile does not fit.
+ * SPMM_ERR_UNSUPPORTED, enqueuing nothing, when a single tile does not fit, and for
+ * every plan cut along K (info.k_slices > 1: its sums need more than the array holds).
  * All plans and all callers on one device share the array, which keeps the last call's
  * content (every launch overwrites what it reads, nothing needs clearing): calls that
  * overlap in time on one device race, also on different streams and for different plans.
@@ -206,7 +230,9 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
  * Row groups in launch order, five int32 each:
  *   row_begin, row_end   rows of the plan the group covers: rows of A (and of C),
  *                        or, when info.sorted_rows is set, positions in the
- *                        length-sorted row order (SPMM_ARRAY_ROWMAP)
+ *                        length-sorted row order (SPMM_ARRAY_ROWMAP); in a plan cut
+ *                        along K, row s * info.slice_rows + i is range s of row
+ *                        (or position) i, and rows M .. slice_rows - 1 of a range are empty
  *   nnz_begin, nnz_end   its range in the schedule-ordered value sequence; for a
  *                        group of whole panels this equals the range
  *                        ptr[row_begin] .. ptr[row_end] of the row pointer of the
@@ -214,7 +240,9 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
  *   flags                bit 0: the group is one piece of a split panel; bit 3: of a panel
  *                        cut into more pieces than a workgroup has waves (info.n_cross)
  * Order: pieces of split panels first (heaviest panel first, pieces in order),
- * then groups of whole panels (heaviest first); ties keep row order.
+ * then groups of whole panels (heaviest first); ties keep row order.  In a plan cut
+ * along K both parts list range after range (heaviest first inside a range), and the
+ * workgroups (8 groups each, never of two ranges) are then dealt to the ranges in turn.
  *   out  HOST int32[5 * cap];  cap must be >= info.n_groups.
  */
 spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_t cap);
@@ -248,10 +276,12 @@ spmm_status_t spmm_plan_get_groups(const spmm_plan_t *plan, int32_t *out, int64_
  *                      across workgroups the number of its workgroups, the scratch slot
  *                      of its first one and this workgroup's place among them
  *                      (rows are rows of the plan, except the row of C, which is
- *                      always a row of the matrix)
+ *                      always a row of the matrix, plus s * slice_rows in a plan cut along K)
  *   SPMM_ARRAY_ROWMAP  M words when info.sorted_rows is set, else none: the row of
  *                      A and C that each row of the plan stands for (rows by
- *                      decreasing length, equal lengths in ascending row order)
+ *                      decreasing length, equal lengths in ascending row order); in a
+ *                      plan cut along K k_slices * slice_rows words: for plan row
+ *                      s * slice_rows + i the value s * slice_rows + (row of A and C)
  *   SPMM_ARRAY_CROSS   12 words per panel cut across workgroups (info.n_cross entries, in the
  *                      order their workgroups are launched): first scratch slot, workgroups,
  *                      rows of the panel, one unused word, then the row of C of each of the

@@ -35,7 +35,8 @@ class PlanInfo(ctypes.Structure):
                 ("n_enum", ctypes.c_int64), ("n_chunks", ctypes.c_int64),
                 ("stream_words", ctypes.c_int64), ("device_bytes", ctypes.c_int64),
                 ("sorted_rows", ctypes.c_int64), ("n_cross", ctypes.c_int64),
-                ("scratch_bytes", ctypes.c_int64)]
+                ("scratch_bytes", ctypes.c_int64), ("k_slices", ctypes.c_int64),
+                ("slice_rows", ctypes.c_int64), ("slice_cols", ctypes.c_int64)]
 
     def as_dict(self):
         return {name: int(getattr(self, name)) for name, _ in self._fields_}
@@ -46,7 +47,8 @@ class Options(ctypes.Structure):
                 ("host_only", ctypes.c_int32), ("ufi", ctypes.c_int32),
                 ("n_hint", ctypes.c_int32), ("sort_rows", ctypes.c_int32),
                 ("force_wide", ctypes.c_int32), ("threads", ctypes.c_int32), ("depth", ctypes.c_int32),
-                ("cross", ctypes.c_int32), ("ufk", ctypes.c_int32), ("probe", ctypes.c_int32)]
+                ("cross", ctypes.c_int32), ("ufk", ctypes.c_int32), ("probe", ctypes.c_int32),
+                ("kslices", ctypes.c_int32)]
 
 
 class SpmmError(RuntimeError):
@@ -191,7 +193,8 @@ class Plan:
 
 
 def plan_create(M, K, row_ptr, col_idx, vals, group_nnz=0, group_panels=0, host_only=False, ufi=0,
-                n_hint=0, sort_rows=0, force_wide=False, threads=0, depth=0, cross=0, ufk=0, probe=False):
+                n_hint=0, sort_rows=0, force_wide=False, threads=0, depth=0, cross=0, ufk=0, probe=False,
+                kslices=0):
     """spmm_plan_create / spmm_plan_create_ex on numpy host arrays."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
@@ -199,9 +202,10 @@ def plan_create(M, K, row_ptr, col_idx, vals, group_nnz=0, group_panels=0, host_
     handle = ctypes.c_void_p()
     lib = load()
     if group_nnz or group_panels or host_only or ufi or n_hint or sort_rows or force_wide or threads or depth \
-            or cross or ufk or probe:
+            or cross or ufk or probe or kslices:
         opts = Options(int(group_nnz), int(group_panels), 1 if host_only else 0, int(ufi), int(n_hint),
-                       int(sort_rows), 1 if force_wide else 0, int(threads), int(depth), int(cross), int(ufk), 1 if probe else 0)
+                       int(sort_rows), 1 if force_wide else 0, int(threads), int(depth), int(cross), int(ufk), 1 if probe else 0,
+                       int(kslices))
         st = lib.spmm_plan_create_ex(ctypes.byref(handle), int(M), int(K), _ptr(row_ptr),
                                      _ptr(col_idx), _ptr(vals), ctypes.byref(opts))
     else:

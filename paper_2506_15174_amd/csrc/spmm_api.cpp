@@ -24,6 +24,9 @@ struct spmm_plan {
     // table of those panels.
     float *d_cross_sums = nullptr;
     uint32_t *d_cross_table = nullptr;
+    // Plans cut along K: the slices' sums of one batch of up to KSLICE_COLS columns
+    // (k_slices x slice_rows rows), written by every execute.
+    float *d_slice_sums = nullptr;
     int64_t scratch_bytes = 0;
     int64_t device_bytes = 0;
     int64_t stream_words = 0;  // length of host.stream at creation (a device plan drops its host mirror)
@@ -33,6 +36,9 @@ struct spmm_plan {
 };
 
 namespace {
+
+// Columns a plan cut along K computes per pair of launches (the width of its slices' buffer).
+constexpr int32_t KSLICE_COLS = 128;
 
 spmm_status_t hip_fail()
 {
@@ -69,8 +75,9 @@ void release_device(spmm_plan *p)
     if (p->d_rowmap) (void)hipFree(p->d_rowmap);
     if (p->d_cross_sums) (void)hipFree(p->d_cross_sums);
     if (p->d_cross_table) (void)hipFree(p->d_cross_table);
+    if (p->d_slice_sums) (void)hipFree(p->d_slice_sums);
     p->d_stream = p->d_wins = p->d_items = p->d_rowmap = p->d_cross_table = nullptr;
-    p->d_cross_sums = nullptr;
+    p->d_cross_sums = p->d_slice_sums = nullptr;
     (void)hipGetLastError();
 }
 
@@ -102,10 +109,14 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
         io.sort_rows = opts->sort_rows;
         io.threads = opts->threads;
         io.cross = opts->cross;
+        if (opts->kslices != 0 && opts->kslices != 1 && opts->kslices != 2 && opts->kslices != 4 && opts->kslices != 8)
+            return SPMM_ERR_INVALID_ARG;
+        io.kslices = opts->kslices;
         if (opts->ufk != 0 && !valid_ufk(opts->ufk)) return SPMM_ERR_INVALID_ARG;
         io.ufk = opts->ufk;
         force_wide = opts->force_wide != 0;
         if (force_wide) io.ufk = UFK;  // the 64-bit addressing kernels read chunks of 8 columns
+        if (io.kslices > 1 && io.ufk != 0 && io.ufk != UFK) return SPMM_ERR_INVALID_ARG;  // only plans with chunks of 8 are cut
         depth = opts->depth;
         probe = opts->probe != 0;
         if (probe && (force_wide || depth != 0 || (io.ufk != 0 && io.ufk > 16))) return SPMM_ERR_INVALID_ARG;
@@ -142,6 +153,11 @@ spmm_status_t spmm_plan_create_ex(spmm_plan_t **plan, int64_t M, int64_t K, cons
             float *unused = nullptr;
             size_t unused_bytes = 0;
             if (spmm_static_scratch(&unused, &unused_bytes) != 0) (void)hipGetLastError();
+        }
+        if (st == SPMM_OK && h.k_slices > 1) {
+            int64_t before = p->device_bytes;
+            st = upload(&p->d_slice_sums, nullptr, (size_t)h.plan_rows * KSLICE_COLS * sizeof(float), p->device_bytes);
+            p->scratch_bytes += p->device_bytes - before;
         }
         if (st != SPMM_OK) {
             release_device(p);
@@ -203,6 +219,11 @@ spmm_status_t execute_with(const spmm_plan_t *plan, const float *B, int32_t N, f
     a.rowmap = plan->d_rowmap;
     a.n_blocks = (int32_t)h.n_blocks;
     a.ldn = N;
+    a.ldc = N;
+    const bool sliced = h.k_slices > 1;
+    a.k_slices = h.k_slices;
+    a.slice_rows = h.slice_rows;
+    a.M = h.M;
     a.col_mask = h.K <= ((int64_t)1 << spmm_fmt::COL_PATTERN_SHIFT) ? spmm_fmt::COL_INDEX_MASK : 0xFFFFFFFFu;
     a.cross_sums = cross_sums;
     a.cross_table = plan->d_cross_table;
@@ -211,11 +232,12 @@ spmm_status_t execute_with(const spmm_plan_t *plan, const float *B, int32_t N, f
     a.probe = plan->probe;
     if (plan->probe && (wide || h.ufk > 16)) return SPMM_ERR_UNSUPPORTED;
     // the scratch of panels cut across workgroups holds so many column tiles of one launch
-    const int32_t max_tiles = h.n_cross_slots > 0 ? cross_tiles : 65535;
+    const int32_t max_tiles = sliced ? 1 : h.n_cross_slots > 0 ? cross_tiles : 65535;
     // A 128-column tile of B that exceeds one L2 (4 MiB) while a 64-column tile fits: two
     // narrower tiles read the plan twice but keep their rows of B L2-resident (measured on a
     // 16384-column matrix of 13 M nonzeros: 275 against 295 us).
-    const bool narrow_tiles = (int64_t)h.K * 512 > ((int64_t)4 << 20) && (int64_t)h.K * 256 <= ((int64_t)4 << 20);
+    // (A plan cut along K binds every slice of B to the L2s of its own XCDs instead and runs full tiles.)
+    const bool narrow_tiles = !sliced && (int64_t)h.K * 512 > ((int64_t)4 << 20) && (int64_t)h.K * 256 <= ((int64_t)4 << 20);
     // Such a tile fills the L2: two workgroups per CU instead of three keep the rows of B that
     // concurrently running waves sweep inside it (same matrix: 262 against 275 us).
     a.lds_pad = narrow_tiles ? 24u << 10 : 0u;
@@ -237,7 +259,8 @@ spmm_status_t execute_with(const spmm_plan_t *plan, const float *B, int32_t N, f
     };
     int32_t j0 = 0;
     while (j0 < N) {
-        const int32_t left = N - j0;
+        // a plan cut along K takes the columns in batches its slices' buffer holds
+        const int32_t left = sliced && N - j0 > KSLICE_COLS ? KSLICE_COLS : N - j0;
         int slices = 0;
         const int32_t tile = tile_for(left, slices);
         int32_t n_tiles = left / tile, cols = n_tiles * tile;
@@ -252,6 +275,14 @@ spmm_status_t execute_with(const spmm_plan_t *plan, const float *B, int32_t N, f
         }
         a.B = B ? B + j0 : nullptr;
         a.C = C + j0;
+        if (sliced) {
+            // the launch writes the slices' sums, rows of (cols rounded up to 4) floats; its
+            // last step adds them into C
+            a.C = plan->d_slice_sums;
+            a.ldc = (cols + 3) / 4 * 4;
+            a.C_out = C + j0;
+            a.ldc_out = N;
+        }
         a.width = cols;
         a.tile_cols = tile;
         a.n_tiles = n_tiles;
@@ -275,6 +306,7 @@ spmm_status_t spmm_execute_static(const spmm_plan_t *plan, const float *B, int32
 {
     if (!plan) return SPMM_ERR_INVALID_ARG;
     const HostPlan &h = plan->host;
+    if (h.k_slices > 1 && plan->on_device) return SPMM_ERR_UNSUPPORTED;  // the slices' buffer is beyond the static array
     if (h.n_cross_slots == 0 || !plan->on_device) return execute_with(plan, B, N, C, stream, nullptr, 0);
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return hip_fail();
@@ -319,6 +351,9 @@ spmm_status_t spmm_plan_describe(const spmm_plan_t *plan, spmm_plan_info_t *out)
     out->sorted_rows = h.rowmap.empty() ? 0 : 1;
     out->n_cross = h.n_cross;
     out->scratch_bytes = plan->scratch_bytes;
+    out->k_slices = h.k_slices;
+    out->slice_rows = h.slice_rows;
+    out->slice_cols = h.slice_cols;
     return SPMM_OK;
 }
 
@@ -340,7 +375,7 @@ spmm_status_t spmm_plan_get_array(const spmm_plan_t *plan, int32_t which, uint32
     const HostPlan &h = plan->host;
     if (which == SPMM_ARRAY_ROWMAP) {
         // M entries for a plan with sorted rows (the vector carries padding for the kernel), else none
-        const int64_t n = h.rowmap.empty() ? 0 : h.M;
+        const int64_t n = h.rowmap.empty() ? 0 : h.plan_rows;
         if (n_words) *n_words = n;
         if (!out) return SPMM_OK;
         if (cap_words < n) return SPMM_ERR_INVALID_ARG;

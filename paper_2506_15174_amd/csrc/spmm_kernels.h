@@ -14,8 +14,9 @@ struct spmm_launch_args {
     int32_t n_blocks;       // workgroups to launch
     const float *B;         // DEVICE first column of the launch's first column tile
     uint32_t b_bytes;       // bytes of B reachable from that pointer (narrow addressing only)
-    float *C;               // DEVICE first column of the launch's first column tile
-    int32_t ldn;            // leading dimension of B and C (= N)
+    float *C;               // DEVICE first column of the launch's first column tile (of the slices' buffer when k_slices > 1)
+    int32_t ldn;            // leading dimension of B (= N)
+    int32_t ldc;            // leading dimension of what C points to
     int32_t width;          // columns of this launch: n_tiles tiles of tile_cols, the last maybe narrower
     int32_t tile_cols;      // columns per tile (per blockIdx.y)
     int32_t n_tiles;        // column tiles of this launch (grid y)
@@ -27,9 +28,16 @@ struct spmm_launch_args {
     const uint32_t *cross_table = nullptr;// DEVICE one entry per such panel: slots and rows of C
     uint32_t n_cross_slots = 0;
     int32_t n_cross = 0;
+    // Plans cut along K (k_slices > 1; else unused): C above is the slices' buffer (k_slices x
+    // slice_rows rows of ldc floats); a last launch adds the slices of the first M rows into C_out.
+    int32_t k_slices = 1;
+    int64_t slice_rows = 0, M = 0;
+    float *C_out = nullptr;  // DEVICE first column of this launch in the caller's C
+    int32_t ldc_out = 0;     // its leading dimension (= N)
 };
 
-// Enqueues one launch of n_tiles column tiles.  ufi = rows per panel of the plan (1, 2, 4, 8).
+// Enqueues one launch of n_tiles column tiles (plus the small launches that add the sums of
+// panels cut across workgroups and of plans cut along K).  ufi = rows per panel of the plan (1, 2, 4, 8).
 // slices = 2 / 4 / 8: four columns per lane (16-byte loads and stores at 4-byte alignment;
 // the last lane of a tile may own fewer than four columns), tile of up to 128 / 64 / 32
 // columns; slices = 1: one column per lane, tile of up to 64 columns.  wide = 64-bit

@@ -314,7 +314,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_WG, (waves_per_simd(S, UFI, UFKT, WI
 spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                    const uint32_t *__restrict__ wins_g, const uint32_t *__restrict__ items_g,
                    const uint32_t *__restrict__ rowmap_g, const float *__restrict__ B_all, uint32_t b_bytes_all,
-                   float *__restrict__ C_all, int32_t ldn, int32_t width_all, int32_t tile_cols, uint32_t col_mask,
+                   float *__restrict__ C_all, int32_t ldn, int32_t ldc, int32_t width_all, int32_t tile_cols, uint32_t col_mask,
                    float *__restrict__ cross_sums, uint32_t n_cross_slots)
 {
     // blockIdx.y: the column tile this workgroup computes (tiles of tile_cols columns of
@@ -497,7 +497,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                                 } else if ((uint32_t)r < rows_here && owner && col < width) {
                                     // rows sorted by length: the plan's row `row + r` is another row of C
                                     const size_t c_row = map ? (size_t)map[r] : (size_t)row + (size_t)r;
-                                    float *dst = C + c_row * (size_t)ldn + col;
+                                    float *dst = C + c_row * (size_t)ldc + col;
                                     if constexpr (S == 2) {
                                         if (col + 1 < width) *reinterpret_cast<f32x2_unaligned_t *>(dst) = f32x2_unaligned_t{lo, hi};
                                         else *dst = lo;
@@ -523,12 +523,12 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
 #pragma unroll
                                     for (int r = 0; r < UFI; ++r)
                                         if ((uint32_t)r < rows_here)
-                                            store_cols(C + (size_t)map[r] * (size_t)ldn + sl_now * VW, acc[r], valid_now);
+                                            store_cols(C + (size_t)map[r] * (size_t)ldc + sl_now * VW, acc[r], valid_now);
                                 } else {
-                                    float *c_panel = C + (size_t)row * (size_t)ldn + sl_now * VW;
+                                    float *c_panel = C + (size_t)row * (size_t)ldc + sl_now * VW;
 #pragma unroll
                                     for (int r = 0; r < UFI; ++r)
-                                        if ((uint32_t)r < rows_here) store_cols(c_panel + (size_t)r * ldn, acc[r], valid_now);
+                                        if ((uint32_t)r < rows_here) store_cols(c_panel + (size_t)r * ldc, acc[r], valid_now);
                                 }
                             }
                         }
@@ -564,7 +564,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
                 add_to(sum, *reinterpret_cast<const vec_t *>(&lds[first + p][(r * L + sl) * VW]));
         }
         if (!(flags & FLAG_CROSS)) {
-            if (adds) store_cols(C + (size_t)it[IT_RED_ROW] * (size_t)ldn + sl * VW, sum, valid);
+            if (adds) store_cols(C + (size_t)it[IT_RED_ROW] * (size_t)ldc + sl * VW, sum, valid);
         } else if (adds) {
             // The panel is cut across several blocks: each parks the sums of its pieces in
             // its scratch slot; spmm_cross_combine_kernel, enqueued behind this launch, adds the
@@ -584,7 +584,7 @@ spmm_chunks_kernel(const uint32_t *__restrict__ stream_g,
 // no counters, nothing to clear between launches.
 __global__ __launch_bounds__(256) void
 spmm_cross_combine_kernel(const uint32_t *__restrict__ table, const float *__restrict__ sums, uint32_t n_cross_slots,
-                          int32_t ufi, float *__restrict__ C_all, int32_t ldn, int32_t width_all, int32_t tile_cols)
+                          int32_t ufi, float *__restrict__ C_all, int32_t ldc, int32_t width_all, int32_t tile_cols)
 {
     const uint32_t *e = table + (size_t)blockIdx.x * CROSS_ENTRY_WORDS;
     const uint32_t slot0 = e[CE_SLOT0], nparts = e[CE_NPARTS], nrows = e[CE_NROWS];
@@ -597,7 +597,26 @@ spmm_cross_combine_kernel(const uint32_t *__restrict__ table, const float *__res
     const float *s = sums + ((size_t)blockIdx.y * n_cross_slots + slot0) * slot_floats + r * (uint32_t)CROSS_ROW_FLOATS + c;
     f32x4_t total = Vec<4>::zero();
     for (uint32_t p = 0; p < nparts; ++p) total += *reinterpret_cast<const f32x4_t *>(s + (size_t)p * slot_floats);
-    store_cols(C_all + (size_t)e[CE_ROW0 + r] * (size_t)ldn + col0 + c, total, width - c);
+    store_cols(C_all + (size_t)e[CE_ROW0 + r] * (size_t)ldc + col0 + c, total, width - c);
+}
+
+// Last step of a plan cut along K: C = sum over the slices, in slice order, of the rows the
+// main launch (and the step above) wrote to the slices' buffer: slice s of row i at row
+// s * slice_rows + i, `ldp` floats per row.  Thread t of block b owns four columns of one row.
+__global__ __launch_bounds__(256) void
+spmm_kslice_combine_kernel(const float *__restrict__ sums, int32_t k_slices, uint32_t slice_rows, int32_t ldp,
+                           float *__restrict__ C, int32_t ldc, uint32_t M, int32_t width)
+{
+    const uint32_t quads = (uint32_t)(width + 3) / 4u;
+    const uint64_t t = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    const uint32_t row = (uint32_t)(t / quads);
+    const int32_t c = (int32_t)(t % quads) * 4;
+    if (row >= M) return;
+    const float *p = sums + (size_t)row * (size_t)ldp + c;
+    f32x4_t total = *reinterpret_cast<const f32x4_t *>(p);
+    for (int32_t s = 1; s < k_slices; ++s)
+        total += *reinterpret_cast<const f32x4_t *>(p + (size_t)s * (size_t)slice_rows * (size_t)ldp);
+    store_cols(C + (size_t)row * (size_t)ldc + c, total, width - c);
 }
 
 template <int U, int S, int VW, int D, bool WIDE, int UFKT = UFK, bool PROBE = false>
@@ -605,7 +624,7 @@ void launch_instance(const spmm_launch_args &a, void *stream)
 {
     hipLaunchKernelGGL((spmm_chunks_kernel<U, S, VW, D, WIDE, UFKT, PROBE>), dim3((unsigned)a.n_blocks, (unsigned)a.n_tiles),
                        dim3(64 * WAVES_PER_WG), a.lds_pad, (hipStream_t)stream, a.stream, a.wins, a.items, a.rowmap,
-                       a.B, a.b_bytes, a.C, a.ldn, a.width, a.tile_cols, a.col_mask, a.cross_sums, a.n_cross_slots);
+                       a.B, a.b_bytes, a.C, a.ldn, a.ldc, a.width, a.tile_cols, a.col_mask, a.cross_sums, a.n_cross_slots);
 }
 
 // One (height, slices) pair at the pipeline depth asked for.  DMAX is the depth the
@@ -680,8 +699,14 @@ int spmm_launch_chunks(const spmm_launch_args &a, int ufi, int ufk, int slices, 
     }
     if (a.n_cross > 0)
         hipLaunchKernelGGL(spmm_cross_combine_kernel, dim3((unsigned)a.n_cross, (unsigned)a.n_tiles), dim3(256), 0,
-                           (hipStream_t)stream, a.cross_table, a.cross_sums, a.n_cross_slots, (int32_t)ufi, a.C, a.ldn,
+                           (hipStream_t)stream, a.cross_table, a.cross_sums, a.n_cross_slots, (int32_t)ufi, a.C, a.ldc,
                            a.width, a.tile_cols);
+    if (a.k_slices > 1) {
+        const uint64_t threads = (uint64_t)a.M * (uint64_t)((a.width + 3) / 4);
+        hipLaunchKernelGGL(spmm_kslice_combine_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
+                           (hipStream_t)stream, a.C, a.k_slices, (uint32_t)a.slice_rows, a.ldc, a.C_out, a.ldc_out,
+                           (uint32_t)a.M, a.width);
+    }
     return (int)hipGetLastError();
 }
 

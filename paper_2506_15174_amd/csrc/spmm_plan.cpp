@@ -192,6 +192,39 @@ bool cross_allowed(int32_t setting, bool skewed, int64_t nnz, int32_t n_hint)
     return skewed && !narrow && nnz >= ((int64_t)1 << 20);
 }
 
+// Slices along K.  A column tile of B larger than one L2 (4 MiB per XCD) is re-fetched over
+// and over by waves that sweep different parts of it.  The plan is then cut into column
+// ranges whose share of the tile takes at most half an L2, every workgroup works on one
+// range only, and workgroup b takes range b mod k_slices: workgroups are handed to the
+// eight XCDs in turn, so each L2 holds one range of B (for two or four ranges, two or four
+// XCDs share a range).  The ranges' partial sums of C meet in a buffer that a second launch
+// adds up, which costs 8 k_slices M bCols bytes of traffic and a launch: only for matrices
+// of at least 2^20 entries whose rows hold at least 32 entries per range on average
+// (1024 per row where the tile is exactly one L2).
+// Measured on a 16384 x 16384 matrix of 13 M entries with Zipf row lengths, 128 columns:
+// 145 us uncut (two tiles of 64 columns), 106 + 9 us in four ranges bound to XCDs, 153 us in
+// four ranges not bound to them; matrices whose tile of B fits the L2 gain nothing.
+// Plans made for narrow B (chunks wider than 8) are never cut.
+int choose_kslices(int32_t setting, int64_t M, int64_t K, int64_t nnz, int32_t n_hint, int ufk)
+{
+    if (ufk != UFK || M <= 0 || K < 8) return 1;
+    if ((M + MAX_UFI) * 8 > (int64_t)INT32_MAX) return 1;
+    if (setting == 2 || setting == 4 || setting == 8) return setting;
+    if (setting != 0) return 1;
+    const bool medium = n_hint > 32 && n_hint <= 64;
+    const int64_t tile_row_bytes = medium ? 256 : 512;
+    const int64_t l2 = (int64_t)4 << 20;
+    if (K * tile_row_bytes < l2 || nnz < ((int64_t)1 << 20)) return 1;
+    int ns = 2;
+    while (ns < 8 && (K + ns - 1) / ns * tile_row_bytes > l2 / 2) ns *= 2;
+    // a tile that just fills the L2 shares it with the plan's stream: two slices pay from rows of
+    // 1024 entries on (8192 x 8192, 128 columns: 5 % faster at 50 to 80 % sparsity, 2 % at 90 %,
+    // 3 to 6 % slower from 95 % on)
+    const int64_t min_row = K * tile_row_bytes > l2 ? 32 * ns : 1024;
+    if (nnz < min_row * M) return 1;
+    return ns;
+}
+
 // Row lengths so uneven that sorting the rows pays: the rows longer than four
 // times the mean hold at least a quarter of the entries.
 bool skewed_rows(const int32_t *row_ptr, int64_t M, int64_t nnz)
@@ -294,8 +327,9 @@ struct Emitter {
 // Row groups in creation order, from row_ptr alone.  Panels (ufi consecutive
 // rows) are taken in order.  A panel heavier than the budget G is cut into
 // nseg pieces of equal size of its schedule order: want = min(8, ceil(pn / G))
-// rounded up to a power of two (so that the pieces of several panels fill the
-// eight wave slots of a workgroup exactly), size = ceil(pn / want),
+// rounded up to a power of two and raised to the panel height (a workgroup holds
+// 8 / ufi split panels, so that the pieces of its panels fill its eight wave slots
+// exactly), size = ceil(pn / want),
 // nseg = ceil(pn / size); the last piece takes the rest.
 // A panel heavier than both eight budgets and 1 / CROSS_SHARE of all entries (and
 // `cross` permitting) is cut across blocks instead: parts = ceil(pn / that bound), at
@@ -323,6 +357,7 @@ std::vector<Group> make_groups(const int32_t *row_ptr, int64_t M, int ufi, int64
             flush();
             int64_t want = std::min<int64_t>(WAVES_PER_WG, (pn + G - 1) / G);
             while (want & (want - 1)) want += 1;
+            want = std::max<int64_t>(want, ufi);  // a block holds 8 / ufi split panels: fewer pieces would leave its waves idle
             const bool across = cross && pn > part_bound;
             if (across) want = WAVES_PER_WG * std::min<int64_t>(MAX_CROSS_PARTS, (pn + part_bound - 1) / part_bound);
             const int64_t size = (pn + want - 1) / want;
@@ -418,46 +453,100 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         int ufi = opts.ufi;
         const bool forced_ufi = ufi == 1 || ufi == 2 || ufi == 4 || ufi == 8;
         const bool skewed = skewed_rows(row_ptr, M, nnz);
-        const bool cross = cross_allowed(opts.cross, skewed, nnz, opts.n_hint);
+        bool cross = cross_allowed(opts.cross, skewed, nnz, opts.n_hint);
+        out.ufk = valid_ufk(opts.ufk) && K <= ((int64_t)1 << COL_PATTERN_SHIFT) ? opts.ufk : choose_ufk(K, opts.n_hint);
+        // slices along K: the heights below then see the columns of one slice
+        const int NS = choose_kslices(opts.kslices, M, K, nnz, opts.n_hint, out.ufk);
+        const int64_t KS = NS > 1 ? (K + NS - 1) / NS : K;                              // columns per slice
+        const int64_t MS = NS > 1 ? (M + MAX_UFI - 1) / MAX_UFI * MAX_UFI : M;          // plan rows per slice
+        const int64_t MP = NS > 1 ? NS * MS : M;                                        // plan rows
+        out.k_slices = NS;
+        out.slice_rows = MS;
+        out.slice_cols = KS;
+        out.plan_rows = MP;
+        if (NS > 1) {
+            // the longest row of a slice
+            max_row = 0;
+            int64_t in_slice[8];
+            for (int64_t i = 0; i < M; ++i) {
+                std::fill(in_slice, in_slice + NS, (int64_t)0);
+                for (int64_t q = row_ptr[i]; q < row_ptr[i + 1]; ++q) in_slice[(int64_t)col_idx[q] / KS] += 1;
+                max_row = std::max(max_row, *std::max_element(in_slice, in_slice + NS));
+            }
+            // A slice's panels are lighter by the number of slices: where the tallest panel of
+            // its longest rows is no longer the tail of the launch, no panel needs to be cut
+            // across workgroups (the 16384 x 16384 matrix above, four slices, eight rows:
+            // 112 us with every panel in one workgroup, 119 us with the heavy ones cut)
+            if (opts.cross == 0 && cross) {
+                const bool medium = opts.n_hint > 32 && opts.n_hint <= 64;
+                if (choose_ufi_skewed(KS, nnz, max_row, opts.n_hint, false) >= (medium ? 4 : 8)) cross = false;
+            }
+        }
         if (!forced_ufi) {
             // a forced sort asks for the height a sorted matrix would get
             const bool as_sorted = opts.sort_rows > 0 || (opts.sort_rows == 0 && skewed);
-            ufi = as_sorted ? choose_ufi_skewed(K, nnz, max_row, opts.n_hint, cross) : choose_ufi(M, K, nnz, opts.n_hint);
+            ufi = as_sorted ? choose_ufi_skewed(KS, nnz, max_row, opts.n_hint, cross) : choose_ufi(M, KS, nnz, opts.n_hint);
         }
         // single rows share nothing: sorting them would only scatter the rows of C
         const bool sorted = opts.sort_rows > 0 || (opts.sort_rows == 0 && skewed && ufi > 1);
-        std::vector<int32_t> sorted_ptr;
+        // row_order[i]: the matrix row that row i of a slice stands for (sorted plans only)
+        std::vector<uint32_t> row_order;
+        std::vector<int32_t> own_ptr;
         if (sorted) {
-            out.rowmap.resize((size_t)M);
-            std::iota(out.rowmap.begin(), out.rowmap.end(), 0u);
-            std::stable_sort(out.rowmap.begin(), out.rowmap.end(), [&](uint32_t x, uint32_t y) {
+            row_order.resize((size_t)M);
+            std::iota(row_order.begin(), row_order.end(), 0u);
+            std::stable_sort(row_order.begin(), row_order.end(), [&](uint32_t x, uint32_t y) {
                 return row_ptr[x + 1] - row_ptr[x] > row_ptr[y + 1] - row_ptr[y];
             });
-            sorted_ptr.resize((size_t)M + 1);
-            sorted_ptr[0] = 0;
-            for (int64_t i = 0; i < M; ++i) {
-                const uint32_t r = out.rowmap[(size_t)i];
-                sorted_ptr[(size_t)i + 1] = sorted_ptr[(size_t)i] + (row_ptr[r + 1] - row_ptr[r]);
+        }
+        // Row i of the plan is slice i / MS of matrix row mrow(i % MS) (none for the rows that
+        // pad a slice); out_row(i) is the row of the output buffer it is written to: a row of
+        // C, or of the slices' buffer.  plan_ptr is the row pointer of the plan's own rows.
+        auto mrow = [&](int64_t i) -> int64_t {
+            const int64_t w = NS > 1 ? i % MS : i;
+            return w >= M ? -1 : sorted ? (int64_t)row_order[(size_t)w] : w;
+        };
+        auto src = [&](int64_t i) -> int64_t {  // out_row
+            if (NS == 1) return sorted ? (int64_t)row_order[(size_t)i] : i;
+            const int64_t w = i % MS;
+            return i - w + (w < M && sorted ? (int64_t)row_order[(size_t)w] : w);
+        };
+        if (sorted || NS > 1) {
+            own_ptr.assign((size_t)MP + 1, 0);
+            for (int64_t i = 0; i < MS; ++i) {
+                const int64_t m = mrow(i);
+                if (m < 0) continue;
+                if (NS == 1) {
+                    own_ptr[(size_t)i + 1] = row_ptr[m + 1] - row_ptr[m];
+                } else {
+                    for (int64_t q = row_ptr[m]; q < row_ptr[m + 1]; ++q)
+                        own_ptr[(size_t)((int64_t)col_idx[q] / KS * MS + i) + 1] += 1;
+                }
+            }
+            for (int64_t i = 0; i < MP; ++i) own_ptr[(size_t)i + 1] += own_ptr[(size_t)i];
+            if (sorted) {
+                out.rowmap.resize((size_t)MP);
+                for (int64_t i = 0; i < MP; ++i) out.rowmap[(size_t)i] = (uint32_t)src(i);
             }
         }
-        // row i of the plan: entries [row_ptr[src(i)], row_ptr[src(i) + 1]) of the CSR;
-        // plan_ptr is the row pointer of the plan's own row order
-        auto src = [&](int64_t i) -> int64_t { return sorted ? (int64_t)out.rowmap[(size_t)i] : i; };
-        const int32_t *plan_ptr = sorted ? sorted_ptr.data() : row_ptr;
+        const int32_t *plan_ptr = sorted || NS > 1 ? own_ptr.data() : row_ptr;
         // ---- 1. group budget and row groups, from the row pointer alone ----------
         int32_t auto_g = 0, auto_gp = 0;
-        choose_group_budget(M, nnz, ufi, opts.n_hint, auto_g, auto_gp);
+        choose_group_budget(MP, nnz, ufi, opts.n_hint, auto_g, auto_gp);
         // heavy panels cut as finely as needed: half the budget, so that the launch is made of
         // lighter pieces throughout (measured with the heights above: stress matrix 162 -> 154 us,
         // 8192 x 8192 lognormal rows of sigma 1.5 94 -> 81 us at 128 columns, 60 -> 53 us at 64)
         if (cross) auto_g = std::max<int32_t>(32, auto_g / 2 / 32 * 32);
+        // skewed rows in a plan cut along K whose panels all stay inside a workgroup: a quarter, so
+        // that more of the medium panels are cut into eight pieces (the 16384 x 16384 matrix above,
+        // four slices: 106 us against 109 us with half and 117 us with the whole budget)
+        else if (NS > 1 && skewed) auto_g = std::max<int32_t>(32, auto_g / 4 / 32 * 32);
         out.group_nnz = opts.group_nnz > 0 ? std::max(8, opts.group_nnz) : auto_g;
         out.group_panels = opts.group_panels > 0 ? opts.group_panels : auto_gp;
         const int64_t G = out.group_nnz;
         const int64_t GP = out.group_panels;
-        std::vector<Group> groups = make_groups(plan_ptr, M, ufi, G, GP, cross);
+        std::vector<Group> groups = make_groups(plan_ptr, MP, ufi, G, GP, cross);
         out.ufi = ufi;
-        out.ufk = valid_ufk(opts.ufk) && K <= ((int64_t)1 << COL_PATTERN_SHIFT) ? opts.ufk : choose_ufk(K, opts.n_hint);
         const int UFI = ufi;  // panel height of this plan
         const int UFK = out.ufk;  // columns per chunk of this plan (shadows the default)
         const int WINW = win_words(UFK), LOOK = lookahead(UFK);
@@ -489,11 +578,12 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                 const int64_t first_panel = g0.row_begin / UFI;
                 const int64_t last_panel = (g0.row_end + UFI - 1) / UFI;  // exclusive
                 for (int64_t p = first_panel; p < last_panel; ++p) {
-                    const int64_t r0 = p * UFI, r1 = std::min<int64_t>(M, r0 + UFI);
+                    const int64_t r0 = p * UFI, r1 = std::min<int64_t>(MP, r0 + UFI);
                     const int rows = (int)(r1 - r0);
                     // canonical rows: stable order by column (duplicates keep stored order)
                     for (int r = 0; r < rows; ++r) {
-                        const int64_t a = row_ptr[src(r0 + r)], b = row_ptr[src(r0 + r) + 1];
+                        const int64_t m = mrow(r0 + r);
+                        const int64_t a = m < 0 ? 0 : row_ptr[m], b = m < 0 ? 0 : row_ptr[m + 1];
                         const int64_t len = b - a;
                         ccol[r].resize((size_t)len);
                         cval[r].resize((size_t)len);
@@ -513,6 +603,17 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                                 ccol[r][(size_t)q] = col_idx[a + order[(size_t)q]];
                                 cval[r][(size_t)q] = vals[a + order[(size_t)q]];
                             }
+                        }
+                        if (NS > 1) {
+                            // this slice's columns: a contiguous range of the canonical row
+                            const int64_t sl = (r0 + r) / MS;
+                            const auto lo = std::lower_bound(ccol[r].begin(), ccol[r].end(), (int32_t)std::min<int64_t>(sl * KS, INT32_MAX));
+                            const auto hi = std::lower_bound(ccol[r].begin(), ccol[r].end(), (int32_t)std::min<int64_t>((sl + 1) * KS, INT32_MAX));
+                            const size_t i0 = (size_t)(lo - ccol[r].begin()), i1 = (size_t)(hi - ccol[r].begin());
+                            ccol[r].erase(ccol[r].begin() + (ptrdiff_t)i1, ccol[r].end());
+                            ccol[r].erase(ccol[r].begin(), ccol[r].begin() + (ptrdiff_t)i0);
+                            cval[r].erase(cval[r].begin() + (ptrdiff_t)i1, cval[r].end());
+                            cval[r].erase(cval[r].begin(), cval[r].begin() + (ptrdiff_t)i0);
                         }
                     }
                     // merge the rows' column lists.  The t-th occurrence of a column in
@@ -666,6 +767,13 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
             return (groups[(size_t)x].nnz_end - groups[(size_t)x].nnz_begin) >
                    (groups[(size_t)y].nnz_end - groups[(size_t)y].nnz_begin);
         });
+        // Plans cut along K: every block works on one slice (slice by slice here, heaviest
+        // first inside a slice); the blocks are dealt out to the slices in turn at the end.
+        auto slice_of = [&](int64_t gi) { return NS > 1 ? (int64_t)groups[(size_t)gi].row_begin / MS : (int64_t)0; };
+        if (NS > 1) {
+            std::stable_sort(split_heads.begin(), split_heads.end(), [&](int64_t x, int64_t y) { return slice_of(x) < slice_of(y); });
+            std::stable_sort(whole.begin(), whole.end(), [&](int64_t x, int64_t y) { return slice_of(x) < slice_of(y); });
+        }
 
         // upper bound of the stream: headers (padded per window), columns, values
         const int64_t bound_words = total_chunks * (1 + UFK) + total_value_words + 8 * total_chunks / 4 + 64;
@@ -759,9 +867,14 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         {
             size_t at = 0;
             int used = WAVES_PER_WG, panels = SPLIT_PANELS_PER_WG;  // forces a new block
+            int64_t slice_now = -1;
             for (int64_t head : split_heads) {
                 const Group &g0 = groups[(size_t)head];
                 const int nseg = g0.nseg;
+                if (slice_of(head) != slice_now) {  // a block never mixes slices
+                    slice_now = slice_of(head);
+                    used = WAVES_PER_WG;
+                }
                 if (g0.flags & FLAG_CROSS) {
                     // a panel cut across blocks: its pieces fill blocks of their own, eight at a
                     // time; after its barrier wave r of every block adds row r of the block's
@@ -830,7 +943,12 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         {
             size_t at = 0;
             int used = WAVES_PER_WG;
+            int64_t slice_now = -1;
             for (int64_t gi2 : whole) {
+                if (slice_of(gi2) != slice_now) {
+                    slice_now = slice_of(gi2);
+                    used = WAVES_PER_WG;
+                }
                 if (used == WAVES_PER_WG) {
                     at = new_block(0);
                     used = 0;
@@ -838,6 +956,38 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
                 place(gi2, &out.items[at + (size_t)used * ITEM_WORDS]);
                 used += 1;
             }
+        }
+        if (NS > 1) {
+            // Block b of the launch works on slice b mod NS: workgroups go to the XCDs in
+            // turn, so an XCD's L2 sees the rows of B of one slice (of 8 / NS slices' worth of
+            // XCDs).  A slice with fewer blocks than the longest gets idle blocks.
+            const size_t BW = (size_t)WAVES_PER_WG * ITEM_WORDS;
+            std::vector<std::vector<size_t>> of_slice((size_t)NS);
+            for (size_t b = 0; b < (size_t)out.n_blocks; ++b) {
+                int64_t sl = 0;
+                for (int w = 0; w < WAVES_PER_WG; ++w) {
+                    const uint32_t *it = &out.items[b * BW + (size_t)w * ITEM_WORDS];
+                    if (!(it[IT_FLAGS] & FLAG_IDLE)) {
+                        sl = (int64_t)it[IT_ROW0] / MS;
+                        break;
+                    }
+                }
+                of_slice[(size_t)sl].push_back(b);
+            }
+            size_t longest = 0;
+            for (const std::vector<size_t> &v : of_slice) longest = std::max(longest, v.size());
+            std::vector<uint32_t> dealt(longest * (size_t)NS * BW, 0u);
+            for (size_t i = 0; i < longest; ++i)
+                for (size_t sl = 0; sl < (size_t)NS; ++sl) {
+                    uint32_t *dst = dealt.data() + (i * (size_t)NS + sl) * BW;
+                    if (i < of_slice[sl].size())
+                        std::copy(out.items.begin() + (ptrdiff_t)(of_slice[sl][i] * BW),
+                                  out.items.begin() + (ptrdiff_t)((of_slice[sl][i] + 1) * BW), dst);
+                    else
+                        for (int w = 0; w < WAVES_PER_WG; ++w) dst[(size_t)w * ITEM_WORDS + IT_FLAGS] = FLAG_IDLE;
+                }
+            out.items.swap(dealt);
+            out.n_blocks = (int64_t)(longest * (size_t)NS);
         }
         out.wins.push_back(0u);  // look-ahead slot
         // the windows' words, contiguous runs of placed groups per thread
@@ -877,7 +1027,7 @@ int spmm_inspect(int64_t M, int64_t K, const int32_t *row_ptr, const int32_t *co
         out.n_chunks = total_chunks;
         out.n_enum = total_enum;
         // the kernel may fetch the map entries of a whole panel at once
-        if (sorted) out.rowmap.resize((size_t)M + MAX_UFI, 0u);
+        if (sorted) out.rowmap.resize((size_t)MP + MAX_UFI, 0u);
     } catch (const std::bad_alloc &) {
         out = HostPlan();
         return ST_ALLOC;

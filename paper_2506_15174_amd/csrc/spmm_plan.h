@@ -30,6 +30,15 @@ struct HostPlan {
     // Rows sorted by length (skewed matrices): rowmap[i] = row of A and C that the
     // plan's row i stands for.  Empty = the plan's rows are the matrix's rows.
     std::vector<uint32_t> rowmap;
+    // Plans cut along K (k_slices > 1): the plan's rows are k_slices copies of the matrix's
+    // rows, copy s holding the entries whose columns fall into [s * slice_cols, (s + 1) *
+    // slice_cols); every copy is padded to slice_rows rows (a multiple of the tallest panel),
+    // so plan row s * slice_rows + i stands for slice s of row i (of row rowmap[...] when sorted).
+    // The executor writes the slices' sums to a buffer of k_slices * slice_rows rows and a
+    // second launch adds them into C.  rowmap then has plan_rows entries and holds rows of
+    // that buffer.  k_slices == 1: plan_rows == M, slice_rows == M, slice_cols == K.
+    int32_t k_slices = 1;
+    int64_t slice_rows = 0, slice_cols = 0, plan_rows = 0;
 };
 
 struct InspectorOptions {
@@ -41,6 +50,7 @@ struct InspectorOptions {
     int32_t threads = 0;       // 0 = choose; else host threads of the enumeration (1..64)
     int32_t cross = 0;         // 0 = choose whether panels may be cut across blocks; < 0 = never; > 0 = always
     int32_t ufk = 0;           // 0 = choose; else columns per chunk: 8, 16, 32 or 64
+    int32_t kslices = 0;       // 0 = choose; 1 = never cut along K; 2, 4 or 8 = so many slices
 };
 
 // Status codes follow spmm_status_t (0 ok, 1 invalid argument, 2 invalid CSR,

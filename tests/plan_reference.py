@@ -40,6 +40,7 @@ def _groups_for(rp, M, ufi, group_nnz, group_panels, cross=True):
             want = min(WAVES_PER_WG, -(-pn // group_nnz))
             while want & (want - 1):
                 want += 1
+            want = max(want, ufi)      # a block holds 8 / ufi split panels
             across = cross and pn > part_bound
             if across:
                 want = WAVES_PER_WG * min(MAX_CROSS_PARTS, -(-pn // part_bound))
@@ -145,9 +146,75 @@ def choose_ufi_skewed(K, nnz, max_row, n_hint=0, cross=False):
     return h
 
 
+def choose_kslices(M, K, nnz, n_hint=0, setting=0, ufk=UFK):
+    """Column ranges a plan is cut into (1 = not cut): the caller's setting (2, 4, 8; any
+    other nonzero value = 1), else the smallest power of two whose share of a column tile
+    of B (512 bytes per row, 256 for hints of 33 to 64 columns) takes at most half of a
+    4 MiB L2, when the whole tile exceeds one L2, the matrix holds 2^20 entries or more and
+    its rows at least 32 entries per range on average (a tile of exactly one L2: rows of
+    1024 entries on average); plans with chunks wider than 8 are never cut."""
+    if ufk != UFK or M <= 0 or K < 8 or (M + MAX_UFI) * 8 > 2**31 - 1:
+        return 1
+    if setting in (2, 4, 8):
+        return setting
+    if setting != 0:
+        return 1
+    tile_row_bytes = 256 if 32 < n_hint <= 64 else 512
+    l2 = 4 << 20
+    if K * tile_row_bytes < l2 or nnz < 1 << 20:
+        return 1
+    ns = 2
+    while ns < 8 and -(-K // ns) * tile_row_bytes > l2 // 2:
+        ns *= 2
+    min_row = 32 * ns if K * tile_row_bytes > l2 else 1024       # a tile of exactly one L2: long rows only
+    return ns if nnz >= min_row * M else 1
+
+
+def sliced_row_ptr(row_ptr, col_idx, K, ns, order=None):
+    """Row pointer of the rows of a plan cut into `ns` column ranges: range s of row i
+    (of row order[i] when given) is plan row s * MS + i, MS = M rounded up to 8."""
+    row_ptr = np.asarray(row_ptr, dtype=np.int64)
+    M = len(row_ptr) - 1
+    MS = -(-M // MAX_UFI) * MAX_UFI
+    KS = -(-K // ns)
+    lens = np.diff(row_ptr)
+    rows = np.repeat(np.arange(M), lens)
+    if order is not None:
+        pos = np.empty(M, dtype=np.int64)
+        pos[np.asarray(order)] = np.arange(M)
+        rows = pos[rows]
+    cnt = np.bincount((np.asarray(col_idx, dtype=np.int64) // KS) * MS + rows, minlength=ns * MS)
+    return np.concatenate(([0], np.cumsum(cnt)))
+
+
+def plan_schedule(row_ptr, col_idx, M, K, n_hint=0, ufi=0, sort_rows=0, cross=0, kslices=0, ufk=UFK):
+    """(column ranges, panel height, rows sorted?, panels cut across workgroups allowed?) as
+    the inspector decides them; `ufi`, `sort_rows`, `cross` and `kslices` are the caller's
+    settings (0 = choose).  A plan cut along K chooses its height as for the columns of one
+    range and the longest row of a range, and cuts panels across workgroups only where the
+    tallest panels would otherwise be too heavy for one workgroup."""
+    lens = np.diff(np.asarray(row_ptr, dtype=np.int64))
+    nnz = int(lens.sum())
+    ns = choose_kslices(M, K, nnz, n_hint, kslices, ufk)
+    may_cross = cross_allowed(row_ptr, cross, n_hint)
+    max_row = int(lens.max()) if M else 0
+    KS = -(-K // ns)
+    if ns > 1:
+        rows = np.repeat(np.arange(M), lens)
+        per = np.bincount(rows * ns + np.asarray(col_idx, dtype=np.int64) // KS, minlength=M * ns)
+        max_row = int(per.max()) if len(per) else 0
+        if cross == 0 and may_cross:
+            if choose_ufi_skewed(KS, nnz, max_row, n_hint, False) >= (4 if 32 < n_hint <= 64 else 8):
+                may_cross = False
+    skewed = skewed_rows(row_ptr)
+    if ufi not in (1, 2, 4, 8):
+        as_sorted = sort_rows > 0 or (sort_rows == 0 and skewed)
+        ufi = choose_ufi_skewed(KS, nnz, max_row, n_hint, may_cross) if as_sorted else choose_ufi(M, KS, nnz, n_hint)
+    return ns, ufi, bool(sort_rows > 0 or (sort_rows == 0 and skewed and ufi > 1)), may_cross
+
+
 def choose_schedule(row_ptr, M, K, n_hint=0, ufi=0, sort_rows=0, cross=0):
-    """(panel height, rows sorted?) as the inspector decides them: `ufi`, `sort_rows` and
-    `cross` are the caller's settings (0 = choose; sort_rows > 0 sort, < 0 keep)."""
+    """(panel height, rows sorted?) of a plan that is not cut along K."""
     lens = np.diff(np.asarray(row_ptr, dtype=np.int64))
     nnz = int(lens.sum())
     skewed = skewed_rows(row_ptr)
@@ -187,6 +254,30 @@ def derive_groups(row_ptr, M, group_nnz, group_panels, ufi, cross=True):
     blocks = _blocks_for(split, whole, ufi)
     out = [piece for pieces in split for piece in pieces] + whole
     return np.array(out, dtype=np.int32).reshape(-1, 5), blocks
+
+
+def derive_sliced_groups(plan_ptr, slice_rows, ns, group_nnz, group_panels, ufi, cross=True):
+    """derive_groups for a plan cut into `ns` column ranges (plan_ptr from sliced_row_ptr):
+    groups and blocks are formed range by range, and every range gets as many blocks as
+    the one with the most (they are dealt to the ranges in turn)."""
+    rp = [int(x) for x in plan_ptr]
+    split, whole = _groups_for(rp, ns * slice_rows, ufi, group_nnz, group_panels, cross)
+    out_split, out_whole, most = [], [], 0
+    for sl in range(ns):
+        sp = [pieces for pieces in split if pieces[0][0] // slice_rows == sl]
+        wh = [g for g in whole if g[0] // slice_rows == sl]
+        most = max(most, _blocks_for(sp, wh, ufi))
+        out_split += [piece for pieces in sp for piece in pieces]
+        out_whole += wh
+    return np.array(out_split + out_whole, dtype=np.int32).reshape(-1, 5), most * ns
+
+
+def undeal_blocks(items, ns):
+    """The wave-slot table of a plan cut into `ns` ranges with its blocks back in the order
+    they were formed: range by range (block b of the launch belongs to range b mod ns)."""
+    blocks = np.asarray(items).reshape(-1, WAVES_PER_WG, ITEM_WORDS)
+    assert len(blocks) % ns == 0
+    return np.concatenate([blocks[sl::ns] for sl in range(ns)]).reshape(-1)
 
 
 def canonical_csr(row_ptr, col_idx, vals):

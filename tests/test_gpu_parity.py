@@ -388,6 +388,97 @@ def test_panels_cut_across_workgroups_in_a_replayed_graph(torch_gpu, oracle):
     check(oracle, csr, B.cpu().numpy(), C.cpu().numpy())
 
 
+@pytest.mark.parametrize("N", [1, 5, 32, 64, 100, 128, 129, 200, 257])
+@pytest.mark.parametrize("ns,ufi,sort_rows,cross", [(2, 0, 0, 0), (4, 8, 1, 1), (8, 4, 1, -1), (4, 2, -1, 0), (8, 1, 0, 1),
+                                                    (2, 8, -1, 1)])
+def test_plans_cut_along_k(torch_gpu, oracle, ns, ufi, sort_rows, cross, N):
+    """A plan cut into column ranges: every workgroup multiplies one range, the ranges' sums
+    meet in the plan's scratch memory and a last launch adds them in range order, 128 columns
+    of B at a time (N = 200 and 257 take two and three rounds).  Small integers: bit-exact
+    against the oracle whatever the order of the additions; repeated executes are
+    bit-identical; rows outside C stay untouched; M is not a multiple of the panel height."""
+    rng = np.random.default_rng(700 + ns + ufi)
+    M, K = 61, 2600
+    W = np.where(rng.random((M, K)) < 0.04, rng.integers(-8, 9, (M, K)), 0).astype(np.float32)
+    W[1] = rng.integers(1, 9, K)
+    W[2, ::3] = rng.integers(1, 9, len(W[2, ::3]))
+    W[40] = rng.integers(1, 9, K)
+    W[[7, 8, 9]] = 0
+    csr = gen.csr_from_dense(W)
+    B = rng.integers(-16, 17, (K, N)).astype(np.float32)
+    C_ref, _ = oracle.spmm(csr.row_ptr, csr.col_idx, csr.vals, B)
+    assert np.abs(C_ref).max() < 2 ** 24
+    C, plan = gpu_product(torch_gpu, csr, B, guard_rows=2, group_nnz=64, ufi=ufi, sort_rows=sort_rows, cross=cross,
+                          kslices=ns)
+    info = plan.describe()
+    assert info["k_slices"] == ns and info["slice_rows"] == 64 and info["scratch_bytes"] >= ns * 64 * 128 * 4
+    # heavy panels of a range are cut across workgroups as in any plan (a single row's share
+    # of a range, 325 entries, stays below the bound of eight budgets)
+    assert (info["n_cross"] > 0) == (cross > 0 and ufi == 8)
+    assert np.array_equal(C.astype(np.float64), C_ref)
+    dB = torch_gpu.from_numpy(B).cuda()
+    for _ in range(2):
+        again = plan.execute(dB)
+        torch_gpu.cuda.synchronize()
+        assert np.array_equal(C, again.cpu().numpy())
+    # the entry point without allocations has no room for the ranges' sums
+    with pytest.raises(spmm.SpmmError) as e:
+        plan.execute_static_raw(dB.data_ptr(), N, again.data_ptr())
+    assert e.value.status == spmm.SPMM_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("N", [128, 64, 40])
+def test_plans_cut_along_k_with_real_data_and_unsorted_columns(torch_gpu, oracle, N):
+    """Column ranges of a matrix whose rows are stored with their columns in random order and
+    with duplicates (the inspector orders every row before it cuts it), lognormal row
+    lengths, real values: within the tolerance of the oracle."""
+    csr = gen.lognormal_rows(700, 5000, 0.9, 31)
+    rng = np.random.default_rng(32)
+    rows = np.repeat(np.arange(csr.M), np.diff(csr.row_ptr))
+    extra_rows = rng.integers(0, csr.M, 500)
+    rows_all = np.concatenate([rows, extra_rows])
+    cols_all = np.concatenate([csr.col_idx, rng.integers(0, csr.K, 500).astype(np.int32)])
+    vals_all = np.concatenate([csr.vals, rng.standard_normal(500).astype(np.float32)])
+    o = np.lexsort((rng.random(len(rows_all)), rows_all))       # rows together, columns shuffled
+    row_ptr = np.concatenate(([0], np.cumsum(np.bincount(rows_all, minlength=csr.M)))).astype(np.int32)
+    shuffled = gen.Csr(csr.M, csr.K, row_ptr, cols_all[o].astype(np.int32), vals_all[o].astype(np.float32))
+    B = gen.dense_activations(csr.K, N, 33)
+    for ns in (2, 8):
+        C, plan = gpu_product(torch_gpu, shuffled, B, guard_rows=1, kslices=ns, n_hint=N)
+        assert plan.describe()["k_slices"] == ns
+        check(oracle, shuffled, B, C)
+
+
+def test_plan_cut_along_k_in_a_replayed_graph(torch_gpu, oracle):
+    """The three launches of a plan cut along K whose heavy panels are also cut across
+    workgroups (product, sums of the cut panels, sums of the ranges) replay from a graph."""
+    torch = torch_gpu
+    csr = heavy_tail(64, 3000, 197)
+    N = 128
+    plan = spmm.plan_create(csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals, group_nnz=64, ufi=4, cross=1, kslices=4)
+    assert plan.describe()["n_cross"] > 0 and plan.describe()["k_slices"] == 4
+    B = torch.from_numpy(gen.dense_activations(csr.K, N, 198)).cuda()
+    C = torch.full((csr.M, N), float("nan"), dtype=torch.float32, device="cuda")
+    eager = plan.execute(B).clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        plan.execute(B, C)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.execute(B, C)
+    for replay in range(4):
+        C.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(C, eager), "replay %d differs from the eager result" % replay
+        plan.execute(B)
+        torch.cuda.synchronize()
+    check(oracle, csr, B.cpu().numpy(), C.cpu().numpy())
+
+
 def test_measuring_plans_load_everything_and_multiply_nothing(torch_gpu):
     """probe = 1: the launches request every row of B as the product does and skip the
     multiply-adds, so C is all zeros (never NaN: every element is still written); the
@@ -486,13 +577,19 @@ def test_stress_config_whole_product_at_full_size(torch_gpu, oracle):
     B = gen.activations_for(csr, 128)
     C, plan = gpu_product(torch_gpu, csr, B, n_hint=128)
     # Zipf rows: the inspector sorts them by length, takes eight-row panels and cuts the
-    # heavy ones (the dense rows) across workgroups
+    # heavy ones (the dense rows) across workgroups; 128 columns of B (8 MiB) exceed one L2:
+    # the plan is cut into four column ranges
     info = plan.describe()
-    assert (info["sorted_rows"], info["ufi"]) == (1, 8) and info["n_cross"] > 50 and info["scratch_bytes"] > 0
+    assert (info["sorted_rows"], info["ufi"], info["k_slices"]) == (1, 8, 4)
+    assert info["n_cross"] > 50 and info["scratch_bytes"] > 4 * 16384 * 128 * 4
     check(oracle, csr, B, C, parallel=True)
     lens = np.diff(csr.row_ptr)
     # every empty row of the full matrix is exactly zero
     assert not C[lens == 0].any()
+    # the same matrix left whole (two tiles of 64 columns in one launch)
+    C1, plan1 = gpu_product(torch_gpu, csr, B, n_hint=128, kslices=1)
+    assert plan1.describe()["k_slices"] == 1 and plan1.describe()["n_cross"] > 50
+    check(oracle, csr, B, C1, parallel=True)
 
 
 @pytest.mark.parametrize("N,want_ufi", [(128, 8), (64, 8), (32, 8)])
@@ -515,8 +612,12 @@ def test_wide_b_beyond_one_l2_runs_as_tiles_of_64_columns(torch_gpu, oracle, N):
     the workgroups per CU) over eight-row panels; every element against the oracle."""
     csr = gen.magnitude_pruned(4096, 12288, 0.7, 91)
     B = gen.activations_for(csr, N)
-    C, plan = gpu_product(torch_gpu, csr, B, n_hint=N)
+    C, plan = gpu_product(torch_gpu, csr, B, n_hint=N, kslices=1)
     assert plan.describe()["ufi"] == 8 and plan.describe()["sorted_rows"] == 0
+    check(oracle, csr, B, C, parallel=True)
+    # by default the plan is cut into four ranges of 3072 columns (1.5 MiB of B each) instead
+    C, plan = gpu_product(torch_gpu, csr, B, n_hint=N)
+    assert (plan.describe()["ufi"], plan.describe()["k_slices"], plan.describe()["slice_cols"]) == (8, 4, 3072)
     check(oracle, csr, B, C, parallel=True)
 
 

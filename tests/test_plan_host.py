@@ -16,9 +16,9 @@ import pytest
 import paper_2506_15174_amd as spmm
 from workloads import generators as gen
 
-from plan_reference import (UFK, canonical_csr, choose_group_budget, choose_schedule, choose_ufi,
+from plan_reference import (UFK, canonical_csr, choose_group_budget, choose_kslices, choose_schedule, choose_ufi,
                             check_blocks, choose_ufi_skewed, cross_allowed, decode_plan, derive_groups, interpret_plan, skewed_rows,
-                            sorted_row_order,
+                            derive_sliced_groups, plan_schedule, sliced_row_ptr, sorted_row_order, undeal_blocks,
                             walk_chunks)
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -167,7 +167,11 @@ SCHEDULE_CASES = [
     ((8192, 8192, 4096, 32), (8, 1024, 1)),
     # ... medium and wide B: 8 rows as well
     ((8192, 8192, 4096, 64), (8, 1024, 1)),
-    ((8192, 8192, 4096, 128), (8, 1024, 1)),
+    # (128 columns of B: 8192 rows of 512 bytes are exactly one L2 and the rows hold 1024 entries or
+    # more: two column ranges; 2 x 8192 plan rows = 2048 panels of 16384 -> 4 pieces -> 5120 -> 1024)
+    ((8192, 8192, 4096, 128), (8, 1024, 1, 2)),
+    ((8192, 8192, 4096, 128, 1), (8, 1024, 1, 1)),
+    ((8192, 8192, 1000, 128), (8, 1024, 1, 1)),
     # 64 columns of B: 8 rows from 4096 rows on when rows hold 256 or more
     ((4096, 1024, 512, 64), (8, 640, 1)),
     # ... 512 panels of 3280 -> 8 pieces -> ceil(5*3280/32) = 513 -> 544
@@ -176,24 +180,44 @@ SCHEDULE_CASES = [
     ((1024, 4096, 2048, 64), (2, 640, 1)),
     # wide B, 1024 rows of 102 (64 <= 102 < 128): 2 rows; 512 panels of 204 -> ceil(1020/32) = 32
     ((1024, 1024, 102, 128), (2, 32, 1)),
-    # 16384 rows of B of 512 bytes do not fit one L2: single rows; 2 panels per wave, capped budget
-    ((16384, 16384, 800, 128), (1, 1024, 2)),
+    # 16384 rows of B of 512 bytes do not fit one L2.  Left whole (kslices = 1): single rows; 2 panels
+    # per wave, capped budget
+    ((16384, 16384, 800, 128, 1), (1, 1024, 2)),
     # ... but rows of 1100 take eight rows there (the product runs as 64-column tiles that fit):
     # 2048 panels of 8800 -> 4 pieces -> ceil(5*8800/16) = 2750 -> capped at 1024
-    ((16384, 16384, 1100, 128), (8, 1024, 1)),
+    ((16384, 16384, 1100, 128, 1), (8, 1024, 1)),
     # K = 32768: no tile fits, single rows whatever the rows
-    ((4096, 32768, 2000, 128), (1, 1024, 1)),
+    ((4096, 32768, 2000, 128, 1), (1, 1024, 1)),
+    # By default such matrices are cut along K (13 M entries >= 2^20): 16384 columns in 4 ranges of
+    # 4096 (2 MiB of B each).  The height is that of a 4096-column matrix (rows of 800 >= 192: eight
+    # rows); 4 x 16384 plan rows = 8192 panels of 1600 -> whole panels, ceil(5*1600/4) = 2000 -> 1024
+    ((16384, 16384, 800, 128), (8, 1024, 1, 4)),
+    # ... 32768 columns in 8 ranges of 4096; 8 x 4096 plan rows = 4096 panels of 2000 -> 2500 -> 1024
+    ((4096, 32768, 2000, 128), (8, 1024, 1, 8)),
+    # ... 64 columns of B: 16384 rows of 256 bytes fit (not cut); 32768 do not: 4 ranges of 8192 (2 MiB)
+    ((16384, 16384, 800, 64), (8, 1024, 1, 1)),
+    ((8192, 32768, 800, 64), (8, 1024, 1, 4)),
+    # ... rows too short for 4 ranges (rows of 100 < 4 x 32) or too few entries (2^20 > 16384 x 60): whole,
+    # single rows, 2 per wave: ceil(5*100*2/4) = 250 -> 256, ceil(5*60*2/4) = 150 -> 160
+    ((16384, 16384, 100, 128), (1, 256, 2, 1)),
+    ((16384, 16384, 60, 128), (1, 160, 2, 1)),
+    # ... a plan with chunks of 16 (hint of 32 columns or fewer) is never cut
+    ((4096, 65536, 2000, 32), (1, 1024, 1, 1)),
 ]
 
 
 @pytest.mark.parametrize("case,want", SCHEDULE_CASES)
 def test_schedule_constants_rule(case, want):
-    M, K, per_row, hint = case
-    info = _row_ptr_only_plan(M, K, per_row, n_hint=hint).describe()
-    assert (info["ufi"], info["group_nnz"], info["group_panels"]) == want
+    M, K, per_row, hint = case[:4]
+    setting = case[4] if len(case) > 4 else 0
+    info = _row_ptr_only_plan(M, K, per_row, n_hint=hint, kslices=setting).describe()
+    assert (info["ufi"], info["group_nnz"], info["group_panels"]) == want[:3]
     nnz = M * per_row
-    ufi = choose_ufi(M, K, nnz, hint)
-    assert (ufi,) + choose_group_budget(M, nnz, ufi, hint) == want
+    ns = choose_kslices(M, K, nnz, hint, setting, info["ufk"])
+    assert info["k_slices"] == ns == (want[3] if len(want) > 3 else 1)
+    assert info["slice_rows"] == (-(-M // 8) * 8 if ns > 1 else M) and info["slice_cols"] == -(-K // ns)
+    ufi = choose_ufi(M, -(-K // ns), nnz, hint)
+    assert (ufi,) + choose_group_budget(ns * info["slice_rows"], nnz, ufi, hint) == want[:3]
 
 
 def _plan_from_row_lengths(lens, K, **kw):
@@ -228,8 +252,9 @@ SKEWED_CASES = [
     # 14000: 8 x 2000 <= 28000 -> eight rows; narrow B: two rows
     (((1024, 2000), (15360, 100)), 2048, 0, (8, 1)),
     (((1024, 2000), (15360, 100)), 2048, 32, (2, 1)),
-    # K = 16384: 128 columns of B exceed one L2 but the executor's 64-column tiles fit;
-    # 64 columns of a K = 32768 matrix do not: single rows
+    # K = 16384: 128 columns of B exceed one L2; the plan is cut into 4 column ranges (3.6 M entries
+    # >= 32 x 4 x 16384) and takes the height of a 4096-column matrix; K = 32768 would need 8 ranges,
+    # for which the rows are too short (3.6 M < 32 x 8 x 16384): left whole, single rows, unsorted
     (((1024, 2000), (15360, 100)), 16384, 128, (8, 1)),
     (((1024, 2000), (15360, 100)), 32768, 128, (1, 0)),
 ]
@@ -242,9 +267,17 @@ def test_schedule_of_skewed_matrices(runs, K, hint, want):
     row_ptr, plan = _plan_from_row_lengths(lens, K, n_hint=hint)
     info = plan.describe()
     assert (info["ufi"], info["sorted_rows"]) == want
-    assert choose_schedule(row_ptr, len(lens), K, hint) == (want[0], bool(want[1]))
+    col_idx = np.concatenate([np.arange(n, dtype=np.int32) for n in lens])
+    assert plan_schedule(row_ptr, col_idx, len(lens), K, hint)[:3] == (info["k_slices"], want[0], bool(want[1]))
     if want[1]:
         rowmap = plan.get_array(spmm.ARRAY_ROWMAP)
+        if info["k_slices"] > 1:
+            # cut along K: one map per column range, the same order in each, shifted by the range's rows
+            M, MS = len(lens), info["slice_rows"]
+            maps = rowmap.reshape(info["k_slices"], MS)
+            for sidx, m in enumerate(maps):
+                assert np.array_equal(m[:M], maps[0][:M] + sidx * MS) and np.array_equal(m[M:], np.arange(M, MS) + sidx * MS)
+            rowmap = maps[0][:M]
         assert sorted(rowmap.tolist()) == list(range(len(lens)))
         sl = lens[rowmap]
         assert np.all(np.diff(sl) <= 0), "longest rows first"
@@ -578,6 +611,96 @@ def test_heavy_panels_are_cut_across_blocks(ufi):
             assert entry[4:4 + rows_of_panel].tolist() == want_rows and not entry[4 + rows_of_panel:].any()
         C = interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap)
         assert np.array_equal(C.astype(np.float64), dense)
+
+
+def sliced_plan_rows(csr, plan):
+    """(row map or None, row pointer of the plan's rows, row order or None) of a plan cut along K,
+    with the exported map checked against the order the header describes."""
+    info = plan.describe()
+    ns, MS = info["k_slices"], info["slice_rows"]
+    rowmap = plan.get_array(spmm.ARRAY_ROWMAP)
+    order = None
+    if info["sorted_rows"]:
+        order, _ = sorted_row_order(csr.row_ptr)
+        want = np.arange(ns * MS).reshape(ns, MS)
+        want[:, :csr.M] = order[None, :] + (np.arange(ns) * MS)[:, None]
+        assert np.array_equal(rowmap, want.reshape(-1))
+    else:
+        assert len(rowmap) == 0
+        rowmap = None
+    return rowmap, sliced_row_ptr(csr.row_ptr, csr.col_idx, csr.K, ns, order), order
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+@pytest.mark.parametrize("ns", [2, 4, 8])
+@pytest.mark.parametrize("force_ufi", [0, 1, 4, 8])
+@pytest.mark.parametrize("sort_rows,cross,group_nnz", [(0, 0, 0), (1, 1, 32), (-1, -1, 200)])
+def test_plans_cut_along_k(oracle, name, ns, force_ufi, sort_rows, cross, group_nnz):
+    """A plan cut into column ranges is the plan of the matrix's rows taken once per range
+    (range s of row i as plan row s * slice_rows + i): same groups as the re-derivation
+    from that row pointer, every block in one range, block b of the launch in range
+    b mod k_slices, the entries of the matrix each exactly once and in their range, and the
+    ranges' partial products adding up to the product."""
+    csr = CASES[name]()
+    plan = host_plan(csr, kslices=ns, ufi=force_ufi, sort_rows=sort_rows, cross=cross, group_nnz=group_nnz)
+    info = plan.describe()
+    nnz = int(csr.row_ptr[-1])
+    want_ns = choose_kslices(csr.M, csr.K, nnz, 0, ns)
+    assert info["k_slices"] == want_ns == (ns if csr.K >= 8 else 1)
+    MS, KS = info["slice_rows"], info["slice_cols"]
+    assert (info["M"], info["K"]) == (csr.M, csr.K) and MS == -(-csr.M // 8) * 8 and KS == -(-csr.K // ns)
+    _, UFI, is_sorted, may_cross = plan_schedule(csr.row_ptr, csr.col_idx, csr.M, csr.K, 0, force_ufi, sort_rows, cross, ns)
+    assert info["ufi"] == UFI and info["sorted_rows"] == int(is_sorted)
+    rowmap, plan_ptr, order = sliced_plan_rows(csr, plan)
+    assert plan_ptr[-1] == nnz
+    auto_g, auto_gp = choose_group_budget(ns * MS, nnz, UFI)
+    if may_cross:
+        auto_g = max(32, auto_g // 2 // 32 * 32)
+    elif skewed_rows(csr.row_ptr):
+        auto_g = max(32, auto_g // 4 // 32 * 32)       # skewed rows, every panel inside one workgroup: a quarter
+    assert info["group_nnz"] == (group_nnz or auto_g) and info["group_panels"] == auto_gp
+    want, blocks = derive_sliced_groups(plan_ptr, MS, ns, info["group_nnz"], info["group_panels"], UFI, cross=may_cross)
+    assert np.array_equal(plan.get_groups(), want) and info["n_blocks"] == blocks and blocks % ns == 0
+    items, hdr, stream, wins = arrays(plan)
+    # block b of the launch holds rows of range b mod ns only
+    for b, blk in enumerate(items.reshape(-1, 8, 16)):
+        live = blk[(blk[:, 5] & 2) == 0]
+        assert np.all(live[:, 0] // MS == b % ns) and np.all((live[:, 0] + live[:, 1] - 1) // MS == b % ns)
+    formed = undeal_blocks(items, ns)
+    rows, cc, bits = decode_plan(formed, hdr, stream, wins, UFI, rowmap)
+    assert len(rows) == nnz
+    assert np.array_equal(rows // MS, cc // KS), "every entry sits in the range of its column"
+    o = np.lexsort((cc, rows % MS))
+    want_rows, want_cols, want_bits = canonical_csr(csr.row_ptr, csr.col_idx, csr.vals)
+    assert np.array_equal((rows % MS)[o], want_rows) and np.array_equal(cc[o], want_cols)
+    assert np.array_equal(bits[o], want_bits)
+    # the ranges' products, added in range order as the last launch does
+    B = gen.dense_activations(csr.K, 5, 99)
+    parts = interpret_plan(formed, hdr, stream, wins, B, ns * MS, UFI, rowmap).reshape(ns, MS, 5)
+    assert not np.isnan(parts).any(), "every row of every range is written"
+    assert not parts[:, csr.M:].any(), "the rows that pad a range are empty"
+    C = parts[0, :csr.M].copy()
+    for sl in range(1, ns):
+        C += parts[sl, :csr.M]
+    C_ref, S = oracle.spmm(csr.row_ptr, csr.col_idx, csr.vals, B)
+    err, bad_zero = oracle.parity_error(C, C_ref, S)
+    assert err <= 1e-5 and bad_zero == 0
+
+
+def test_options_of_plans_cut_along_k():
+    csr = CASES["uniform_half"]()
+    for bad in (3, 5, 16, -1):
+        with pytest.raises(spmm.SpmmError) as e:
+            host_plan(csr, kslices=bad)
+        assert e.value.status == spmm.SPMM_ERR_INVALID_ARG
+    with pytest.raises(spmm.SpmmError) as e:     # only plans with chunks of 8 columns are cut
+        host_plan(csr, kslices=4, ufk=16)
+    assert e.value.status == spmm.SPMM_ERR_INVALID_ARG
+    assert host_plan(csr, kslices=4, n_hint=16).describe()["k_slices"] == 1      # the hint's wider chunks win
+    assert host_plan(csr, kslices=1).describe()["k_slices"] == 1
+    assert host_plan(csr).describe()["k_slices"] == 1                            # a small matrix is never cut by itself
+    info = host_plan(gen.csr_from_dense(np.ones((3, 5), np.float32)), kslices=8).describe()
+    assert (info["k_slices"], info["slice_rows"], info["slice_cols"]) == (1, 3, 5)   # fewer than 8 columns
 
 
 @pytest.mark.parametrize("K", [(1 << 24) - 1, 1 << 24, (1 << 24) + 1, (1 << 24) + 77])
