@@ -59,18 +59,24 @@ struct Entry {
 //     (8192 < K <= 16384, run as tiles of 64 columns) takes eight rows from 4096
 //     rows on with row >= 1024 (16384 x 16384 at 90 %: 434 against 521 us; at
 //     98 %, row 327, single rows win 118 against 159 us);
+//   * what a tall panel saves are the columns its rows have in common; two rows of the mean
+//     length share about row * row / K of them (`shared` below);
 //   * narrow B (hint <= 32 columns): one wave load already covers eight enumerated
 //     columns, so tall panels save fewer loads: from 4096 rows on eight rows with
 //     row >= 768 and four with row >= 384 in rows at least an eighth full (chunks of 16
-//     columns, two per slice: 4096 x 4096
-//     at 50 % 27.7 against 32.3 us with four rows, 4096 x 1024 at 50 % 10.2 with four rows
-//     against 12.7 us with single rows); two rows for 512 .. 4095 rows with row >= 256;
-//     else single rows;
-//   * medium B (hint 33 .. 64): eight rows from 4096 rows on with row >= 256; two
-//     rows for 512 .. 4095 rows with row >= 64; else single rows;
-//   * wide or unknown B: eight rows from 4096 rows on with row >= 192; for 1024 ..
-//     4095 rows four rows with row >= 128 and two with row >= 64; two rows for
-//     512 .. 1023 rows with row >= 128; else single rows.
+//     columns, two per slice: 4096 x 4096 at 50 % 27.7 against 32.3 us with four rows,
+//     4096 x 1024 at 50 % 10.2 with four rows against 12.7 us with single rows); four rows
+//     under the same condition for 2048 .. 4095 rows (2048 x 8192 at 70 %: 23.9 against
+//     27.3 us with two rows); two rows for 1024 .. 2047 rows with row >= 256 in rows at
+//     least a third full, for 512 .. 1023 rows with row >= 256; else single rows;
+//   * medium B (hint 33 .. 64): eight rows from 4096 rows on with row >= 128 and shared
+//     >= 16; four rows for 2048 .. 4095 rows with row >= 256 and shared >= 32; two rows for
+//     1024 .. 2047 rows with shared >= 128 and for 512 .. 1023 rows with row >= 64; else
+//     single rows;
+//   * wide or unknown B: eight rows from 2048 rows on with row >= 128 and shared >= 16
+//     (2048 x 8192 at 70 %: 62 against 71 us with four rows); for 1024 .. 2047 rows four
+//     rows with row >= 128 and two with row >= 64; two rows for 512 .. 1023 rows with
+//     row >= 128; else single rows.
 //
 // Short rows leave most patterns with one row set, so tall panels share nothing;
 // few rows cannot fill the chip with tall panels (a split panel of eight rows owns
@@ -88,17 +94,22 @@ int choose_ufi(int64_t M, int64_t K, int64_t nnz, int32_t n_hint)
         if (!narrow && !medium && K * 256 <= l2 && M >= 4096 && row >= 1024) return 8;
         return 1;
     }
+    const int64_t shared = K > 0 ? row * row / K : 0;
     if (narrow) {
         if (M >= 4096) return row >= 768 ? 8 : row >= 384 && 8 * row >= K ? 4 : 1;
+        if (M >= 2048) return row >= 384 && 8 * row >= K ? 4 : 1;
+        if (M >= 1024) return row >= 256 && 3 * row >= K ? 2 : 1;
         if (M >= 512) return row >= 256 ? 2 : 1;
         return 1;
     }
     if (medium) {
-        if (M >= 4096) return row >= 256 ? 8 : 1;
+        if (M >= 4096) return row >= 128 && shared >= 16 ? 8 : 1;
+        if (M >= 2048) return row >= 256 && shared >= 32 ? 4 : 1;
+        if (M >= 1024) return shared >= 128 ? 2 : 1;
         if (M >= 512) return row >= 64 ? 2 : 1;
         return 1;
     }
-    if (M >= 4096) return row >= 192 ? 8 : 1;
+    if (M >= 2048) return row >= 128 && shared >= 16 ? 8 : 1;
     if (M >= 1024) return row >= 128 ? 4 : row >= 64 ? 2 : 1;
     if (M >= 512) return row >= 128 ? 2 : 1;
     return 1;
@@ -158,9 +169,11 @@ int choose_ufk(int64_t K, int32_t n_hint)
 // G = ceil(5 mean GP / (4 ppt)), rounded up to a multiple of 32 inside [32, 1024];
 // the quarter of headroom keeps panels near the mean on the typical piece count.
 // Single rows of a matrix of 1024 .. 2047 rows meant for B of at most 64 columns are not cut
-// below 256 entries (rows shorter than that stay whole): such products take 3 to 5 us, and
-// waves of 32 to 64 entries cost them 10 to 20 % in start-up (every wave first fetches its
-// descriptor, its first window and its first rows of B) and in workgroups to dispatch.
+// below 128 entries, nor into more than two pieces below 256: such products take 3 to 5 us, and
+// waves of 32 entries cost them 10 to 20 % in start-up (every wave first fetches its
+// descriptor, its first window and its first rows of B) and in workgroups to dispatch, while
+// whole rows of 200 and more entries leave the chip short of waves (1024 x 1024 at 80 %,
+// 64 columns: 4.4 us in halves against 5.8 us whole).
 // Wider B and matrices of fewer rows need the finer cut to occupy the chip.
 void choose_group_budget(int64_t M, int64_t nnz, int ufi, int32_t n_hint, int32_t &G_out, int32_t &GP_out)
 {
@@ -170,7 +183,7 @@ void choose_group_budget(int64_t M, int64_t nnz, int ufi, int32_t n_hint, int32_
     const int64_t GP = std::min<int64_t>(16, std::max<int64_t>(1, (P + 8191) / 8192));
     int64_t g = (5 * mean * GP + 4 * ppt - 1) / (4 * ppt);
     if (ufi == 1 && M >= 1024 && M < 2048 && n_hint > 0 && n_hint <= 64)
-        g = std::max<int64_t>(g, std::min<int64_t>((5 * mean + 3) / 4, 256));
+        g = std::max<int64_t>(g, std::min<int64_t>((5 * mean + 7) / 8, 128));
     g = (g + 31) / 32 * 32;
     if (g < 32) g = 32;
     if (g > 1024) g = 1024;

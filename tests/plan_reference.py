@@ -91,16 +91,25 @@ def choose_ufi(M, K, nnz, n_hint=0):
         # wide B run as 64-column tiles that still fit one L2
         wide_tiles = not narrow and not medium and K * 256 <= 4 << 20
         return 8 if (wide_tiles and M >= 4096 and row >= 1024) else 1
+    shared = row * row // K if K else 0      # columns two rows of the mean length have in common
     if narrow:
         if M >= 4096:
             return 8 if row >= 768 else 4 if (row >= 384 and 8 * row >= K) else 1
+        if M >= 2048:
+            return 4 if (row >= 384 and 8 * row >= K) else 1
+        if M >= 1024:
+            return 2 if (row >= 256 and 3 * row >= K) else 1
         return 2 if (M >= 512 and row >= 256) else 1
     if medium:
         if M >= 4096:
-            return 8 if row >= 256 else 1
+            return 8 if (row >= 128 and shared >= 16) else 1
+        if M >= 2048:
+            return 4 if (row >= 256 and shared >= 32) else 1
+        if M >= 1024:
+            return 2 if shared >= 128 else 1
         return 2 if (M >= 512 and row >= 64) else 1
-    if M >= 4096:
-        return 8 if row >= 192 else 1
+    if M >= 2048:
+        return 8 if (row >= 128 and shared >= 16) else 1
     if M >= 1024:
         return 4 if row >= 128 else 2 if row >= 64 else 1
     return 2 if (M >= 512 and row >= 128) else 1
@@ -240,8 +249,8 @@ def choose_group_budget(M, nnz, ufi, n_hint=0):
     ppt = min(8, -(-8192 // P)) if P < 4096 else 1
     GP = min(16, max(1, -(-P // 8192)))
     g = -(-(5 * mean * GP) // (4 * ppt))
-    if ufi == 1 and 1024 <= M < 2048 and 0 < n_hint <= 64:   # single rows of small matrices for narrow B: not cut below 256 entries
-        g = max(g, min(-(-(5 * mean) // 4), 256))
+    if ufi == 1 and 1024 <= M < 2048 and 0 < n_hint <= 64:   # single rows of small matrices for narrow B: not cut below 128 entries
+        g = max(g, min(-(-(5 * mean) // 8), 128))
     g = -(-g // 32) * 32
     return min(1024, max(32, g)), GP
 

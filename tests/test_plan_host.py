@@ -146,11 +146,28 @@ SCHEDULE_CASES = [
     ((512, 2048, 410, 32), (2, 160, 1)),
     # ... but rows of 200 stay single: 512 panels of 200 -> 8 pieces -> ceil(5*200/32) = 32
     ((512, 2048, 200, 32), (1, 32, 1)),
-    # 1024 single rows of 100 for narrow B are not cut: 125 -> 128; for wide B 8 pieces -> 16 -> 32
-    ((1024, 1024, 100, 32), (1, 128, 1)),
+    # 1024 single rows of 100 for narrow B are cut in two at most: ceil(5*100/8) = 63 -> 64; for wide B 8 pieces -> 16 -> 32
+    ((1024, 1024, 100, 32), (1, 64, 1)),
     ((1024, 1024, 30, 128), (1, 32, 1)),
-    # ... and rows of 400 for 64 columns (2 rows from rows of 64 on) are unaffected: 512 panels of 800 -> 125 -> 128
-    ((1024, 4096, 400, 64), (2, 128, 1)),
+    # ... rows of 400 in 4096 columns for 64 columns of B: two such rows share 400 * 400 / 4096 = 39 < 128
+    # columns: single rows, not cut below 128 entries either; rows of 1200 share 351: two rows, 512 panels
+    # of 2400 -> 8 pieces -> ceil(5*2400/32) = 375 -> 384
+    ((1024, 4096, 400, 64), (1, 128, 1)),
+    ((1024, 4096, 1200, 64), (2, 384, 1)),
+    # 2048 rows: eight rows for wide B from rows of 128 sharing 16 columns on (256 panels of 6560 -> 8
+    # pieces -> 1025 -> 1024), four rows for 64 columns (row >= 256, shared >= 32: 512 panels of 3280 ->
+    # 8 pieces -> 513 -> 544) and for 32 (row >= 384, rows an eighth full)
+    ((2048, 2048, 820, 128), (8, 1024, 1)),
+    ((2048, 2048, 820, 64), (4, 544, 1)),
+    ((2048, 2048, 820, 32), (4, 544, 1)),
+    # ... rows of 400 in 8192 columns share 19 columns: eight rows for wide B (256 panels of 3200 -> 500 ->
+    # 512), single rows for 64 columns (shared < 32; 2048 rows of 400 -> 4 pieces -> 125 -> 128) and for 32
+    # (rows less than an eighth full)
+    ((2048, 8192, 400, 128), (8, 512, 1)),
+    ((2048, 8192, 400, 64), (1, 128, 1)),
+    ((2048, 8192, 400, 32), (1, 128, 1)),
+    # 4096 x 4096 with rows of 204 (95 % pruned): two rows share 10 columns < 16: single rows for wide B
+    ((4096, 4096, 204, 128), (1, 256, 1)),
     # 4096 x 1024 at 50 %, wide B: 8 rows; 512 panels of 4096 -> 8 pieces -> 640
     ((4096, 1024, 512, 128), (8, 640, 1)),
     # narrow B, 384 <= rows of 512 < 768, half full: four rows; 1024 panels of 2048 -> 8 pieces -> 5*2048/32 = 320
