@@ -182,6 +182,23 @@ def measured_traffic(workload, N):
     return None, None
 
 
+def measured_counters(workload, N):
+    """L2 hit rate, VALU busy and vector-L1 busy (per cent) of the product's main kernel from
+    the same committed counter run as measured_traffic: lines `counters_per_launch <workload>
+    <bCols> l2_hit=.. valu_busy=.. l1_busy=.. <source hash>`; passed on under the same
+    condition (taken on the library sources that are in the tree now)."""
+    import glob
+    now = kernel_source_hash()
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 5 and parts[0] == "counters_per_launch" and parts[1] == workload \
+                        and parts[2] == str(N) and parts[-1] == now:
+                    return {k: float(v) for k, v in (x.split("=") for x in parts[3:-1])}
+    return None
+
+
 def tiles_of_64(N, K):
     """True when spmm_execute runs more than 64 columns as tiles of 64: 128 columns of B
     exceed one 4 MiB L2 and 64 columns fit (8192 < K <= 16384)."""
@@ -533,6 +550,44 @@ def run_tune(args):
                       "plan_size_by_sparsity_bcols128": size, "points": pts}))
 
 
+def run_unhinted(args):
+    """What the bCols hint is worth: every sweep matrix as ONE plan made without a hint (the
+    inspector then assumes wide B), executed at 32, 64 and 128 columns, against the three
+    hinted plans the other workloads create per matrix."""
+    import torch
+    import paper_2506_15174_amd as spmm
+    from workloads import generators as gen
+    torch.cuda.set_device(0)
+    cols = (32, 64, 128)
+    pts = []
+    for entry in gen.sweep_entries():
+        csr = gen.sweep_matrix(entry)
+        a = (csr.M, csr.K, csr.row_ptr, csr.col_idx, csr.vals)
+        plain = spmm.plan_create(*a)
+        pi = plain.describe()
+        for N in cols:
+            B = torch.from_numpy(gen.activations_for(csr, N)).cuda()
+            C = torch.empty((csr.M, N), dtype=torch.float32, device="cuda")
+            hinted = spmm.plan_create(*a, n_hint=N)
+            hi = hinted.describe()
+            _time_plan(torch, hinted, B, C, N, reps=3)
+            t_h = _time_plan(torch, hinted, B, C, N)
+            t_p = _time_plan(torch, plain, B, C, N)
+            hinted.destroy()
+            pts.append({"M": csr.M, "K": csr.K, "sparsity": entry["sparsity"], "N": N, "hinted_us": round(t_h, 3),
+                        "unhinted_us": round(t_p, 3), "hinted": [hi["ufi"], hi["ufk"], hi["group_nnz"], hi["k_slices"]],
+                        "unhinted": [pi["ufi"], pi["ufk"], pi["group_nnz"], pi["k_slices"]],
+                        "unhinted_over_hinted": round(t_p / t_h, 3)})
+        plain.destroy()
+    summary = {str(N): {"geomean_unhinted_over_hinted": round(_geomean([p["unhinted_over_hinted"] for p in pts if p["N"] == N]), 3),
+                        "worst": max(p["unhinted_over_hinted"] for p in pts if p["N"] == N)} for N in cols}
+    print(json.dumps({"metric": "time of the plan made without a bCols hint / time of the hinted plan (geomean)",
+                      "value": round(_geomean([p["unhinted_over_hinted"] for p in pts]), 3), "unit": "ratio", "n_gpus": 1,
+                      "higher_is_better": False, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": "48 sweep matrices, one unhinted plan each, executed at bCols 32/64/128"},
+                      "summary": summary, "points": pts}))
+
+
 def kernel_report(torch, csr, plan, info, B, C, N, workload_key, samples=20, plan_kw=None):
     """Roofline block of one launch: algorithmic bytes over the launch's average duration
     (HIP events on the launch stream) against the HBM peak, the rate of wave-wide loads of
@@ -550,7 +605,9 @@ def kernel_report(torch, csr, plan, info, B, C, N, workload_key, samples=20, pla
                 "cache_state": "hot",
                 "avg_launch_us": round(avg_ms * 1e3, 3), "median_launch_us": round(med_ms * 1e3, 3),
                 "launches_per_execute": 1 + (info["n_cross"] > 0) + (info["k_slices"] > 1), "algorithmic_bytes": bmin, "kernel_tflops": round(kernel_tflops, 3),
-                "frac_of_fp32_valu_peak": round(kernel_tflops / FP32_VALU_PEAK_TFLOPS, 5)}
+                "frac_of_fp32_valu_peak": round(kernel_tflops / FP32_VALU_PEAK_TFLOPS, 5),
+                "traffic_gbs": round(traffic / (avg_ms * 1e-3) / 1e9, 2) if traffic else None,
+                "counters_pct": measured_counters(workload_key, N)}
     # On-chip gather: each chunk of ufk enumerated columns costs ufk / S wave-wide loads of B
     # rows (S rows of B per load); the ceiling is the rate the gather microbenchmark
     # reaches on distinct rows of an L2-resident B.
@@ -660,6 +717,8 @@ def run_headline(args):
                          "frac_of_fp32_valu_peak": round(tflops / FP32_VALU_PEAK_TFLOPS, 5),
                          "hot": {k: hot[k] for k in ("achieved", "frac", "avg_launch_us", "median_launch_us",
                                                      "kernel_tflops")}})
+        if roofline.get("traffic"):
+            roofline["traffic_gbs"] = round(roofline["traffic"] / (cold["mean_us"] * 1e-6) / 1e9, 2)
         g = roofline["gather"]
         rate = g["wave_loads_per_launch"] / (cold["mean_us"] * 1e-6) / 1e9
         roofline["gather"] = dict(g, g_wave_loads_per_s=round(rate, 2), frac=round(rate / GATHER_CEILING_GWLS, 4))
@@ -801,7 +860,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="headline",
                     help="headline (default: sweep + stress) | conv | stress | ffn | ffn-all | matrix | sweep | "
-                         "narrow | sparsity | ablation | tune")
+                         "narrow | sparsity | ablation | tune | unhinted")
     ap.add_argument("--shape", default="4096x4096", help="--workload matrix: rows x columns of A")
     ap.add_argument("--sparsity", type=float, default=0.5, help="--workload matrix: pruned share")
     ap.add_argument("--bcols", type=int, default=128, help="--workload matrix: columns of B")
@@ -833,8 +892,8 @@ def main():
         return run_sweep(args, cols=(64, 4), square512=True)
     if args.workload == "ffn-all":
         return run_sweep(args, ffn=True)
-    if args.workload in ("sweep", "ablation", "tune"):
-        return {"sweep": run_sweep, "ablation": run_ablation, "tune": run_tune}[args.workload](args)
+    if args.workload in ("sweep", "ablation", "tune", "unhinted"):
+        return {"sweep": run_sweep, "ablation": run_ablation, "tune": run_tune, "unhinted": run_unhinted}[args.workload](args)
     return run_single(args)
 
 
