@@ -424,14 +424,17 @@ def run_ablation(args):
       +balance    nnz-balanced row groups: heavy rows cut into pieces that meet in LDS
       +enumerate  panels of 2, 4 or 8 rows enumerated by nonzero pattern, height by the
                   schedule rule; still one chunk at a time (pipeline depth 1)
-      +coarsen    the full method: the chunks of B rows of the next D - 1 steps in flight
-                  while one is multiplied (the paper's unroll(k, UFk), Section 3.3.2)"""
+      +coarsen    the chunks of B rows of the next D - 1 steps in flight while one is
+                  multiplied (the paper's unroll(k, UFk), Section 3.3.2)
+      full        the plan the inspector makes by itself: as +coarsen, and cut into column
+                  ranges bound to the XCDs' L2 caches where a tile of B fills or exceeds one
+                  (of these matrices only 8192 x 8192 at 50 to 80 % for 128 columns)"""
     import torch
     import paper_2506_15174_amd as spmm
     from workloads import generators as gen
     torch.cuda.set_device(0)
     cols = (32, 64, 128)
-    rungs = ("rows", "+balance", "+enumerate", "+coarsen")
+    rungs = ("rows", "+balance", "+enumerate", "+coarsen", "full")
     pts = []
     t_start = time.perf_counter()
     for entry in _ladder_matrices(gen):
@@ -441,12 +444,13 @@ def run_ablation(args):
         for N in cols:
             B = torch.from_numpy(gen.activations_for(csr, N)).cuda()
             C = torch.empty((csr.M, N), dtype=torch.float32, device="cuda")
-            plans = {"rows": spmm.plan_create(*a, ufi=1, group_nnz=1 << 30, group_panels=1, depth=1),
-                     "+balance": spmm.plan_create(*a, ufi=1, n_hint=N, depth=1),
-                     "+enumerate": spmm.plan_create(*a, n_hint=N, depth=1),
-                     "+coarsen": spmm.plan_create(*a, n_hint=N)}
+            plans = {"rows": spmm.plan_create(*a, ufi=1, group_nnz=1 << 30, group_panels=1, depth=1, kslices=1),
+                     "+balance": spmm.plan_create(*a, ufi=1, n_hint=N, depth=1, kslices=1),
+                     "+enumerate": spmm.plan_create(*a, n_hint=N, depth=1, kslices=1),
+                     "+coarsen": spmm.plan_create(*a, n_hint=N, kslices=1),
+                     "full": spmm.plan_create(*a, n_hint=N)}
             row = {"M": csr.M, "K": csr.K, "sparsity": entry["sparsity"], "N": N,
-                   "ufi": plans["+coarsen"].describe()["ufi"]}
+                   "ufi": plans["full"].describe()["ufi"], "k_slices": plans["full"].describe()["k_slices"]}
             for r in rungs:
                 us = _time_plan(torch, plans[r], B, C, N)
                 row[r + "_us"] = round(us, 3)
@@ -459,10 +463,10 @@ def run_ablation(args):
         sel = [p for p in pts if p["N"] == N]
         summary[str(N)] = {r: round(_geomean([p[r + "_gflops"] for p in sel]), 1) for r in rungs}
         summary[str(N)]["speedup_full_over_rows"] = round(
-            _geomean([p["rows_us"] / p["+coarsen_us"] for p in sel]), 3)
+            _geomean([p["rows_us"] / p["full_us"] for p in sel]), 3)
         summary[str(N)]["speedup_coarsen_over_enumerate"] = round(
             _geomean([p["+enumerate_us"] / p["+coarsen_us"] for p in sel]), 3)
-    full = [p["+coarsen_gflops"] for p in pts]
+    full = [p["full_gflops"] for p in pts]
     print(json.dumps({"metric": "fp32 CSR SpMM GFLOP/s (2*nnz*bCols), geomean per rung", "value": round(_geomean(full), 2),
                       "unit": "GFLOP/s", "n_gpus": 1, "higher_is_better": True, "dtype": "f32", "data": "synthetic",
                       "config": {"workload": "ablation ladder on 30 sweep matrices (M, K >= 1024) x bCols 32/64/128",
@@ -494,7 +498,7 @@ def run_tune(args):
     import paper_2506_15174_amd as spmm
     from workloads import generators as gen
     torch.cuda.set_device(0)
-    cols = (32, 64, 128)
+    cols = tuple(int(x) for x in args.cols.split(",")) if args.cols else (32, 64, 128)
     pts = []
     t_start = time.perf_counter()
     entries = ([dict(e, heldout=False) for e in _ladder_matrices(gen)] + [dict(e, heldout=False, extra=True) for e in FIT_EXTRA]
@@ -538,13 +542,13 @@ def run_tune(args):
     summary_heldout = loss([p for p in pts if p["heldout"]])
     size = {}
     for sp in sorted({p["sparsity"] for p in pts if not p["heldout"]}):
-        sel = [p for p in pts if p["sparsity"] == sp and p["N"] == 128 and not p["heldout"]]
+        sel = [p for p in pts if p["sparsity"] == sp and p["N"] == max(cols) and not p["heldout"]]
         size[str(sp)] = {"plan_over_csr": round(_geomean([p["plan_bytes_over_csr"] for p in sel]), 3),
                          "plan_over_dense": round(_geomean([p["plan_bytes_over_dense"] for p in sel]), 3)}
     print(json.dumps({"metric": "time of the rule's plan / time of the best forced plan (geomean)",
                       "value": round(_geomean([p["rule_over_best"] for p in pts]), 3), "unit": "ratio", "n_gpus": 1,
                       "higher_is_better": False, "dtype": "f32", "data": "synthetic",
-                      "config": {"workload": "tuning run on 30 sweep matrices (M, K >= 1024), 8 shapes between them and 8 held-out shapes x bCols 32/64/128",
+                      "config": {"workload": "tuning run on 30 sweep matrices (M, K >= 1024), 8 shapes between them and 8 held-out shapes x bCols " + "/".join(map(str, cols)),
                                  "wall_s": round(time.perf_counter() - t_start, 1)},
                       "summary": summary, "summary_heldout": summary_heldout,
                       "plan_size_by_sparsity_bcols128": size, "points": pts}))
@@ -872,6 +876,7 @@ def main():
                     help="single workloads: force the enumerated columns per chunk (8, 16, 32, 64)")
     ap.add_argument("--depth", type=int, default=0,
                     help="single workloads: chunks of B rows in flight per wave (1, 2, 3, 4, 8; 0 = tuned)")
+    ap.add_argument("--cols", default="", help="tune: comma-separated column counts instead of 32,64,128")
     ap.add_argument("--points-file", default="", help="headline: also write the per-point figures to this JSON file")
     ap.add_argument("--no-baselines", action="store_true")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")

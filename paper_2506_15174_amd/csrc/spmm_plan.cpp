@@ -95,6 +95,21 @@ int choose_ufi(int64_t M, int64_t K, int64_t nnz, int32_t n_hint)
         return 1;
     }
     const int64_t shared = K > 0 ? row * row / K : 0;
+    if (n_hint > 0 && n_hint <= 16) {
+        // Chunks of 32 or 64 columns, one lane or a few per row of B: a wave load already covers 16
+        // to 64 enumerated columns, and what a tall panel saves in loads it pays in multiply slots of
+        // absent rows.  Eight rows only where two rows share most of their columns (from 4096 rows
+        // on: shared >= 160 for 9 .. 16 columns of B, 320 for 5 .. 8, 640 for up to 4: 4096 x 4096 at
+        // 80 %, shared 163, 4 columns: 7.5 us with single rows against 12.3 us with eight); for 9 ..
+        // 16 columns also the four and two rows of the rule for 17 .. 32 columns below.
+        const int64_t need = n_hint <= 4 ? 640 : n_hint <= 8 ? 320 : 160;
+        if (M >= 4096 && shared >= need) return 8;
+        if (n_hint > 8) {
+            if (M >= 2048) return row >= 384 && 8 * row >= K ? 4 : 1;
+            if (M >= 1024) return row >= 256 && 3 * row >= K ? 2 : 1;
+        }
+        return 1;
+    }
     if (narrow) {
         if (M >= 4096) return row >= 768 ? 8 : row >= 384 && 8 * row >= K ? 4 : 1;
         if (M >= 2048) return row >= 384 && 8 * row >= K ? 4 : 1;
@@ -163,7 +178,8 @@ int choose_ufk(int64_t K, int32_t n_hint)
 // Nonzero budget G of a row group and the cap GP on the panels one group packs.
 // P panels of mean weight `mean`:
 //   * fewer than 4096 panels: a typical panel is cut into ppt = min(8, ceil(8192 / P))
-//     pieces so that the launch holds about 8192 waves;
+//     pieces so that the launch holds about 8192 waves (4096 waves, from fewer than 2048
+//     panels, for B of at most 16 columns; a quarter as many was no better);
 //   * 4096 panels or more: panels stay whole, and beyond 8192 panels GP =
 //     ceil(P / 8192) of them (at most 16) share a wave.
 // G = ceil(5 mean GP / (4 ppt)), rounded up to a multiple of 32 inside [32, 1024];
@@ -179,7 +195,11 @@ void choose_group_budget(int64_t M, int64_t nnz, int ufi, int32_t n_hint, int32_
 {
     const int64_t P = std::max<int64_t>(1, (M + ufi - 1) / ufi);
     const int64_t mean = (nnz + P - 1) / P;
-    const int64_t ppt = P < 4096 ? std::min<int64_t>(8, (8192 + P - 1) / P) : 1;
+    // B of at most 16 columns: half as many waves of twice the work (a wave's chunk of 32 or 64
+    // columns is little arithmetic against its fixed start-up; 2048 x 4096 at 90 %, 4 columns:
+    // 5.6 us with rows cut in two against 7.4 us cut in four)
+    const int64_t waves = n_hint > 0 && n_hint <= 16 ? 4096 : 8192;
+    const int64_t ppt = P < waves / 2 ? std::min<int64_t>(8, (waves + P - 1) / P) : 1;
     const int64_t GP = std::min<int64_t>(16, std::max<int64_t>(1, (P + 8191) / 8192));
     int64_t g = (5 * mean * GP + 4 * ppt - 1) / (4 * ppt);
     if (ufi == 1 && M >= 1024 && M < 2048 && n_hint > 0 && n_hint <= 64)

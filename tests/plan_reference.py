@@ -92,6 +92,16 @@ def choose_ufi(M, K, nnz, n_hint=0):
         wide_tiles = not narrow and not medium and K * 256 <= 4 << 20
         return 8 if (wide_tiles and M >= 4096 and row >= 1024) else 1
     shared = row * row // K if K else 0      # columns two rows of the mean length have in common
+    if 0 < n_hint <= 16:                      # chunks of 32 or 64 columns
+        need = 640 if n_hint <= 4 else 320 if n_hint <= 8 else 160
+        if M >= 4096 and shared >= need:
+            return 8
+        if n_hint > 8:
+            if M >= 2048:
+                return 4 if (row >= 384 and 8 * row >= K) else 1
+            if M >= 1024:
+                return 2 if (row >= 256 and 3 * row >= K) else 1
+        return 1
     if narrow:
         if M >= 4096:
             return 8 if row >= 768 else 4 if (row >= 384 and 8 * row >= K) else 1
@@ -246,7 +256,8 @@ def choose_group_budget(M, nnz, ufi, n_hint=0):
     """(nonzero budget, panel cap) of a row group for panels of `ufi` rows."""
     P = max(1, -(-M // ufi))
     mean = -(-nnz // P)
-    ppt = min(8, -(-8192 // P)) if P < 4096 else 1
+    waves = 4096 if 0 < n_hint <= 16 else 8192      # B of at most 16 columns: half as many waves
+    ppt = min(8, -(-waves // P)) if P < waves // 2 else 1
     GP = min(16, max(1, -(-P // 8192)))
     g = -(-(5 * mean * GP) // (4 * ppt))
     if ufi == 1 and 1024 <= M < 2048 and 0 < n_hint <= 64:   # single rows of small matrices for narrow B: not cut below 128 entries

@@ -449,6 +449,18 @@ def test_plans_cut_along_k_with_real_data_and_unsorted_columns(torch_gpu, oracle
         check(oracle, shuffled, B, C)
 
 
+@pytest.mark.parametrize("N", [64, 37, 130])
+def test_plans_cut_along_k_on_the_64_bit_addressing_kernels(torch_gpu, oracle, N):
+    """force_wide: the kernels that address B with 64 bits (N = 37 and 130: one column per
+    lane, tiles of 64 columns, so the column ranges' sums are added 64 columns at a time)."""
+    csr = heavy_tail(70, 1200, 301)
+    B = gen.dense_activations(csr.K, N, 302)
+    for ufi in (1, 4):
+        C, plan = gpu_product(torch_gpu, csr, B, guard_rows=1, force_wide=True, kslices=4, ufi=ufi, group_nnz=96)
+        assert plan.describe()["k_slices"] == 4
+        check(oracle, csr, B, C)
+
+
 def test_plan_cut_along_k_in_a_replayed_graph(torch_gpu, oracle):
     """The three launches of a plan cut along K whose heavy panels are also cut across
     workgroups (product, sums of the cut panels, sums of the ranges) replay from a graph."""

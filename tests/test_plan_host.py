@@ -168,6 +168,18 @@ SCHEDULE_CASES = [
     ((2048, 8192, 400, 32), (1, 128, 1)),
     # 4096 x 4096 with rows of 204 (95 % pruned): two rows share 10 columns < 16: single rows for wide B
     ((4096, 4096, 204, 128), (1, 256, 1)),
+    # B of at most 16 columns (chunks of 32 or 64): eight rows only where two rows share 160 / 320 / 640
+    # columns (hints 16 / 8 / 4).  Rows of 819 in 4096 columns share 163: eight rows for 16 columns (512
+    # panels of 6552 -> 8 pieces -> 1024), single rows for 8 and 4 (4096 whole rows of 819 -> 1024)
+    ((4096, 4096, 819, 16), (8, 1024, 1)),
+    ((4096, 4096, 819, 8), (1, 1024, 1)),
+    ((4096, 4096, 2048, 4), (8, 1024, 1)),
+    # ... about 4096 waves instead of 8192: 1024 single rows of 400 are cut in 4 (not 8): ceil(5*400/16) = 125 -> 128
+    ((1024, 4096, 400, 8), (1, 128, 1)),
+    # ... 9 .. 16 columns keep the four- and two-row panels of the rule for 17 .. 32 columns; fewer columns do not
+    # (512 four-row panels of 3280 -> 8 pieces -> 513 -> 544; 2048 whole single rows of 820 -> 1025 -> 1024)
+    ((2048, 2048, 820, 16), (4, 544, 1)),
+    ((2048, 2048, 820, 8), (1, 1024, 1)),
     # 4096 x 1024 at 50 %, wide B: 8 rows; 512 panels of 4096 -> 8 pieces -> 640
     ((4096, 1024, 512, 128), (8, 640, 1)),
     # narrow B, 384 <= rows of 512 < 768, half full: four rows; 1024 panels of 2048 -> 8 pieces -> 5*2048/32 = 320
