@@ -526,7 +526,7 @@ def interpret_plan(items, hdr, stream, wins, B, M, ufi, rowmap=None, K=0, ufk=UF
                 if not int(it[5]) & FLAG_CROSS:
                     C[crow] = total
                     continue
-                # the block parks its sums; whichever block comes last adds the blocks' sums in block order
+                # the block parks its sums; the second launch adds the blocks' sums in block order
                 nparts, xslot0, part = (int(x) for x in it[13:16])
                 parked[(xslot0 + part, r)] = total
                 if part == nparts - 1:

@@ -328,11 +328,11 @@ def test_pipeline_depth_setting_does_not_change_the_result(torch_gpu, oracle, de
 @pytest.mark.parametrize("ufi", [1, 2, 4, 8])
 def test_panels_cut_across_workgroups(torch_gpu, oracle, ufi, N):
     """Dense rows far heavier than the group budget: their panels are cut across several
-    workgroups whose sums meet in the plan's scratch memory (the workgroup that arrives
-    last adds them in workgroup order).  Small integers: bit-exact against the oracle;
-    repeated executes are bit-identical (the arrival counters are back at zero after
-    every launch); N = 700 needs more column tiles than one launch's scratch holds; the
-    same matrix with cross < 0 (every panel inside one workgroup) gives the same C."""
+    workgroups whose sums meet in the plan's scratch memory, and a second launch adds them
+    in workgroup order.  Small integers: bit-exact against the oracle; repeated executes are
+    bit-identical (every launch overwrites what its second step reads, nothing is cleared
+    in between); N = 700 needs more column tiles than one launch's scratch holds; the same
+    matrix with cross < 0 (every panel inside one workgroup) gives the same C."""
     rng = np.random.default_rng(600 + ufi)
     M, K = 61, 2600
     W = np.where(rng.random((M, K)) < 0.04, rng.integers(-8, 9, (M, K)), 0).astype(np.float32)
@@ -359,8 +359,8 @@ def test_panels_cut_across_workgroups(torch_gpu, oracle, ufi, N):
 
 
 def test_panels_cut_across_workgroups_in_a_replayed_graph(torch_gpu, oracle):
-    """The arrival counters of panels cut across workgroups are reset by the kernel itself
-    (no clearing call between launches), so a captured execute replays correctly."""
+    """Both launches of a plan with panels cut across workgroups are plain kernel nodes (no
+    clearing call in between), so a captured execute replays correctly."""
     torch = torch_gpu
     csr = heavy_tail(64, 3000, 195)
     N = 128
