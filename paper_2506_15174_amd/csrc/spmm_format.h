@@ -90,10 +90,11 @@ constexpr int WAVES_PER_WG = 8;
 // A block holds at most WAVES_PER_WG / ufi split panels, so that every
 // (panel, row) sum after the barrier has a wave of its own.
 
-// Wave-slot descriptor: WAVES_PER_WG per block, launch order.
+// Wave-slot descriptor: WAVES_PER_WG per block, launch order.  In a plan cut along K a block
+// holds groups of one column range only and block b of the launch belongs to range b mod k_slices.
 constexpr int ITEM_WORDS = 16;
 enum ItemField {
-    IT_ROW0 = 0,      // first row
+    IT_ROW0 = 0,      // first row of the plan (a plan cut along K: column range * slice_rows + row)
     IT_NROWS = 1,     // rows covered (whole panels; the last may be short)
     IT_CHUNK0 = 2,    // first chunk
     IT_NCHUNKS = 3,   // chunks of the group (0 for an idle slot)
@@ -102,7 +103,7 @@ enum ItemField {
     IT_RED_NSEG = 6,  // after the barrier: pieces to add (0 = this wave adds nothing)
     IT_RED_SLOT0 = 7, // ... wave slot of the first piece
     IT_RED_R = 8,     // ... row of the tile to add
-    IT_RED_ROW = 9,   // ... row of C to write
+    IT_RED_ROW = 9,   // ... row to write: of C, or of the ranges' buffer in a plan cut along K
     IT_WIN0 = 10,     // first window of the group
     IT_NWINS = 11,    // windows of the group (0 for an idle slot)
     IT_WIN_FIRST = 12,// copy of the first window's entry of the window table (saves a dependent load)
@@ -132,7 +133,7 @@ enum CrossField {
     CE_SLOT0 = 0,   // scratch slot of the panel's first block
     CE_NPARTS = 1,  // blocks of the panel
     CE_NROWS = 2,   // rows of the panel
-    CE_ROW0 = 4     // CE_ROW0 + r: row of C that row r of the panel is
+    CE_ROW0 = 4     // CE_ROW0 + r: row of C (of the ranges' buffer in a plan cut along K) that row r of the panel is
 };
 
 }  // namespace spmm_fmt

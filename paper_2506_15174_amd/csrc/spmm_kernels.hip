@@ -16,13 +16,14 @@
 //     when a panel ends (the warp-level reduction of Section 3.3.2).
 //   * The UFI x 4 accumulators of a panel stay in VGPRs across all chunks of the
 //     panel (the paper's register tile, Listing 6).
-//   * A chunk is UFKT = 8 (16, 32, 64 in plans made for narrow B) enumerated columns of one nonzero pattern (or leftovers
-//     of several patterns under the union of their patterns, with zeros where a
-//     column lacks a row).  Its column indices and values are staged through LDS,
-//     a window of the group's stream at a time, with coalesced 16-byte loads (the
-//     scalar data path tops out far below what the stream needs); a slice reads
-//     its own slots back with one broadcast LDS read per row of the pattern.  The one-word chunk header comes
-//     from the same window: its pattern selects, with wave-uniform branches,
+//   * A chunk is UFKT = 8 (16, 32, 64 in plans made for narrow B) enumerated
+//     columns of one nonzero pattern (or leftovers of several patterns under the
+//     union of their patterns, with zeros where a column lacks a row).  Its column
+//     indices and values are staged through LDS, a window of the group's stream at
+//     a time, with coalesced 16-byte loads (the scalar data path tops out far below
+//     what the stream needs); a slice reads its own slots back with one broadcast
+//     LDS read per row of the pattern.  The one-word chunk header comes from the
+//     same window: its pattern selects, with wave-uniform branches,
 //     which of the UFI row blocks run, so no lane ever tests a sparsity condition
 //     (Section 3.2.2: enumerated blocks carry no conditionals).  No scalar load
 //     sits inside the chunk loop, so its LDS waits are counted, not drained.
@@ -33,6 +34,15 @@
 //     they park their partial tiles in LDS, meet at one barrier and one wave per
 //     tile row adds the pieces in piece order (the write-after-write hazard of
 //     Section 3.3.2, solved without atomics and with a fixed summation order).
+//     A panel too heavy even for one workgroup is cut across several: each parks
+//     the sum of its pieces in a scratch slot and spmm_cross_combine_kernel, a
+//     second launch, adds the slots in workgroup order.
+//   * A plan cut along K (a column tile of B larger than one XCD's L2) holds every
+//     row once per column range; workgroup b of the launch works on range
+//     b mod k_slices, so that the XCDs, which receive the workgroups in turn, each
+//     gather from one range of B.  The kernel is the same: it writes the ranges'
+//     partial rows of C to a buffer and spmm_kslice_combine_kernel adds them in
+//     range order.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
