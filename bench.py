@@ -728,23 +728,34 @@ def run_headline(args):
         roofline["gather"] = dict(g, g_wave_loads_per_s=round(rate, 2), frac=round(rate / GATHER_CEILING_GWLS, 4))
     stress_base = {} if args.no_baselines else measure_baselines(torch, np, csr, (Ns,), {Ns: B}).get(str(Ns), {})
 
-    # the timed steps: one pass over every product of the batch, launched back to back
-    st = torch.cuda.current_stream().cuda_stream or None
+    # The timed steps: one pass over every product of the batch.  The products are independent
+    # (each has its own plan, B and C), so they are issued round robin over args.streams HIP
+    # streams of the default priority: a short product then starts while the previous one drains
+    # (most of the batch takes 3 to 10 us per product, close to what a launch costs).  A product
+    # always goes to the same stream, so the executes of one plan never overlap.  The per-product
+    # figures above and the roofline block are single-stream launches of one product at a time.
     calls = [(p, b.data_ptr(), n, c.data_ptr()) for (p, b, c, n, _) in resident]
 
-    def step():
-        for p, pb, n, pc in calls:
-            p.execute_raw(pb, n, pc, st)
+    def timed_steps(n_streams, steps, warmup):
+        pool = [torch.cuda.Stream() for _ in range(n_streams)] if n_streams > 1 else [torch.cuda.current_stream()]
+        handles = [q.cuda_stream or None for q in pool]
+        torch.cuda.synchronize()
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
+        def step():
+            for i, (p, pb, n, pc) in enumerate(calls):
+                p.execute_raw(pb, n, pc, handles[i % len(handles)])
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        return 1e3 * (time.perf_counter() - t0) / steps
+
+    single_ms = timed_steps(1, max(3, args.steps // 4), args.warmup) if args.streams > 1 else None
+    ms_per_step = timed_steps(args.streams, args.steps, args.warmup)
     flops_step = sum(2.0 * z * n for (_, _, _, n, z) in resident)
     value = flops_step / (ms_per_step * 1e-3) / 1e9
 
@@ -754,8 +765,10 @@ def run_headline(args):
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": "sweep: 48 magnitude-pruned matrices x bCols 32/64/128 (configs[4]) + stress "
                                   "16384x16384 @95% Zipf(1.5) rows, 5% empty, bCols 128 (configs[3]); one step = "
-                                  "all 145 products",
+                                  "all 145 products, issued over " + str(args.streams) + " stream(s)",
                       "products_per_step": len(resident), "flops_per_step": flops_step,
+                      "streams": args.streams,
+                      "single_stream_ms_per_step": round(single_ms, 5) if single_ms else None,
                       "sweep_only": {"gflops_from_per_launch_medians": round(sweep_flops / sweep_s / 1e9, 2),
                                      "sum_of_launch_medians_ms": round(sweep_s * 1e3, 4)},
                       "stress": {"M": csr.M, "K": csr.K, "nnz": nnz, "bCols": Ns,
@@ -876,6 +889,8 @@ def main():
                     help="single workloads: force the enumerated columns per chunk (8, 16, 32, 64)")
     ap.add_argument("--depth", type=int, default=0,
                     help="single workloads: chunks of B rows in flight per wave (1, 2, 3, 4, 8; 0 = tuned)")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="headline: HIP streams the independent products of a step are issued over (1 = one after the other)")
     ap.add_argument("--cols", default="", help="tune: comma-separated column counts instead of 32,64,128")
     ap.add_argument("--points-file", default="", help="headline: also write the per-point figures to this JSON file")
     ap.add_argument("--no-baselines", action="store_true")
