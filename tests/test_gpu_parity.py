@@ -673,6 +673,39 @@ def test_random_shapes_settings_and_widths(torch_gpu, oracle, seed):
     plan = spmm.plan_create(M, K, row_ptr, col_idx, vals, ufi=int(rng.choice([0, 1, 2, 4, 8])),
                             group_nnz=int(rng.choice([0, 16, 100, 1000])), sort_rows=int(rng.choice([-1, 0, 1])),
                             n_hint=int(rng.choice([0, 32, 64, 128])))
+    check_random_plan(torch_gpu, oracle, rng, csr, plan, B, N)
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_shapes_settings_and_widths_with_cut_plans(torch_gpu, oracle, seed):
+    """The same with plans cut along K into 2, 4 or 8 column ranges, with and without panels
+    cut across workgroups, for hints of more than 32 columns or none."""
+    rng = np.random.default_rng(4400 + seed)
+    M, K = int(rng.integers(1, 300)), int(rng.integers(8, 1500))
+    mode = seed % 4
+    if mode == 0:
+        lens = rng.integers(0, K + 1, M)
+    elif mode == 1:
+        lens = np.where(rng.random(M) < 0.1, K, rng.integers(0, 6, M))
+    elif mode == 2:
+        lens = rng.integers(0, 4, M)
+    else:
+        lens = np.where(rng.random(M) < 0.2, 0, rng.integers(0, 2 * K, M))       # duplicates
+    row_ptr = np.concatenate(([0], np.cumsum(lens))).astype(np.int32)
+    nnz = int(row_ptr[-1])
+    csr = gen.Csr(M, K, row_ptr, rng.integers(0, K, nnz).astype(np.int32), rng.standard_normal(nnz).astype(np.float32))
+    N = int(rng.choice([1, 3, 4, 7, 17, 32, 33, 64, 70, 100, 128, 129, 190, 260]))
+    B = rng.standard_normal((K, N)).astype(np.float32)
+    ns = int(rng.choice([2, 4, 8]))
+    plan = spmm.plan_create(M, K, csr.row_ptr, csr.col_idx, csr.vals, ufi=int(rng.choice([0, 1, 2, 4, 8])),
+                            group_nnz=int(rng.choice([0, 16, 100, 1000])), sort_rows=int(rng.choice([-1, 0, 1])),
+                            n_hint=int(rng.choice([0, 64, 128])), cross=int(rng.choice([-1, 0, 1])), kslices=ns)
+    assert plan.describe()["k_slices"] == ns
+    check_random_plan(torch_gpu, oracle, rng, csr, plan, B, N)
+
+
+def check_random_plan(torch_gpu, oracle, rng, csr, plan, B, N):
+    M, K = csr.M, csr.K
     shift = int(rng.integers(0, 4))
     flatB = torch_gpu.zeros(K * N + 8, dtype=torch_gpu.float32, device="cuda")
     flatB[shift:shift + K * N] = torch_gpu.from_numpy(B).cuda().reshape(-1)
