@@ -42,6 +42,25 @@ def test_kernel_label_follows_the_launch_table():
     assert "h.K * 512 > ((int64_t)4 << 20) && (int64_t)h.K * 256 <= ((int64_t)4 << 20)" in api
 
 
+def test_counter_figures_are_passed_on_only_for_the_profiled_sources(monkeypatch):
+    """Traffic and counter figures come from the committed counter summaries, which carry
+    the hash of the library sources they were taken on: they are withheld once the sources
+    differ, and a plan cut into column ranges is labelled as such."""
+    now = bench.kernel_source_hash()
+    traffic, prov = bench.measured_traffic("stress", 128)
+    assert prov is not None and prov["file"].startswith("profiles/") and prov["source_hash_now"] == now
+    assert (traffic is not None) == prov["current"] == (prov["source_hash_at_profile"] == now)
+    counters = bench.measured_counters("stress", 128)
+    assert (counters is not None) == prov["current"]
+    if counters:
+        assert set(counters) == {"l2_hit", "valu_busy", "l1_busy"} and all(0 < v <= 100 for v in counters.values())
+    monkeypatch.setattr(bench, "kernel_source_hash", lambda: "0" * 16)
+    traffic, prov = bench.measured_traffic("stress", 128)
+    assert traffic is None and not prov["current"] and prov["withheld_bytes"] > 0
+    assert bench.measured_counters("stress", 128) is None
+    assert bench.kernel_shape(128, 8, 16384, k_slices=4) == "S=2,VW=4,D=2, 4 column ranges"
+
+
 def test_more_than_one_gpu_is_refused_with_a_message():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
                        text=True, timeout=120)
